@@ -1,0 +1,234 @@
+// C ABI, descriptor validation and the chunk scheduler: the share [lo,hi) is cut
+// into k chunks which are enqueued one after another on the caller's stream
+// (op-order), all on the current device (op-assign), every chunk reusing the same
+// workspace (co-shard, Section 2 of the paper).
+#include "../../include/ss_attn.h"
+#include "kparams.h"
+
+#include <cstdio>
+
+namespace {
+
+using ssa::KP;
+
+constexpr size_t ALIGN = 256;
+inline size_t align_up(size_t x) { return (x + ALIGN - 1) / ALIGN * ALIGN; }
+inline size_t esize(int dtype) { return dtype == SS_BF16 ? 2 : 4; }
+
+int validate(const ss_attn_desc* d) {
+  if (!d) return SS_ERR_NULL;
+  if (d->B < 1 || d->H < 1 || d->S < 1 || d->D < 1) return SS_ERR_BAD_SHAPE;
+  if (d->dtype != SS_F32 && d->dtype != SS_BF16) return SS_ERR_UNSUPPORTED;
+  if (d->stride_h < d->D || d->stride_s < d->D || d->stride_b < d->D) return SS_ERR_BAD_SHAPE;
+  if (d->dtype == SS_BF16 && (d->stride_h % 8 || d->stride_s % 8 || d->stride_b % 8 || d->D % 8))
+    return SS_ERR_BAD_SHAPE;
+  if (d->bias_kind < SS_BIAS_NONE || d->bias_kind > SS_BIAS_RELPOS) return SS_ERR_UNSUPPORTED;
+  if (d->bias_kind != SS_BIAS_NONE && d->bias_dtype != SS_F32 && d->bias_dtype != SS_BF16)
+    return SS_ERR_UNSUPPORTED;
+  if (d->bias_kind == SS_BIAS_RELPOS &&
+      (d->win_h < 1 || d->win_w < 1 || (int64_t)d->win_h * d->win_w != d->S))
+    return SS_ERR_BAD_SHAPE;
+  if (d->mask_kind < SS_MASK_NONE || d->mask_kind > SS_MASK_REGION) return SS_ERR_UNSUPPORTED;
+  if (d->mask_kind == SS_MASK_REGION && d->mask_period < 1) return SS_ERR_BAD_SHAPE;
+  if (d->gated != 0 && d->gated != 1) return SS_ERR_BAD_SHAPE;
+  if (d->shard_axis != SS_AXIS_HEAD && d->shard_axis != SS_AXIS_ROW) return SS_ERR_UNSUPPORTED;
+  const int extent = d->shard_axis == SS_AXIS_HEAD ? d->H : d->B;
+  if (d->lo < 0 || d->lo >= d->hi || d->hi > extent) return SS_ERR_BAD_RANGE;
+  if (d->k < 1 || d->k > d->hi - d->lo) return SS_ERR_BAD_K;
+  if (d->flags & ~(uint32_t)SS_FLAG_GENERIC_KERNELS) return SS_ERR_UNSUPPORTED;
+  if (d->D > 256) return SS_ERR_UNSUPPORTED;
+  // grid dimensions y,z carry heads and rows
+  if (d->H > 65535 || d->B > 65535) return SS_ERR_UNSUPPORTED;
+  return SS_OK;
+}
+
+inline void chunk(const ss_attn_desc* d, int c, int* a, int* b) {
+  const int64_t n = d->hi - d->lo;
+  *a = d->lo + (int)((c * n) / d->k);
+  *b = d->lo + (int)(((c + 1) * n) / d->k);
+}
+
+struct WsLayout {
+  size_t lse, delta, dO, dense, total;
+};
+
+WsLayout bwd_layout(const ss_attn_desc* d) {
+  const int64_t n = d->hi - d->lo;
+  const int64_t nmax = (n + d->k - 1) / d->k;  // largest chunk of the balanced split
+  const int64_t Bc = d->shard_axis == SS_AXIS_ROW ? nmax : d->B;
+  const int64_t Hc = d->shard_axis == SS_AXIS_HEAD ? nmax : d->H;
+  WsLayout w{};
+  size_t off = 0;
+  w.lse = off;   off += align_up((size_t)(Bc * Hc * d->S) * 4);
+  w.delta = off; off += align_up((size_t)(Bc * Hc * d->S) * 4);
+  w.dO = off;
+  if (d->gated) off += align_up((size_t)(Bc * d->S * Hc * d->D) * esize(d->dtype));
+  w.dense = off;
+  if (d->bias_kind == SS_BIAS_RELPOS) off += align_up((size_t)d->H * d->S * d->S * 4);
+  w.total = off;
+  return w;
+}
+
+KP base_params(const ss_attn_desc* d) {
+  KP p{};
+  p.sb = d->stride_b; p.ss = d->stride_s; p.sh = d->stride_h;
+  p.B = d->B; p.H = d->H; p.S = d->S; p.D = d->D;
+  p.scale = d->scale;
+  p.bias_kind = d->bias_kind; p.bias_bf16 = d->bias_dtype == SS_BF16;
+  p.mask_kind = d->mask_kind; p.mask_period = d->mask_period > 0 ? d->mask_period : 1;
+  p.win_h = d->win_h; p.win_w = d->win_w; p.gated = d->gated;
+  return p;
+}
+
+inline void set_chunk(KP& p, const ss_attn_desc* d, int c) {
+  int a, b;
+  chunk(d, c, &a, &b);
+  if (d->shard_axis == SS_AXIS_HEAD) { p.b0 = 0; p.b1 = d->B; p.h0 = a; p.h1 = b; }
+  else { p.b0 = a; p.b1 = b; p.h0 = 0; p.h1 = d->H; }
+}
+
+int hip_fail(hipError_t e, const char* what) {
+  fprintf(stderr, "ss_attn: %s: %s\n", what, hipGetErrorString(e));
+  return SS_ERR_HIP;
+}
+#define SS_LAUNCH(expr, what)                         \
+  do {                                                \
+    hipError_t e_ = (expr);                           \
+    if (e_ != hipSuccess) return hip_fail(e_, what);  \
+  } while (0)
+
+}  // namespace
+
+extern "C" {
+
+const char* ss_strerror(int code) {
+  switch (code) {
+    case SS_OK: return "ok";
+    case SS_ERR_NULL: return "a required pointer is NULL";
+    case SS_ERR_BAD_SHAPE: return "bad shape, stride, window or mask period";
+    case SS_ERR_BAD_RANGE: return "bad [lo,hi) for the shard axis";
+    case SS_ERR_BAD_K: return "co-shard factor k must satisfy 1 <= k <= hi-lo";
+    case SS_ERR_UNSUPPORTED: return "unsupported dtype / head size / bias / mask / flags";
+    case SS_ERR_WORKSPACE: return "workspace missing, too small or not 256-byte aligned";
+    case SS_ERR_HIP: return "HIP kernel launch failed";
+    default: return "unknown error code";
+  }
+}
+
+int ss_attn_workspace_bytes(const ss_attn_desc* d, size_t* fwd_bytes, size_t* bwd_bytes) {
+  const int rc = validate(d);
+  if (rc != SS_OK) return rc;
+  if (fwd_bytes) *fwd_bytes = 0;
+  if (bwd_bytes) *bwd_bytes = bwd_layout(d).total;
+  return SS_OK;
+}
+
+int ss_attn_chunk_range(const ss_attn_desc* d, int32_t c, int32_t* lo, int32_t* hi) {
+  const int rc = validate(d);
+  if (rc != SS_OK) return rc;
+  if (!lo || !hi) return SS_ERR_NULL;
+  if (c < 0 || c >= d->k) return SS_ERR_BAD_K;
+  int a, b;
+  chunk(d, c, &a, &b);
+  *lo = a; *hi = b;
+  return SS_OK;
+}
+
+int ss_attn_fwd(const ss_attn_desc* d, const void* Q, const void* K, const void* V, const void* bias,
+                const int32_t* region_ids, const void* G, void* Y, float* lse, void* workspace,
+                size_t workspace_bytes, void* hip_stream) {
+  (void)workspace; (void)workspace_bytes;
+  const int rc = validate(d);
+  if (rc != SS_OK) return rc;
+  if (!Q || !K || !V || !Y) return SS_ERR_NULL;
+  if (d->bias_kind != SS_BIAS_NONE && !bias) return SS_ERR_NULL;
+  if (d->mask_kind == SS_MASK_REGION && !region_ids) return SS_ERR_NULL;
+  if (d->gated && !G) return SS_ERR_NULL;
+  hipStream_t st = (hipStream_t)hip_stream;
+  const bool bf16 = d->dtype == SS_BF16;
+  KP p = base_params(d);
+  p.Q = Q; p.K = K; p.V = V; p.G = G; p.Y = Y; p.bias = bias; p.region = region_ids;
+  p.lse_out = lse; p.lse_sb = (int64_t)d->H * d->S; p.lse_sh = d->S;
+  const bool mfma = !(d->flags & SS_FLAG_GENERIC_KERNELS) && ssa::mfma_supported(p, bf16);
+  for (int c = 0; c < d->k; ++c) {
+    set_chunk(p, d, c);
+    if (mfma) SS_LAUNCH(ssa::launch_mfma_fwd(p, false, st), "forward");
+    else SS_LAUNCH(ssa::launch_generic_fwd(p, bf16, false, st), "forward (generic)");
+  }
+  return SS_OK;
+}
+
+int ss_attn_bwd(const ss_attn_desc* d, const void* Q, const void* K, const void* V, const void* bias,
+                const int32_t* region_ids, const void* G, const void* dY, const float* lse, void* dQ,
+                void* dK, void* dV, float* dBias, void* dG, void* workspace, size_t workspace_bytes,
+                void* hip_stream) {
+  const int rc = validate(d);
+  if (rc != SS_OK) return rc;
+  if (!Q || !K || !V || !dY || !dQ || !dK || !dV) return SS_ERR_NULL;
+  if (d->bias_kind != SS_BIAS_NONE && !bias) return SS_ERR_NULL;
+  if (d->mask_kind == SS_MASK_REGION && !region_ids) return SS_ERR_NULL;
+  if (d->gated && (!G || !dG)) return SS_ERR_NULL;
+  const WsLayout w = bwd_layout(d);
+  if (!workspace || workspace_bytes < w.total || ((uintptr_t)workspace % ALIGN)) return SS_ERR_WORKSPACE;
+  hipStream_t st = (hipStream_t)hip_stream;
+  const bool bf16 = d->dtype == SS_BF16;
+  const size_t es = esize(d->dtype);
+  char* ws = (char*)workspace;
+  const bool want_dbias = d->bias_kind != SS_BIAS_NONE && dBias != nullptr;
+
+  KP p = base_params(d);
+  p.Q = Q; p.K = K; p.V = V; p.G = G; p.dY = dY; p.bias = bias; p.region = region_ids;
+  p.dQ = dQ; p.dK = dK; p.dV = dV; p.dG = dG;
+  const bool mfma = !(d->flags & SS_FLAG_GENERIC_KERNELS) && ssa::mfma_supported(p, bf16);
+  float* dense = nullptr;
+  if (want_dbias) {
+    dense = d->bias_kind == SS_BIAS_DENSE ? dBias : (float*)(ws + w.dense);
+    p.dbias_acc = dense;
+  }
+  for (int c = 0; c < d->k; ++c) {
+    set_chunk(p, d, c);
+    const int64_t Bc = p.b1 - p.b0, Hc = p.h1 - p.h0;
+    (void)Bc;
+    // chunk-local scratch, addressed with whole-operator (b,h): pre-offset the bases
+    const int64_t st_sb = Hc * d->S, st_sh = d->S;
+    const int64_t st_off = (int64_t)p.b0 * st_sb + (int64_t)p.h0 * st_sh;
+    p.delta = (float*)(ws + w.delta) - st_off; p.dl_sb = st_sb; p.dl_sh = st_sh;
+    if (lse) {
+      p.lse = lse; p.lse_out = nullptr; p.lse_sb = (int64_t)d->H * d->S; p.lse_sh = d->S;
+    } else {
+      p.lse_out = (float*)(ws + w.lse) - st_off; p.lse = p.lse_out; p.lse_sb = st_sb; p.lse_sh = st_sh;
+    }
+    if (d->gated) {
+      p.do_sh = d->D; p.do_ss = Hc * d->D; p.do_sb = (int64_t)d->S * p.do_ss;
+      const int64_t off = (int64_t)p.b0 * p.do_sb + (int64_t)p.h0 * p.do_sh;
+      p.dO_out = (void*)(ws + w.dO - off * (int64_t)es);
+      p.dO = p.dO_out;
+    } else {
+      p.dO = dY; p.dO_out = nullptr; p.do_sb = p.sb; p.do_ss = p.ss; p.do_sh = p.sh;
+    }
+    // the first chunk that touches a bias-gradient entry starts its sum: for a HEAD split every
+    // chunk owns its heads; for a ROW split chunk 0 starts and later chunks continue in row order
+    p.dbias_accumulate = (d->shard_axis == SS_AXIS_ROW && c > 0) ? 1 : 0;
+    if (mfma) {
+      SS_LAUNCH(ssa::launch_mfma_fwd(p, true, st), "recompute");
+      SS_LAUNCH(ssa::launch_mfma_dq(p, st), "dQ");
+      SS_LAUNCH(ssa::launch_mfma_dkdv(p, st), "dK/dV");
+      if (want_dbias) SS_LAUNCH(ssa::launch_mfma_dbias(p, st), "dBias");
+    } else {
+      SS_LAUNCH(ssa::launch_generic_fwd(p, bf16, true, st), "recompute (generic)");
+      SS_LAUNCH(ssa::launch_generic_dq(p, bf16, st), "dQ (generic)");
+      SS_LAUNCH(ssa::launch_generic_dkdv(p, bf16, st), "dK/dV (generic)");
+      if (want_dbias) SS_LAUNCH(ssa::launch_generic_dbias(p, bf16, st), "dBias (generic)");
+    }
+    if (want_dbias && d->bias_kind == SS_BIAS_RELPOS &&
+        (d->shard_axis == SS_AXIS_HEAD || c == d->k - 1)) {
+      const int h0 = d->shard_axis == SS_AXIS_HEAD ? p.h0 : 0;
+      const int h1 = d->shard_axis == SS_AXIS_HEAD ? p.h1 : d->H;
+      SS_LAUNCH(ssa::launch_relpos_reduce(dense, dBias, h0, h1, d->S, d->win_h, d->win_w, st),
+                "relative-position table reduce");
+    }
+  }
+  return SS_OK;
+}
+
+}  // extern "C"

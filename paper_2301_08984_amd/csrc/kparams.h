@@ -1,0 +1,53 @@
+// Kernel-side view of one co-shard sub-task (one chunk of the share).
+// Filled by the host scheduler, passed by value to every kernel.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace ssa {
+
+struct KP {
+  // whole-operator activations, element (b,s,h,d) at b*sb + s*ss + h*sh + d
+  const void *Q, *K, *V, *G, *dY;
+  void *Y, *dQ, *dK, *dV, *dG;
+  int64_t sb, ss, sh;
+  // gradient w.r.t. the un-gated output: dY itself, or the chunk's pre-gated copy in
+  // the workspace (pointer pre-offset so that whole-operator (b,h) indices address it)
+  const void* dO;
+  int64_t do_sb, do_ss, do_sh;
+  void* dO_out;  // recompute pass writes here when gated (same indexing as dO)
+  // softmax statistics, (b,h,s) at b*st_sb + h*st_sh + s (pointers pre-offset likewise)
+  float* lse_out;       // forward: optional caller tensor; recompute: workspace
+  const float* lse;     // backward kernels read this
+  int64_t lse_sb, lse_sh;
+  float* delta;         // rowsum(dO*O), workspace
+  int64_t dl_sb, dl_sh;
+  // bias / mask
+  const void* bias;     // dense [H,S,S] or table [H,R]
+  const int32_t* region;
+  float* dbias_acc;     // dense fp32 [H,S,S] accumulator (caller's dBias, or workspace for RELPOS)
+  int dbias_accumulate; // 0: this chunk starts the sum, 1: continue from the stored value
+  // shapes and the chunk
+  int B, H, S, D;
+  int b0, b1, h0, h1;
+  float scale;
+  int bias_kind, bias_bf16, mask_kind, mask_period, win_h, win_w, gated;
+};
+
+// launchers (each returns the hipError_t of the launch)
+hipError_t launch_generic_fwd(const KP& p, bool bf16, bool recompute, hipStream_t st);
+hipError_t launch_generic_dq(const KP& p, bool bf16, hipStream_t st);
+hipError_t launch_generic_dkdv(const KP& p, bool bf16, hipStream_t st);
+hipError_t launch_generic_dbias(const KP& p, bool bf16, hipStream_t st);
+// dTable[h][r] = sum of dense[h][i][j] over idx(i,j)=r, heads [h0,h1), fixed order
+hipError_t launch_relpos_reduce(const float* dense, float* table, int h0, int h1, int S, int win_h,
+                                int win_w, hipStream_t st);
+hipError_t launch_fill_zero(float* p, size_t n, hipStream_t st);
+
+bool mfma_supported(const KP& p, bool bf16);
+hipError_t launch_mfma_fwd(const KP& p, bool recompute, hipStream_t st);
+hipError_t launch_mfma_dq(const KP& p, hipStream_t st);
+hipError_t launch_mfma_dkdv(const KP& p, hipStream_t st);
+hipError_t launch_mfma_dbias(const KP& p, hipStream_t st);
+
+}  // namespace ssa

@@ -1,0 +1,80 @@
+"""Device-side harness: puts one workload's tensors in HBM (torch is used for
+allocation and streams only) and calls the C ABI through `binding`.  No
+attention arithmetic happens here."""
+from __future__ import annotations
+
+import math
+
+import numpy as np
+import torch
+
+from . import binding as ss
+
+_AXIS = {"head": ss.SS_AXIS_HEAD, "row": ss.SS_AXIS_ROW}
+_MASK = {None: ss.SS_MASK_NONE, "causal": ss.SS_MASK_CAUSAL, "region": ss.SS_MASK_REGION}
+_BIAS = {None: ss.SS_BIAS_NONE, "dense": ss.SS_BIAS_DENSE, "relpos": ss.SS_BIAS_RELPOS}
+
+
+class DeviceCase:
+    """One attention operator resident on the GPU plus its output buffers."""
+
+    def __init__(self, inputs: dict, *, dtype: str, bias=None, mask=None, gated=False, win=None,
+                 scale=None, device="cuda:0", fill=float("nan")):
+        if not torch.cuda.is_available():
+            raise RuntimeError("no GPU: the HIP path has no CPU fallback")
+        self.dev = torch.device(device)
+        self.tdtype = torch.bfloat16 if dtype == "bf16" else torch.float32
+        self.dtype = ss.SS_BF16 if dtype == "bf16" else ss.SS_F32
+        up = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(self.dev).to(self.tdtype).contiguous()
+        self.Q, self.K, self.V, self.dY = (up(inputs[n]) for n in ("Q", "K", "V", "dY"))
+        self.B, self.S, self.H, self.D = self.Q.shape
+        self.scale = (1.0 / math.sqrt(self.D)) if scale is None else scale
+        self.bias_kind, self.mask_kind, self.gated, self.win = _BIAS[bias], _MASK[mask], gated, win or (0, 0)
+        self.bias = up(inputs["bias"]) if bias else None
+        self.G = up(inputs["G"]) if gated else None
+        self.region = None
+        self.mask_period = 0
+        if mask == "region":
+            self.region = torch.from_numpy(np.ascontiguousarray(inputs["region_ids"], dtype=np.int32)).to(self.dev)
+            self.mask_period = self.region.shape[0]
+        mk = lambda: torch.full_like(self.Q, fill)
+        self.Y, self.dQ, self.dK, self.dV = mk(), mk(), mk(), mk()
+        self.dG = mk() if gated else None
+        self.lse = torch.full((self.B, self.H, self.S), fill, dtype=torch.float32, device=self.dev)
+        self.dBias = (torch.full(self.bias.shape, fill, dtype=torch.float32, device=self.dev)
+                      if bias else None)
+        self.ws = None
+
+    def desc(self, axis, lo, hi, k, flags=0):
+        return ss.make_desc(self.B, self.H, self.S, self.D, self.dtype, self.scale, _AXIS[axis], lo, hi, k,
+                            bias_kind=self.bias_kind, win=self.win, mask_kind=self.mask_kind,
+                            mask_period=self.mask_period, gated=self.gated, flags=flags)
+
+    def workspace(self, desc):
+        _, need = ss.ss_attn_workspace_bytes(desc)
+        if self.ws is None or self.ws.numel() < need:
+            self.ws = torch.empty(max(need, 256), dtype=torch.uint8, device=self.dev)
+        return need
+
+    def fwd(self, desc, want_lse=True, stream=None):
+        st = torch.cuda.current_stream(self.dev).cuda_stream if stream is None else stream
+        ss.ss_attn_fwd(desc, self.Q, self.K, self.V, self.bias, self.region, self.G, self.Y,
+                       self.lse if want_lse else None, None, 0, st)
+
+    def bwd(self, desc, use_lse=False, stream=None):
+        need = self.workspace(desc)
+        st = torch.cuda.current_stream(self.dev).cuda_stream if stream is None else stream
+        ss.ss_attn_bwd(desc, self.Q, self.K, self.V, self.bias, self.region, self.G, self.dY,
+                       self.lse if use_lse else None, self.dQ, self.dK, self.dV, self.dBias, self.dG,
+                       self.ws, self.ws.numel(), st)
+        return need
+
+    def caller_bytes(self):
+        """Bytes of every tensor the caller holds for forward+backward (without the workspace)."""
+        ts = [self.Q, self.K, self.V, self.dY, self.Y, self.dQ, self.dK, self.dV, self.G, self.dG,
+              self.bias, self.dBias, self.region, self.lse]
+        return sum(t.numel() * t.element_size() for t in ts if t is not None)
+
+    def host(self, name):
+        t = getattr(self, name)
+        return None if t is None else t.detach().float().cpu().numpy().astype(np.float64)
