@@ -1,0 +1,223 @@
+#!/usr/bin/env python3
+"""Benchmark of the co-sharded attention hot path on one MI355X.
+
+One step = ss_attn_fwd + ss_attn_bwd over the whole share of one workload at one
+co-shard factor k (all k chunks, one stream).  Inputs are seeded synthetic
+tensors already resident in HBM.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload gpt3_shard] [--k 2]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_MFMA_BF16 = 2.5e15  # dense bf16 FLOP/s, MI355X
+PEAK_HBM = 8.0e12        # B/s
+# which published roofline bounds the dominant kernel of each workload
+BOUND = {"gpt3_shard": "mfma", "swin_window": "hbm", "af2_msa_row": "hbm", "af2_triangle": "hbm",
+         "tiny_mha": "hbm"}
+# contractions (each 2*D flop per visible score element) a kernel performs
+CONTRACTIONS = {"fwd": 2, "recompute": 2, "dq": 3, "dkdv": 4, "dbias": 2, "table_reduce": 0}
+
+
+def visible_fraction(w):
+    return 0.5 if w["mask"] == "causal" else 1.0
+
+
+def job_flops(w):
+    """fwd+bwd algorithmic flop of the whole share: 14*E*D, half under a causal mask."""
+    E = w["B"] * w["H"] * w["S"] ** 2
+    return 14.0 * E * w["D"] * visible_fraction(w)
+
+
+def kernel_flops(w, name, units, axis_extent):
+    E = w["B"] * w["H"] * w["S"] ** 2 * (units / axis_extent)
+    return 2.0 * CONTRACTIONS[name] * E * w["D"] * visible_fraction(w)
+
+
+def kernel_bytes(w, name, units, axis_extent):
+    """Bytes a kernel must move once per launch: its activation tensors plus bias."""
+    es = 2 if w["dtype"] == "bf16" else 4
+    T = w["B"] * w["H"] * w["S"] * w["D"] * es * (units / axis_extent)
+    g = 1 if w["gated"] else 0
+    nb = 0
+    if w["bias"] == "dense":
+        nb = w["H"] * w["S"] ** 2 * es
+    elif w["bias"] == "relpos":
+        nb = w["H"] * 169 * es
+    stat = w["B"] * w["H"] * w["S"] * 4 * (units / axis_extent)
+    table = {
+        "fwd": (4 + g) * T + nb + stat,
+        "recompute": (4 + g) * T + 2 * g * T + nb + 2 * stat,
+        "dq": 5 * T + nb + 2 * stat,
+        "dkdv": 6 * T + nb + 2 * stat,
+        "dbias": 4 * T + nb + 2 * stat + (w["H"] * w["S"] ** 2 * 4 if w["bias"] else 0),
+        "table_reduce": w["H"] * w["S"] ** 2 * 4,
+    }
+    return table[name]
+
+
+def cpu_baseline(w, budget_s=15.0):
+    """The fp64 oracle, as it stands, on a bounded sample of the same workload."""
+    from oracle import attention as orc
+    from paper_2301_08984_amd.workloads import make_inputs
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+    from parity import oracle_problem
+    axis = orc.AXIS_HEAD if w["axis"] == "head" else orc.AXIS_ROW
+    ext = w["H"] if w["axis"] == "head" else w["B"]
+    rows = None if w["axis"] == "head" else (0, min(ext, 64))
+    small = dict(w)
+    if rows is not None:
+        small["B"] = rows[1]
+    inp = make_inputs(**small, rows=rows)
+    p = oracle_problem(inp, small)
+    dY = inp["dY"].astype(np.float64)
+    avail = small["H"] if w["axis"] == "head" else small["B"]
+
+    def run(n):
+        t0 = time.perf_counter()
+        orc.coshard_forward(p, axis, 0, n, 1)
+        orc.coshard_backward(p, dY, axis, 0, n, 1)
+        return time.perf_counter() - t0
+
+    t1 = run(1)
+    n = int(max(1, min(avail, budget_s / max(t1, 1e-4))))
+    t = run(n) if n > 1 else t1
+    flops = job_flops(w) * n / ext
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([i.get("num_threads", 1) for i in threadpool_info()] + [1])
+    except Exception:
+        threads = 1
+    threads = min(threads, len(os.sched_getaffinity(0)))
+    unit = "heads" if w["axis"] == "head" else "rows"
+    return {"value": flops / t / 1e12, "unit": "TFLOP/s", "cores": threads, "kind": "oracle",
+            "sample": f"{n} of {ext} {unit} of {w['name']} (fwd+bwd, fp64 numpy), {t:.2f} s",
+            "seconds": t}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="gpt3_shard")
+    ap.add_argument("--k", type=int, default=None, help="co-shard factor of the timed steps")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true", help="skip the per-k table and the instrumented pass")
+    a = ap.parse_args()
+    if a.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (no collectives, no sharding across GPUs); "
+              "use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2301_08984_amd import binding as ss
+    from paper_2301_08984_amd.runner import DeviceCase
+    from paper_2301_08984_amd.workloads import WORKLOADS, make_inputs
+
+    w = dict(WORKLOADS[a.workload], name=a.workload)
+    ext = w["H"] if w["axis"] == "head" else w["B"]
+    ks = list(w["k"])
+    k_main = a.k if a.k is not None else (ks[1] if len(ks) > 1 else ks[0])
+    ss.lib()  # fail loudly if the HIP library is missing
+    dc = DeviceCase(make_inputs(**w), dtype=w["dtype"], bias=w["bias"], mask=w["mask"], gated=w["gated"],
+                    win=w.get("win"), fill=0.0)
+    desc = dc.desc(w["axis"], 0, ext, k_main)
+    family = ss.ss_attn_kernel_family(desc)
+    dc.workspace(desc)
+
+    def step(d):
+        dc.fwd(d, want_lse=False)
+        dc.bwd(d)
+
+    for _ in range(a.warmup):
+        step(desc)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(a.steps):
+        step(desc)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms = dt / a.steps * 1e3
+    value = job_flops(w) / (ms * 1e-3) / 1e12
+
+    out = {
+        "metric": "attn fwd+bwd TFLOP/s (1 GPU) + % MFMA peak; peak HBM bytes vs co-shard k",
+        "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": w["dtype"], "data": "synthetic",
+        "config": {"workload": a.workload, "B": w["B"], "H": w["H"], "S": w["S"], "D": w["D"],
+                   "bias": w["bias"], "mask": w["mask"], "gated": w["gated"], "shard_axis": w["axis"],
+                   "k": k_main, "kernels": family},
+        "pct_mfma_peak": 100.0 * value * 1e12 / PEAK_MFMA_BF16,
+    }
+
+    if not a.no_extras:
+        # instrumented pass over the same K steps: HIP events around every kernel launch
+        ss.ss_attn_profile_enable(True)
+        for _ in range(a.steps):
+            step(desc)
+        torch.cuda.synchronize()
+        ss.ss_attn_profile_enable(False)
+        per_kernel = {}
+        for kid, name in enumerate(ss.KERNEL_NAMES):
+            tot, n = ss.ss_attn_profile_read(kid)
+            if n:
+                per_kernel[name] = {"avg_us": tot / n * 1e3, "launches_per_step": n / a.steps,
+                                    "ms_per_step": tot / a.steps}
+        dom = max(per_kernel, key=lambda n: per_kernel[n]["ms_per_step"])
+        units = ext / k_main
+        dur = per_kernel[dom]["avg_us"] * 1e-6
+        if BOUND[a.workload] == "mfma":
+            ach = kernel_flops(w, dom, units, ext) / dur / 1e12
+            roof = {"bound": "mfma", "achieved": ach, "peak": PEAK_MFMA_BF16 / 1e12, "unit": "TFLOP/s",
+                    "frac": ach * 1e12 / PEAK_MFMA_BF16, "traffic": None}
+        else:
+            ach = kernel_bytes(w, dom, units, ext) / dur / 1e9
+            roof = {"bound": "hbm", "achieved": ach, "peak": PEAK_HBM / 1e9, "unit": "GB/s",
+                    "frac": ach * 1e9 / PEAK_HBM, "traffic": None}
+        roof["kernel"] = dom
+        roof["avg_launch_us"] = per_kernel[dom]["avg_us"]
+        out["roofline"] = roof
+        out["kernels"] = per_kernel
+
+        # throughput, workspace and peak HBM bytes for every co-shard factor of the workload
+        table = []
+        caller = dc.caller_bytes()
+        for k in sorted(set(ks) | {k_main}):
+            d = dc.desc(w["axis"], 0, ext, k)
+            _, wsb = ss.ss_attn_workspace_bytes(d)
+            dc.workspace(d)
+            for _ in range(3):
+                step(d)
+            torch.cuda.synchronize()
+            n = max(5, a.steps // 5)
+            t0 = time.perf_counter()
+            for _ in range(n):
+                step(d)
+            torch.cuda.synchronize()
+            t = (time.perf_counter() - t0) / n
+            chunk_units = -(-ext // k)
+            sxs = chunk_units * (w["B"] * w["H"] / ext) * w["S"] ** 2 * 2
+            table.append({"k": k, "ms_per_step": t * 1e3, "tflops": job_flops(w) / t / 1e12,
+                          "workspace_bytes": wsb, "peak_hbm_bytes": caller + wsb,
+                          "unfused_scores_bytes_per_chunk": int(sxs)})
+        out["per_k"] = table
+
+    if not a.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -140,6 +140,24 @@ int ss_attn_bwd(const ss_attn_desc* desc, const void* Q, const void* K, const vo
 /* Static text for an error code (never NULL). */
 const char* ss_strerror(int code);
 
+/* Host-only: which kernel family a descriptor is served by: "mfma_bf16" (bf16
+ * activations, D in {32,64,128}) or "plain_fp32" (everything else, and whenever
+ * SS_FLAG_GENERIC_KERNELS is set).  NULL for an invalid descriptor. */
+const char* ss_attn_kernel_family(const ss_attn_desc* desc);
+
+/* Benchmark instrumentation, not part of the method.  While enabled, every kernel
+ * the scheduler launches is bracketed by two HIP events recorded on the launch
+ * stream (this is the only state the library keeps, and the only time it creates
+ * HIP objects).  ss_attn_profile_read waits for the recorded events, returns the
+ * summed duration in milliseconds and the number of launches of one kernel since
+ * the last read, and resets both.  Not thread-safe. */
+typedef enum {
+  SS_K_FWD = 0, SS_K_RECOMPUTE = 1, SS_K_DQ = 2, SS_K_DKDV = 3, SS_K_DBIAS = 4, SS_K_TABLE_REDUCE = 5,
+  SS_K_COUNT = 6
+} ss_kernel_id;
+int ss_attn_profile_enable(int on);
+int ss_attn_profile_read(int kernel, double* total_ms, int64_t* launches);
+
 #ifdef __cplusplus
 }
 #endif

@@ -21,7 +21,10 @@ SS_OK = 0
 SS_ERR_NULL, SS_ERR_BAD_SHAPE, SS_ERR_BAD_RANGE, SS_ERR_BAD_K = -1, -2, -3, -4
 SS_ERR_UNSUPPORTED, SS_ERR_WORKSPACE, SS_ERR_HIP = -5, -6, -7
 
-EXPORTS = ("ss_attn_workspace_bytes", "ss_attn_chunk_range", "ss_attn_fwd", "ss_attn_bwd", "ss_strerror")
+EXPORTS = ("ss_attn_workspace_bytes", "ss_attn_chunk_range", "ss_attn_fwd", "ss_attn_bwd", "ss_strerror",
+           "ss_attn_kernel_family", "ss_attn_profile_enable", "ss_attn_profile_read")
+SS_K_FWD, SS_K_RECOMPUTE, SS_K_DQ, SS_K_DKDV, SS_K_DBIAS, SS_K_TABLE_REDUCE, SS_K_COUNT = range(7)
+KERNEL_NAMES = ("fwd", "recompute", "dq", "dkdv", "dbias", "table_reduce")
 
 
 class ss_attn_desc(C.Structure):
@@ -64,6 +67,12 @@ def lib():
         L.ss_attn_fwd.restype = C.c_int
         L.ss_attn_bwd.argtypes = [P, V, V, V, V, V, V, V, V, V, V, V, V, V, V, C.c_size_t, V]
         L.ss_attn_bwd.restype = C.c_int
+        L.ss_attn_kernel_family.argtypes = [P]
+        L.ss_attn_kernel_family.restype = C.c_char_p
+        L.ss_attn_profile_enable.argtypes = [C.c_int]
+        L.ss_attn_profile_enable.restype = C.c_int
+        L.ss_attn_profile_read.argtypes = [C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
+        L.ss_attn_profile_read.restype = C.c_int
         L.ss_strerror.argtypes = [C.c_int]
         L.ss_strerror.restype = C.c_char_p
         _lib = L
@@ -124,3 +133,21 @@ def ss_attn_bwd(desc, Q, K, V, bias, region_ids, G, dY, lse, dQ, dK, dV, dBias, 
                            _ptr(workspace), workspace_bytes, stream)
     if rc != SS_OK:
         raise SSAttnError(rc, "ss_attn_bwd")
+
+
+def ss_attn_kernel_family(desc: ss_attn_desc):
+    r = lib().ss_attn_kernel_family(C.byref(desc))
+    return None if r is None else r.decode()
+
+
+def ss_attn_profile_enable(on: bool):
+    lib().ss_attn_profile_enable(1 if on else 0)
+
+
+def ss_attn_profile_read(kernel: int):
+    """-> (total_ms, launches) of one kernel id since the last read."""
+    ms, n = C.c_double(0), C.c_int64(0)
+    rc = lib().ss_attn_profile_read(kernel, C.byref(ms), C.byref(n))
+    if rc != SS_OK:
+        raise SSAttnError(rc, "ss_attn_profile_read")
+    return ms.value, n.value

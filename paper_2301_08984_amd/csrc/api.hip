@@ -6,6 +6,7 @@
 #include "kparams.h"
 
 #include <cstdio>
+#include <vector>
 
 namespace {
 
@@ -91,9 +92,33 @@ int hip_fail(hipError_t e, const char* what) {
   fprintf(stderr, "ss_attn: %s: %s\n", what, hipGetErrorString(e));
   return SS_ERR_HIP;
 }
-#define SS_LAUNCH(expr, what)                         \
+// optional per-kernel timing with HIP events (benchmark instrumentation)
+struct ProfRec { hipEvent_t a, b; int kind; };
+bool g_prof_on = false;
+std::vector<ProfRec> g_prof_pending;
+double g_prof_ms[SS_K_COUNT] = {0};
+int64_t g_prof_n[SS_K_COUNT] = {0};
+
+struct ProfScope {
+  hipStream_t st; int kind; hipEvent_t a = nullptr, b = nullptr; bool on;
+  ProfScope(hipStream_t s, int k) : st(s), kind(k), on(g_prof_on) {
+    if (on) {
+      on = hipEventCreate(&a) == hipSuccess && hipEventCreate(&b) == hipSuccess &&
+           hipEventRecord(a, st) == hipSuccess;
+    }
+  }
+  ~ProfScope() {
+    if (on && hipEventRecord(b, st) == hipSuccess) g_prof_pending.push_back({a, b, kind});
+  }
+};
+
+#define SS_LAUNCH(kind, expr, what)                   \
   do {                                                \
-    hipError_t e_ = (expr);                           \
+    hipError_t e_;                                    \
+    {                                                 \
+      ProfScope ps_(st, kind);                        \
+      e_ = (expr);                                    \
+    }                                                 \
     if (e_ != hipSuccess) return hip_fail(e_, what);  \
   } while (0)
 
@@ -113,6 +138,37 @@ const char* ss_strerror(int code) {
     case SS_ERR_HIP: return "HIP kernel launch failed";
     default: return "unknown error code";
   }
+}
+
+const char* ss_attn_kernel_family(const ss_attn_desc* d) {
+  if (validate(d) != SS_OK) return nullptr;
+  KP p = base_params(d);
+  const bool mfma = !(d->flags & SS_FLAG_GENERIC_KERNELS) && ssa::mfma_supported(p, d->dtype == SS_BF16);
+  return mfma ? "mfma_bf16" : "plain_fp32";
+}
+
+int ss_attn_profile_enable(int on) {
+  g_prof_on = on != 0;
+  return SS_OK;
+}
+
+int ss_attn_profile_read(int kernel, double* total_ms, int64_t* launches) {
+  if (kernel < 0 || kernel >= SS_K_COUNT) return SS_ERR_BAD_RANGE;
+  for (ProfRec& r : g_prof_pending) {
+    float ms = 0.f;
+    if (hipEventSynchronize(r.b) == hipSuccess && hipEventElapsedTime(&ms, r.a, r.b) == hipSuccess) {
+      g_prof_ms[r.kind] += ms;
+      g_prof_n[r.kind] += 1;
+    }
+    (void)hipEventDestroy(r.a);
+    (void)hipEventDestroy(r.b);
+  }
+  g_prof_pending.clear();
+  if (total_ms) *total_ms = g_prof_ms[kernel];
+  if (launches) *launches = g_prof_n[kernel];
+  g_prof_ms[kernel] = 0;
+  g_prof_n[kernel] = 0;
+  return SS_OK;
 }
 
 int ss_attn_workspace_bytes(const ss_attn_desc* d, size_t* fwd_bytes, size_t* bwd_bytes) {
@@ -152,8 +208,8 @@ int ss_attn_fwd(const ss_attn_desc* d, const void* Q, const void* K, const void*
   const bool mfma = !(d->flags & SS_FLAG_GENERIC_KERNELS) && ssa::mfma_supported(p, bf16);
   for (int c = 0; c < d->k; ++c) {
     set_chunk(p, d, c);
-    if (mfma) SS_LAUNCH(ssa::launch_mfma_fwd(p, false, st), "forward");
-    else SS_LAUNCH(ssa::launch_generic_fwd(p, bf16, false, st), "forward (generic)");
+    if (mfma) SS_LAUNCH(SS_K_FWD, ssa::launch_mfma_fwd(p, false, st), "forward");
+    else SS_LAUNCH(SS_K_FWD, ssa::launch_generic_fwd(p, bf16, false, st), "forward (generic)");
   }
   return SS_OK;
 }
@@ -210,21 +266,21 @@ int ss_attn_bwd(const ss_attn_desc* d, const void* Q, const void* K, const void*
     // chunk owns its heads; for a ROW split chunk 0 starts and later chunks continue in row order
     p.dbias_accumulate = (d->shard_axis == SS_AXIS_ROW && c > 0) ? 1 : 0;
     if (mfma) {
-      SS_LAUNCH(ssa::launch_mfma_fwd(p, true, st), "recompute");
-      SS_LAUNCH(ssa::launch_mfma_dq(p, st), "dQ");
-      SS_LAUNCH(ssa::launch_mfma_dkdv(p, st), "dK/dV");
-      if (want_dbias) SS_LAUNCH(ssa::launch_mfma_dbias(p, st), "dBias");
+      SS_LAUNCH(SS_K_RECOMPUTE, ssa::launch_mfma_fwd(p, true, st), "recompute");
+      SS_LAUNCH(SS_K_DQ, ssa::launch_mfma_dq(p, st), "dQ");
+      SS_LAUNCH(SS_K_DKDV, ssa::launch_mfma_dkdv(p, st), "dK/dV");
+      if (want_dbias) SS_LAUNCH(SS_K_DBIAS, ssa::launch_mfma_dbias(p, st), "dBias");
     } else {
-      SS_LAUNCH(ssa::launch_generic_fwd(p, bf16, true, st), "recompute (generic)");
-      SS_LAUNCH(ssa::launch_generic_dq(p, bf16, st), "dQ (generic)");
-      SS_LAUNCH(ssa::launch_generic_dkdv(p, bf16, st), "dK/dV (generic)");
-      if (want_dbias) SS_LAUNCH(ssa::launch_generic_dbias(p, bf16, st), "dBias (generic)");
+      SS_LAUNCH(SS_K_RECOMPUTE, ssa::launch_generic_fwd(p, bf16, true, st), "recompute (generic)");
+      SS_LAUNCH(SS_K_DQ, ssa::launch_generic_dq(p, bf16, st), "dQ (generic)");
+      SS_LAUNCH(SS_K_DKDV, ssa::launch_generic_dkdv(p, bf16, st), "dK/dV (generic)");
+      if (want_dbias) SS_LAUNCH(SS_K_DBIAS, ssa::launch_generic_dbias(p, bf16, st), "dBias (generic)");
     }
     if (want_dbias && d->bias_kind == SS_BIAS_RELPOS &&
         (d->shard_axis == SS_AXIS_HEAD || c == d->k - 1)) {
       const int h0 = d->shard_axis == SS_AXIS_HEAD ? p.h0 : 0;
       const int h1 = d->shard_axis == SS_AXIS_HEAD ? p.h1 : d->H;
-      SS_LAUNCH(ssa::launch_relpos_reduce(dense, dBias, h0, h1, d->S, d->win_h, d->win_w, st),
+      SS_LAUNCH(SS_K_TABLE_REDUCE, ssa::launch_relpos_reduce(dense, dBias, h0, h1, d->S, d->win_h, d->win_w, st),
                 "relative-position table reduce");
     }
   }

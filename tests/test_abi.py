@@ -113,3 +113,22 @@ def test_workspace_shrinks_with_k():
         assert all(a > b for a, b in zip(sizes, sizes[1:])), sizes
         # scratch is proportional to the largest chunk, up to alignment padding
         assert sizes[0] / sizes[-1] > 0.9 * 8 or sizes[-1] <= 4 * 256
+
+
+def test_kernel_family_selection():
+    assert ss.ss_attn_kernel_family(_desc()) == "mfma_bf16"
+    assert ss.ss_attn_kernel_family(_desc(D=128)) == "mfma_bf16"
+    assert ss.ss_attn_kernel_family(_desc(D=48)) == "plain_fp32"
+    assert ss.ss_attn_kernel_family(_desc(dtype=ss.SS_F32)) == "plain_fp32"
+    assert ss.ss_attn_kernel_family(_desc(flags=ss.SS_FLAG_GENERIC_KERNELS)) == "plain_fp32"
+    assert ss.ss_attn_kernel_family(_desc(k=0)) is None
+    # the five workloads: only the fp32 one is served by the plain kernels
+    from paper_2301_08984_amd.workloads import WORKLOADS
+    for name, w in WORKLOADS.items():
+        d = ss.make_desc(w["B"], w["H"], w["S"], w["D"], ss.SS_BF16 if w["dtype"] == "bf16" else ss.SS_F32, 0.1,
+                         ss.SS_AXIS_HEAD if w["axis"] == "head" else ss.SS_AXIS_ROW, 0,
+                         w["H"] if w["axis"] == "head" else w["B"], w["k"][0],
+                         bias_kind={None: 0, "dense": 1, "relpos": 2}[w["bias"]], win=w.get("win", (0, 0)),
+                         mask_kind={None: 0, "causal": 1, "region": 2}[w["mask"]], mask_period=256,
+                         gated=w["gated"])
+        assert ss.ss_attn_kernel_family(d) == ("plain_fp32" if w["dtype"] == "f32" else "mfma_bf16"), name
