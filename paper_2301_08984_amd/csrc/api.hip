@@ -78,6 +78,7 @@ KP base_params(const ss_attn_desc* d) {
   p.bias_kind = d->bias_kind; p.bias_bf16 = d->bias_dtype == SS_BF16;
   p.mask_kind = d->mask_kind; p.mask_period = d->mask_period > 0 ? d->mask_period : 1;
   p.win_h = d->win_h; p.win_w = d->win_w; p.gated = d->gated;
+  p.share_units = (d->hi - d->lo) * (d->shard_axis == SS_AXIS_HEAD ? d->B : d->H);
   return p;
 }
 

@@ -30,6 +30,7 @@ struct KP {
   // shapes and the chunk
   int B, H, S, D;
   int b0, b1, h0, h1;
+  int share_units;  // (row, head) pairs in the whole share [lo,hi): kernel-shape choices use this, never the chunk
   float scale;
   int bias_kind, bias_bf16, mask_kind, mask_period, win_h, win_w, gated;
 };

@@ -25,6 +25,7 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
 
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr float LN2 = 0.6931471805599453f;
@@ -160,109 +161,11 @@ __device__ inline void relpos_setup(const KP& p, int h, int* cidx, float* table,
 
 __device__ inline int key_of(int v, int hl) { return 8 * (v >> 2) + 4 * hl + (v & 3); }
 
-// ---------------------------------------------------------------------------
-// forward, and the backward's recompute pass (RECOMP): one 32-query block per
-// wavefront, NW wavefronts per work-group share the staged K/V tiles
-// ---------------------------------------------------------------------------
-template <int D, int NW, bool RECOMP>
-__global__ __launch_bounds__(NW * 64) void mfma_fwd_kernel(KP p) {
-  constexpr int KS = D / 16, DB = D / 32, LD = D + 8, NT = NW * 64;
-  __shared__ __attribute__((aligned(16))) uint16_t sK[BN * LD];
-  __shared__ __attribute__((aligned(16))) uint16_t sV[BN * LD];
-  __shared__ int s_cidx[MAX_RELPOS_S];
-  __shared__ float s_table[MAX_RELPOS_R];
-  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, r = lane & 31, hl = lane >> 5;
-  const int h = p.h0 + blockIdx.y, b = p.b0 + blockIdx.z;
-  const int qblk = (gridDim.x - 1 - blockIdx.x) * (32 * NW);  // long (late) causal blocks first
-  const int q0 = qblk + 32 * w, q = q0 + r;
-  const int qc = min(q, p.S - 1);
-  const int64_t base = (int64_t)b * p.sb + (int64_t)h * p.sh;
-  const uint16_t* Qb = (const uint16_t*)p.Q + base;
-  const uint16_t* Kb = (const uint16_t*)p.K + base;
-  const uint16_t* Vb = (const uint16_t*)p.V + base;
-  BiasCtx bc;
-  relpos_setup(p, h, s_cidx, s_table, tid, NT, bc);
-  const int32_t* rid = p.mask_kind == 2 ? p.region + (int64_t)(b % p.mask_period) * p.S : nullptr;
-  const int my_rid = rid ? rid[qc] : 0;
-
-  bf16x8 qf[KS];
-#pragma unroll
-  for (int ks = 0; ks < KS; ++ks)
-    qf[ks] = q < p.S ? *(const bf16x8*)(Qb + (int64_t)q * p.ss + 16 * ks + 8 * hl) : zero8();
-  f32x16 oacc[DB];
-#pragma unroll
-  for (int db = 0; db < DB; ++db)
-#pragma unroll
-    for (int v = 0; v < 16; ++v) oacc[db][v] = 0.f;
-  float m = -1e30f, l = 0.f;
-  const float c1 = p.scale * LOG2E;
-
-  int ntiles = (p.S + BN - 1) / BN;
-  if (p.mask_kind == 1) ntiles = min(ntiles, (min(qblk + 32 * NW, p.S) + BN - 1) / BN);
-  for (int kt = 0; kt < ntiles; ++kt) {
-    const int k0 = kt * BN;
-    __syncthreads();
-    stage_tile<D, LD, NT>(sK, Kb, p.ss, k0, p.S, tid);
-    stage_tile<D, LD, NT>(sV, Vb, p.ss, k0, p.S, tid);
-    __syncthreads();
-    if (q0 >= p.S || (p.mask_kind == 1 && k0 > q0 + 31)) continue;  // nothing visible to this wavefront
-    f32x16 sacc[2];
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb) {
-#pragma unroll
-      for (int v = 0; v < 16; ++v) sacc[kb][v] = 0.f;
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks) sacc[kb] = mfma(lds_nat<LD>(sK, 32 * kb + r, ks, hl), qf[ks], sacc[kb]);
-    }
-    float t[2][16];
-    float rmax = -INFINITY;
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb) {
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const int kbase = k0 + 32 * kb + 8 * g + 4 * hl;
-        float bz[4];
-        bias4(p, bc, h, qc, kbase, bz);
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const int key = kbase + e;
-          float x = fmaf(sacc[kb][4 * g + e], c1, bz[e]);
-          bool dead = key >= p.S;
-          if (p.mask_kind == 1) dead = dead || key > q;
-          if (p.mask_kind == 2) dead = dead || rid[min(key, p.S - 1)] != my_rid;
-          x = dead ? -INFINITY : x;
-          t[kb][4 * g + e] = x;
-          rmax = fmaxf(rmax, x);
-        }
-      }
-    }
-    rmax = half_max(rmax);
-    const float mn = fmaxf(m, rmax);
-    const float alpha = fast_exp2(m - mn);
-    m = mn;
-    float lsum = 0.f;
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        t[kb][v] = fast_exp2(t[kb][v] - mn);
-        lsum += t[kb][v];
-      }
-    l = l * alpha + lsum;
-#pragma unroll
-    for (int db = 0; db < DB; ++db)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) oacc[db][v] *= alpha;
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int hb = 0; hb < 2; ++hb) {
-        const bf16x8 pf = pack8(&t[kb][8 * hb]);
-#pragma unroll
-        for (int db = 0; db < DB; ++db)
-          oacc[db] = mfma(lds_tr<LD>(sV, 32 * kb + 16 * hb, 32 * db, lane), pf, oacc[db]);
-      }
-  }
+// forward epilogue: normalise, gate, store Y (and LSE); recompute mode: gate gradient,
+// pre-gated dO copy, Delta = rowsum(dO*O) and LSE into the workspace
+template <int DB, bool RECOMP>
+__device__ inline void fwd_epilogue(const KP& p, f32x16 (&oacc)[DB], float m, float l, int b, int h, int q,
+                                    int hl, int64_t base) {
   if (q >= p.S) return;
   l = half_sum(l);
   const float inv = 1.f / l;
@@ -336,6 +239,408 @@ __global__ __launch_bounds__(NW * 64) void mfma_fwd_kernel(KP p) {
       if (p.lse_out) p.lse_out[(int64_t)b * p.lse_sb + (int64_t)h * p.lse_sh + q] = lse;
     }
   }
+}
+
+// ---------------------------------------------------------------------------
+// forward, and the backward's recompute pass (RECOMP): one 32-query block per
+// wavefront, NW wavefronts per work-group share the staged K/V tiles.  This is the
+// all-features kernel (any bias / mask kind, decided at run time).
+// ---------------------------------------------------------------------------
+template <int D, int NW, bool RECOMP>
+__global__ __launch_bounds__(NW * 64) void mfma_fwd_kernel(KP p) {
+  constexpr int KS = D / 16, DB = D / 32, LD = D + 8, NT = NW * 64;
+  constexpr int CPR = D / 8, CPT = BN * CPR / NT;  // 16-byte chunks per row / per thread per tile
+  __shared__ __attribute__((aligned(16))) uint16_t sK[BN * LD];
+  __shared__ __attribute__((aligned(16))) uint16_t sV[2][BN * LD];
+  __shared__ int s_cidx[MAX_RELPOS_S];
+  __shared__ float s_table[MAX_RELPOS_R];
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, r = lane & 31, hl = lane >> 5;
+  const int h = p.h0 + blockIdx.y, b = p.b0 + blockIdx.z;
+  const int qblk = (gridDim.x - 1 - blockIdx.x) * (32 * NW);  // long (late) causal blocks first
+  const int q0 = qblk + 32 * w, q = q0 + r;
+  const int qc = min(q, p.S - 1);
+  const int64_t base = (int64_t)b * p.sb + (int64_t)h * p.sh;
+  const uint16_t* Qb = (const uint16_t*)p.Q + base;
+  const uint16_t* Kb = (const uint16_t*)p.K + base;
+  const uint16_t* Vb = (const uint16_t*)p.V + base;
+  BiasCtx bc;
+  relpos_setup(p, h, s_cidx, s_table, tid, NT, bc);
+  const int32_t* rid = p.mask_kind == 2 ? p.region + (int64_t)(b % p.mask_period) * p.S : nullptr;
+  const int my_rid = rid ? rid[qc] : 0;
+
+  bf16x8 qf[KS];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks)
+    qf[ks] = q < p.S ? *(const bf16x8*)(Qb + (int64_t)q * p.ss + 16 * ks + 8 * hl) : zero8();
+  f32x16 oacc[DB];
+#pragma unroll
+  for (int db = 0; db < DB; ++db)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) oacc[db][v] = 0.f;
+  float m = -1e30f, l = 0.f;
+  const float c1 = p.scale * LOG2E;
+
+  int ntiles = (p.S + BN - 1) / BN;
+  if (p.mask_kind == 1) ntiles = min(ntiles, (min(qblk + 32 * NW, p.S) + BN - 1) / BN);
+  // tiles that hold at least one key visible to this wavefront
+  int wtiles = ntiles;
+  if (p.mask_kind == 1) wtiles = min(ntiles, (min(q0 + 32, p.S) + BN - 1) / BN);
+  if (q0 >= p.S) wtiles = 0;
+  const bool has_bias = p.bias_kind != 0;
+
+  // software pipeline: tile kt+2 travels global->registers while tile kt+1 sits in LDS and its
+  // scores are produced by the matrix cores, and tile kt goes through softmax and the PV product
+  u32x4 pk[CPT], pv[CPT];
+  auto gload = [&](int kt) {
+#pragma unroll
+    for (int c = 0; c < CPT; ++c) {
+      const int idx = tid + c * NT, row = kt * BN + idx / CPR, col = (idx % CPR) * 8;
+      pk[c] = u32x4{0, 0, 0, 0};
+      pv[c] = u32x4{0, 0, 0, 0};
+      if (row < p.S) {
+        pk[c] = *(const u32x4*)(Kb + (int64_t)row * p.ss + col);
+        pv[c] = *(const u32x4*)(Vb + (int64_t)row * p.ss + col);
+      }
+    }
+  };
+  auto lstore = [&](uint16_t* dV) {
+#pragma unroll
+    for (int c = 0; c < CPT; ++c) {
+      const int idx = tid + c * NT, row = idx / CPR, col = (idx % CPR) * 8;
+      *(u32x4*)(sK + row * LD + col) = pk[c];
+      *(u32x4*)(dV + row * LD + col) = pv[c];
+    }
+  };
+  auto scores = [&](f32x16 (&sa)[2]) {
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+#pragma unroll
+      for (int v = 0; v < 16; ++v) sa[kb][v] = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) sa[kb] = mfma(lds_nat<LD>(sK, 32 * kb + r, ks, hl), qf[ks], sa[kb]);
+    }
+  };
+
+  gload(0);
+  lstore(sV[0]);
+  if (ntiles > 1) gload(1);
+  __syncthreads();
+  f32x16 scur[2], snext[2];
+  if (wtiles > 0) scores(scur);
+  __syncthreads();
+  for (int kt = 0; kt < ntiles; ++kt) {
+    const int k0 = kt * BN;
+    if (kt + 1 < ntiles) lstore(sV[(kt + 1) & 1]);
+    if (kt + 2 < ntiles) gload(kt + 2);
+    __syncthreads();
+    if (kt < wtiles) {
+      if (kt + 1 < wtiles) scores(snext);
+      // does this tile need per-element masking?  (tail keys, the causal diagonal, region ids)
+      const bool edge = (k0 + BN > p.S) || (p.mask_kind == 1 && k0 + BN - 1 > q0) || p.mask_kind == 2;
+      float rmax = -INFINITY;
+      if (has_bias || edge) {
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            const int kbase = k0 + 32 * kb + 8 * g + 4 * hl;
+            float bz[4];
+            bias4(p, bc, h, qc, kbase, bz);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              const int key = kbase + e;
+              float x = fmaf(scur[kb][4 * g + e], c1, bz[e]);
+              if (edge) {
+                bool dead = key >= p.S;
+                if (p.mask_kind == 1) dead = dead || key > q;
+                if (p.mask_kind == 2) dead = dead || rid[min(key, p.S - 1)] != my_rid;
+                x = dead ? -INFINITY : x;
+              }
+              scur[kb][4 * g + e] = x;
+              rmax = fmaxf(rmax, x);
+            }
+          }
+      } else {
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) rmax = fmaxf(rmax, scur[kb][v]);
+        rmax *= c1;
+      }
+      rmax = half_max(rmax);
+      // the running maximum is only raised when it is exceeded by more than 2^8: probabilities
+      // then stay below 2^8 in bf16/fp32 range and the O rescale is skipped on most tiles
+      if (__builtin_amdgcn_ballot_w64(rmax > m + 8.f) != 0) {
+        const float mn = fmaxf(m, rmax);
+        const float alpha = fast_exp2(m - mn);
+        m = mn;
+        l *= alpha;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) oacc[db][v] *= alpha;
+      }
+      float lsum = 0.f;
+      if (has_bias || edge) {
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            scur[kb][v] = fast_exp2(scur[kb][v] - m);
+            lsum += scur[kb][v];
+          }
+      } else {
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            scur[kb][v] = fast_exp2(fmaf(scur[kb][v], c1, -m));
+            lsum += scur[kb][v];
+          }
+      }
+      l += lsum;
+      const uint16_t* tv = sV[kt & 1];
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int hb = 0; hb < 2; ++hb) {
+          float tmp[8];
+#pragma unroll
+          for (int e = 0; e < 8; ++e) tmp[e] = scur[kb][8 * hb + e];
+          const bf16x8 pf = pack8(tmp);
+#pragma unroll
+          for (int db = 0; db < DB; ++db)
+            oacc[db] = mfma(lds_tr<LD>(tv, 32 * kb + 16 * hb, 32 * db, lane), pf, oacc[db]);
+        }
+      scur[0] = snext[0];
+      scur[1] = snext[1];
+    }
+    __syncthreads();
+  }
+  fwd_epilogue<DB, RECOMP>(p, oacc, m, l, b, h, q, hl, base);
+}
+
+// ---------------------------------------------------------------------------
+// forward / recompute, specialised at compile time on the presence of a dense bf16
+// bias and of the causal mask.  The inner loop is straight-line code: loads are
+// clamped instead of guarded, and tiles that need no per-element masking (all keys
+// below the causal diagonal and inside S) take a path without compares.
+//
+// NG = 2 doubles the work-group to eight wavefronts: group g takes the key tiles
+// kt = g, g+2, ... with its own LDS tiles and its own (O, m, l); the two partial
+// softmax results are merged through LDS at the end.  Two wavefronts then share
+// every SIMD, so one's softmax arithmetic overlaps the other's matrix products,
+// and the serial chain of key tiles per wavefront is half as long.  It is chosen
+// from the size of the whole share, never from the chunk, so results do not
+// depend on k.
+// ---------------------------------------------------------------------------
+template <int D, bool BIAS, bool CAUSAL, bool RECOMP, int NG>
+__global__ __launch_bounds__(256 * NG) __attribute__((amdgpu_waves_per_eu(2, 2))) void fwd_fast_kernel(KP p) {
+  constexpr int KS = D / 16, DB = D / 32, NT = 256;
+  constexpr int LDK = D + 8, LDV = D + 16;  // row pads chosen for conflict-free b128 / transpose reads
+  constexpr int CPR = D / 8, CPT = BN * CPR / NT;
+  constexpr int TILE_ELEMS = BN * LDK + BN * LDV;
+  constexpr int MERGE_ELEMS = NG > 1 ? 256 * (16 * DB + 2) * 2 : 0;  // in uint16 units
+  constexpr int LDS_ELEMS = NG * TILE_ELEMS > MERGE_ELEMS ? NG * TILE_ELEMS : MERGE_ELEMS;
+  __shared__ __attribute__((aligned(16))) uint16_t smem[LDS_ELEMS];
+  const int tid = threadIdx.x & 255, grp = threadIdx.x >> 8;
+  const int lane = tid & 63, w = tid >> 6, r = lane & 31, hl = lane >> 5;
+  uint16_t* sK = smem + grp * TILE_ELEMS;
+  uint16_t* sV = sK + BN * LDK;
+  const int h = p.h0 + blockIdx.y, b = p.b0 + blockIdx.z;
+  const int qblk = (gridDim.x - 1 - blockIdx.x) * 128;  // long (late) causal blocks first
+  const int q0 = qblk + 32 * w, q = q0 + r;
+  const int qc = min(q, p.S - 1);
+  const int64_t base = (int64_t)b * p.sb + (int64_t)h * p.sh;
+  const uint16_t* Qb = (const uint16_t*)p.Q + base;
+  const uint16_t* Kb = (const uint16_t*)p.K + base;
+  const uint16_t* Vb = (const uint16_t*)p.V + base;
+  const uint16_t* bias_row = BIAS ? (const uint16_t*)p.bias + ((int64_t)h * p.S + qc) * p.S : nullptr;
+
+  bf16x8 qf[KS];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) qf[ks] = *(const bf16x8*)(Qb + (int64_t)qc * p.ss + 16 * ks + 8 * hl);
+  f32x16 oacc[DB];
+#pragma unroll
+  for (int db = 0; db < DB; ++db)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) oacc[db][v] = 0.f;
+  float m = -1e30f, l = 0.f;
+  const float c1 = p.scale * LOG2E;
+
+  int ntiles = (p.S + BN - 1) / BN;
+  if (CAUSAL) ntiles = min(ntiles, (min(qblk + 128, p.S) + BN - 1) / BN);
+  int wtiles = ntiles;  // tiles holding at least one key visible to this wavefront
+  if (CAUSAL) wtiles = min(ntiles, (min(q0 + 32, p.S) + BN - 1) / BN);
+  if (q0 >= p.S) wtiles = 0;
+
+  u32x4 pk[CPT], pv[CPT];
+  auto gload = [&](int kt) {
+#pragma unroll
+    for (int c = 0; c < CPT; ++c) {
+      const int idx = tid + c * NT, row = min(kt * BN + idx / CPR, p.S - 1), col = (idx % CPR) * 8;
+      pk[c] = *(const u32x4*)(Kb + (int64_t)row * p.ss + col);
+      pv[c] = *(const u32x4*)(Vb + (int64_t)row * p.ss + col);
+    }
+  };
+  if (grp < ntiles) gload(grp);
+  const int nit = (ntiles + NG - 1) / NG;
+  for (int it = 0; it < nit; ++it) {
+    const int kt = it * NG + grp;
+    const int k0 = kt * BN;
+    __syncthreads();
+    if (kt < ntiles) {
+#pragma unroll
+      for (int c = 0; c < CPT; ++c) {
+        const int idx = tid + c * NT, row = idx / CPR, col = (idx % CPR) * 8;
+        *(u32x4*)(sK + row * LDK + col) = pk[c];
+        *(u32x4*)(sV + row * LDV + col) = pv[c];
+      }
+      if (kt + NG < ntiles) gload(kt + NG);
+    }
+    __syncthreads();
+    if (kt >= wtiles) continue;
+    uint2 bz[8];
+    if (BIAS) {
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+          bz[4 * kb + g] = *(const uint2*)(bias_row + min(k0 + 32 * kb + 8 * g + 4 * hl, p.S - 4));
+    }
+    f32x16 sa[2];
+    {
+      // operand reads run ahead of the matrix cores; the two score blocks alternate so that
+      // consecutive MFMAs never wait on each other's accumulator
+      bf16x8 fa[KS], fb[KS];
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        fa[ks] = lds_nat<LDK>(sK, r, ks, hl);
+        fb[ks] = lds_nat<LDK>(sK, 32 + r, ks, hl);
+      }
+#pragma unroll
+      for (int v = 0; v < 16; ++v) { sa[0][v] = 0.f; sa[1][v] = 0.f; }
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        sa[0] = mfma(fa[ks], qf[ks], sa[0]);
+        sa[1] = mfma(fb[ks], qf[ks], sa[1]);
+      }
+      __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+#pragma unroll
+      for (int j = 0; j < 2 * KS - 4; ++j) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      }
+      __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+    }
+    const bool edge = (k0 + BN > p.S) || (CAUSAL && k0 + BN - 1 > q0);
+    if (BIAS) {
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const uint2 u = bz[4 * kb + g];
+          sa[kb][4 * g + 0] = fmaf(sa[kb][4 * g + 0], c1, __uint_as_float(u.x << 16) * LOG2E);
+          sa[kb][4 * g + 1] = fmaf(sa[kb][4 * g + 1], c1, __uint_as_float(u.x & 0xffff0000u) * LOG2E);
+          sa[kb][4 * g + 2] = fmaf(sa[kb][4 * g + 2], c1, __uint_as_float(u.y << 16) * LOG2E);
+          sa[kb][4 * g + 3] = fmaf(sa[kb][4 * g + 3], c1, __uint_as_float(u.y & 0xffff0000u) * LOG2E);
+        }
+    }
+    if (edge) {
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int key = k0 + 32 * kb + key_of(v, hl);
+          const bool dead = key >= p.S || (CAUSAL && key > q);
+          sa[kb][v] = dead ? -INFINITY : sa[kb][v];
+        }
+    }
+    float rmax = -INFINITY;
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) rmax = fmaxf(rmax, sa[kb][v]);
+    if (!BIAS) rmax *= c1;  // scale > 0 on this path
+    rmax = half_max(rmax);
+    // the running maximum is raised only when exceeded by more than 2^8, so the O rescale is
+    // skipped on most tiles; probabilities stay below 2^8, harmless in fp32/bf16 range
+    if (__builtin_amdgcn_ballot_w64(rmax > m + 8.f) != 0) {
+      const float mn = fmaxf(m, rmax);
+      const float alpha = fast_exp2(m - mn);
+      m = mn;
+      l *= alpha;
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) oacc[db][v] *= alpha;
+    }
+    float lsum = 0.f;
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        sa[kb][v] = BIAS ? fast_exp2(sa[kb][v] - m) : fast_exp2(fmaf(sa[kb][v], c1, -m));
+        lsum += sa[kb][v];
+      }
+    l += lsum;
+    {
+      bf16x8 pf[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        float tmp[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) tmp[e] = sa[j >> 1][8 * (j & 1) + e];
+        pf[j] = pack8(tmp);
+      }
+      // V^T fragments of step j+1 are fetched while step j multiplies
+      bf16x8 vf[2][DB];
+#pragma unroll
+      for (int db = 0; db < DB; ++db) vf[0][db] = lds_tr<LDV>(sV, 0, 32 * db, lane);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        if (j + 1 < 4) {
+#pragma unroll
+          for (int db = 0; db < DB; ++db) vf[(j + 1) & 1][db] = lds_tr<LDV>(sV, 16 * (j + 1), 32 * db, lane);
+        }
+#pragma unroll
+        for (int db = 0; db < DB; ++db) oacc[db] = mfma(vf[j & 1][db], pf[j], oacc[db]);
+      }
+      __builtin_amdgcn_sched_group_barrier(0x100, 2 * DB, 1);
+#pragma unroll
+      for (int j = 0; j < 3 * DB; ++j) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 1);
+        __builtin_amdgcn_sched_group_barrier(0x100, 2, 1);
+      }
+      __builtin_amdgcn_sched_group_barrier(0x008, DB, 1);
+    }
+  }
+  if (NG > 1) {
+    // merge the two groups' partial softmax results; group 1 hands (O, m, l) to group 0
+    float* mb = (float*)smem + (size_t)tid * (16 * DB + 2);
+    __syncthreads();
+    if (grp == 1) {
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) mb[16 * db + v] = oacc[db][v];
+      mb[16 * DB] = m;
+      mb[16 * DB + 1] = l;
+    }
+    __syncthreads();
+    if (grp == 1) return;
+    const float m1 = mb[16 * DB], l1 = mb[16 * DB + 1];
+    const float mn = fmaxf(m, m1);
+    const float a0 = fast_exp2(m - mn), a1 = fast_exp2(m1 - mn);
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) oacc[db][v] = oacc[db][v] * a0 + mb[16 * db + v] * a1;
+    l = l * a0 + l1 * a1;
+    m = mn;
+  }
+  if (q >= p.S) return;
+  fwd_epilogue<DB, RECOMP>(p, oacc, m, l, b, h, q, hl, base);
 }
 
 // ---------------------------------------------------------------------------
@@ -547,6 +852,339 @@ __global__ __launch_bounds__(NW * 64) void mfma_dkdv_kernel(KP p) {
 }
 
 // ---------------------------------------------------------------------------
+// dQ, specialised like the forward (dense bf16 bias / causal at compile time, NG key-tile
+// groups).  Q and dO fragments stay in registers; per 32-key block the scores and dP come
+// from the matrix cores, dS from the vector ALUs, and dQ^T += K^T dS^T reads the same K
+// tile transposed.
+// ---------------------------------------------------------------------------
+template <int D, bool BIAS, bool CAUSAL, int NG>
+__global__ __launch_bounds__(256 * NG) __attribute__((amdgpu_waves_per_eu(2, 2))) void dq_fast_kernel(KP p) {
+  constexpr int KS = D / 16, DB = D / 32, NT = 256;
+  constexpr int LDK = D + 16, LDV = D + 8;
+  constexpr int CPR = D / 8, CPT = BN * CPR / NT;
+  constexpr int TILE_ELEMS = BN * LDK + BN * LDV;
+  constexpr int MERGE_ELEMS = NG > 1 ? 256 * (16 * DB) * 2 : 0;
+  constexpr int LDS_ELEMS = NG * TILE_ELEMS > MERGE_ELEMS ? NG * TILE_ELEMS : MERGE_ELEMS;
+  __shared__ __attribute__((aligned(16))) uint16_t smem[LDS_ELEMS];
+  const int tid = threadIdx.x & 255, grp = threadIdx.x >> 8;
+  const int lane = tid & 63, w = tid >> 6, r = lane & 31, hl = lane >> 5;
+  uint16_t* sK = smem + grp * TILE_ELEMS;
+  uint16_t* sV = sK + BN * LDK;
+  const int h = p.h0 + blockIdx.y, b = p.b0 + blockIdx.z;
+  const int qblk = (gridDim.x - 1 - blockIdx.x) * 128;
+  const int q0 = qblk + 32 * w, q = q0 + r;
+  const int qc = min(q, p.S - 1);
+  const int64_t base = (int64_t)b * p.sb + (int64_t)h * p.sh;
+  const uint16_t* Qb = (const uint16_t*)p.Q + base;
+  const uint16_t* Kb = (const uint16_t*)p.K + base;
+  const uint16_t* Vb = (const uint16_t*)p.V + base;
+  const uint16_t* dOb = (const uint16_t*)p.dO + (int64_t)b * p.do_sb + (int64_t)h * p.do_sh;
+  const uint16_t* bias_row = BIAS ? (const uint16_t*)p.bias + ((int64_t)h * p.S + qc) * p.S : nullptr;
+
+  bf16x8 qf[KS], gf[KS];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) {
+    qf[ks] = *(const bf16x8*)(Qb + (int64_t)qc * p.ss + 16 * ks + 8 * hl);
+    gf[ks] = *(const bf16x8*)(dOb + (int64_t)qc * p.do_ss + 16 * ks + 8 * hl);
+  }
+  const float lse2 = p.lse[(int64_t)b * p.lse_sb + (int64_t)h * p.lse_sh + qc] * LOG2E;
+  const float delta = p.delta[(int64_t)b * p.dl_sb + (int64_t)h * p.dl_sh + qc];
+  f32x16 acc[DB];
+#pragma unroll
+  for (int db = 0; db < DB; ++db)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[db][v] = 0.f;
+  const float c1 = p.scale * LOG2E;
+
+  int ntiles = (p.S + BN - 1) / BN;
+  if (CAUSAL) ntiles = min(ntiles, (min(qblk + 128, p.S) + BN - 1) / BN);
+  int wtiles = ntiles;
+  if (CAUSAL) wtiles = min(ntiles, (min(q0 + 32, p.S) + BN - 1) / BN);
+  if (q0 >= p.S) wtiles = 0;
+
+  u32x4 pk[CPT], pv[CPT];
+  auto gload = [&](int kt) {
+#pragma unroll
+    for (int c = 0; c < CPT; ++c) {
+      const int idx = tid + c * NT, row = min(kt * BN + idx / CPR, p.S - 1), col = (idx % CPR) * 8;
+      pk[c] = *(const u32x4*)(Kb + (int64_t)row * p.ss + col);
+      pv[c] = *(const u32x4*)(Vb + (int64_t)row * p.ss + col);
+    }
+  };
+  if (grp < ntiles) gload(grp);
+  const int nit = (ntiles + NG - 1) / NG;
+  for (int it = 0; it < nit; ++it) {
+    const int kt = it * NG + grp;
+    const int k0 = kt * BN;
+    __syncthreads();
+    if (kt < ntiles) {
+#pragma unroll
+      for (int c = 0; c < CPT; ++c) {
+        const int idx = tid + c * NT, row = idx / CPR, col = (idx % CPR) * 8;
+        *(u32x4*)(sK + row * LDK + col) = pk[c];
+        *(u32x4*)(sV + row * LDV + col) = pv[c];
+      }
+      if (kt + NG < ntiles) gload(kt + NG);
+    }
+    __syncthreads();
+    if (kt >= wtiles) continue;
+    const bool edge = (k0 + BN > p.S) || (CAUSAL && k0 + BN - 1 > q0);
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+      uint2 bz[4];
+      if (BIAS) {
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+          bz[g] = *(const uint2*)(bias_row + min(k0 + 32 * kb + 8 * g + 4 * hl, p.S - 4));
+      }
+      f32x16 sa, pa;
+      {
+        bf16x8 fk[KS], fv[KS];
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+          fk[ks] = lds_nat<LDK>(sK, 32 * kb + r, ks, hl);
+          fv[ks] = lds_nat<LDV>(sV, 32 * kb + r, ks, hl);
+        }
+#pragma unroll
+        for (int v = 0; v < 16; ++v) { sa[v] = 0.f; pa[v] = 0.f; }
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+          sa = mfma(fk[ks], qf[ks], sa);
+          pa = mfma(fv[ks], gf[ks], pa);
+        }
+      }
+      float ds[16];
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        float bl[4] = {0.f, 0.f, 0.f, 0.f};
+        if (BIAS) {
+          bl[0] = __uint_as_float(bz[g].x << 16) * LOG2E; bl[1] = __uint_as_float(bz[g].x & 0xffff0000u) * LOG2E;
+          bl[2] = __uint_as_float(bz[g].y << 16) * LOG2E; bl[3] = __uint_as_float(bz[g].y & 0xffff0000u) * LOG2E;
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          float pe = fast_exp2(fmaf(sa[4 * g + e], c1, bl[e] - lse2));
+          if (edge) {
+            const int key = k0 + 32 * kb + 8 * g + 4 * hl + e;
+            const bool dead = key >= p.S || (CAUSAL && key > q);
+            pe = dead ? 0.f : pe;
+          }
+          ds[4 * g + e] = pe * (pa[4 * g + e] - delta);
+        }
+      }
+#pragma unroll
+      for (int hb = 0; hb < 2; ++hb) {
+        const bf16x8 df = pack8(&ds[8 * hb]);
+        bf16x8 kt_[DB];
+#pragma unroll
+        for (int db = 0; db < DB; ++db) kt_[db] = lds_tr<LDK>(sK, 32 * kb + 16 * hb, 32 * db, lane);
+#pragma unroll
+        for (int db = 0; db < DB; ++db) acc[db] = mfma(kt_[db], df, acc[db]);
+      }
+    }
+  }
+  if (NG > 1) {
+    float* mb = (float*)smem + (size_t)tid * (16 * DB);
+    __syncthreads();
+    if (grp == 1) {
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) mb[16 * db + v] = acc[db][v];
+    }
+    __syncthreads();
+    if (grp == 1) return;
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[db][v] += mb[16 * db + v];
+  }
+  if (q >= p.S) return;
+  uint16_t* out = (uint16_t*)p.dQ + base + (int64_t)q * p.ss;
+#pragma unroll
+  for (int db = 0; db < DB; ++db)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const int d0 = 32 * db + 8 * g + 4 * hl;
+      uint2 o;
+      o.x = (uint32_t)f2bf(acc[db][4 * g] * p.scale) | ((uint32_t)f2bf(acc[db][4 * g + 1] * p.scale) << 16);
+      o.y = (uint32_t)f2bf(acc[db][4 * g + 2] * p.scale) | ((uint32_t)f2bf(acc[db][4 * g + 3] * p.scale) << 16);
+      *(uint2*)(out + d0) = o;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// dK, dV without bias (optionally causal), one wavefront per SIMD.  Each wavefront
+// keeps a 32-key block of K and V and both gradient accumulators in registers and
+// walks the queries in 32-row sub-blocks with a software pipeline: while the vector
+// ALUs turn the scores of sub-block j into P and dS, the matrix cores already
+// produce the scores of sub-block j+1 and consume P/dS of sub-block j-1.
+// Q / dO tiles (64 rows) are double-buffered in LDS, one barrier per tile; the next
+// tile travels global -> registers meanwhile.
+// ---------------------------------------------------------------------------
+template <int D, bool CAUSAL>
+__global__ __launch_bounds__(256) void dkdv_fast_kernel(KP p) {
+  constexpr int KS = D / 16, DB = D / 32, LD = D + 16, NT = 256;
+  constexpr int CPR = D / 8, CPT = BN * CPR / NT;
+  __shared__ __attribute__((aligned(16))) uint16_t sQ[2][BN * LD];
+  __shared__ __attribute__((aligned(16))) uint16_t sG[2][BN * LD];
+  __shared__ __attribute__((aligned(16))) float sL[2][BN];
+  __shared__ __attribute__((aligned(16))) float sD[2][BN];
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, r = lane & 31, hl = lane >> 5;
+  const int h = p.h0 + blockIdx.y, b = p.b0 + blockIdx.z;
+  const int kblk = blockIdx.x * 128;  // early key blocks see the most queries under a causal mask
+  const int k0 = kblk + 32 * w, key = k0 + r;
+  const int kc = min(key, p.S - 1);
+  const int64_t base = (int64_t)b * p.sb + (int64_t)h * p.sh;
+  const uint16_t* Qb = (const uint16_t*)p.Q + base;
+  const uint16_t* Kb = (const uint16_t*)p.K + base;
+  const uint16_t* Vb = (const uint16_t*)p.V + base;
+  const uint16_t* dOb = (const uint16_t*)p.dO + (int64_t)b * p.do_sb + (int64_t)h * p.do_sh;
+  const float* lse_b = p.lse + (int64_t)b * p.lse_sb + (int64_t)h * p.lse_sh;
+  const float* dl_b = p.delta + (int64_t)b * p.dl_sb + (int64_t)h * p.dl_sh;
+
+  bf16x8 kf[KS], vf[KS];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) {
+    kf[ks] = *(const bf16x8*)(Kb + (int64_t)kc * p.ss + 16 * ks + 8 * hl);
+    vf[ks] = *(const bf16x8*)(Vb + (int64_t)kc * p.ss + 16 * ks + 8 * hl);
+  }
+  f32x16 dk[DB], dv[DB];
+#pragma unroll
+  for (int db = 0; db < DB; ++db)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) { dk[db][v] = 0.f; dv[db][v] = 0.f; }
+  const float c1 = p.scale * LOG2E;
+  const int ntiles = (p.S + BN - 1) / BN;
+  const int first = CAUSAL ? kblk / BN : 0;  // queries before the block's first key see none of it
+
+  u32x4 pq[CPT], pg[CPT];
+  float pstat = 0.f;
+  auto gload = [&](int qt) {
+#pragma unroll
+    for (int c = 0; c < CPT; ++c) {
+      const int idx = tid + c * NT, row = min(qt * BN + idx / CPR, p.S - 1), col = (idx % CPR) * 8;
+      pq[c] = *(const u32x4*)(Qb + (int64_t)row * p.ss + col);
+      pg[c] = *(const u32x4*)(dOb + (int64_t)row * p.do_ss + col);
+    }
+    if (tid < 2 * BN) {
+      const int i = min(qt * BN + (tid & (BN - 1)), p.S - 1);
+      pstat = tid < BN ? lse_b[i] * LOG2E : dl_b[i];
+    }
+  };
+  auto lstore = [&](int buf) {
+#pragma unroll
+    for (int c = 0; c < CPT; ++c) {
+      const int idx = tid + c * NT, row = idx / CPR, col = (idx % CPR) * 8;
+      *(u32x4*)(&sQ[buf][row * LD + col]) = pq[c];
+      *(u32x4*)(&sG[buf][row * LD + col]) = pg[c];
+    }
+    if (tid < BN) sL[buf][tid] = pstat;
+    else if (tid < 2 * BN) sD[buf][tid - BN] = pstat;
+  };
+  // scores and dP of one 32-query sub-block
+  auto stage_a = [&](const uint16_t* tq, const uint16_t* tg, int sub, f32x16& sa, f32x16& pa) {
+    bf16x8 fq[KS], fg[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      fq[ks] = lds_nat<LD>(tq, 32 * sub + r, ks, hl);
+      fg[ks] = lds_nat<LD>(tg, 32 * sub + r, ks, hl);
+    }
+#pragma unroll
+    for (int v = 0; v < 16; ++v) { sa[v] = 0.f; pa[v] = 0.f; }
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      sa = mfma(fq[ks], kf[ks], sa);
+      pa = mfma(fg[ks], vf[ks], pa);
+    }
+  };
+  // P and dS of one sub-block, as packed bf16 operands
+  auto stage_v = [&](const float* tl, const float* td, int i0, int sub, const f32x16& sa, const f32x16& pa,
+                     bf16x8 (&pf)[2], bf16x8 (&df)[2], bool edge) {
+    float pr[16], ds[16];
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const f32x4 l4 = *(const f32x4*)(tl + 32 * sub + 8 * g + 4 * hl);
+      const f32x4 d4 = *(const f32x4*)(td + 32 * sub + 8 * g + 4 * hl);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        float pe = fast_exp2(fmaf(sa[4 * g + e], c1, -l4[e]));
+        if (edge) {
+          const int i = i0 + 32 * sub + 8 * g + 4 * hl + e;
+          const bool dead = i >= p.S || key >= p.S || (CAUSAL && key > i);
+          pe = dead ? 0.f : pe;
+        }
+        pr[4 * g + e] = pe;
+        ds[4 * g + e] = pe * (pa[4 * g + e] - d4[e]);
+      }
+    }
+    pf[0] = pack8(&pr[0]); pf[1] = pack8(&pr[8]);
+    df[0] = pack8(&ds[0]); df[1] = pack8(&ds[8]);
+  };
+  // dV += dO^T P, dK += Q^T dS for one sub-block
+  auto stage_b = [&](const uint16_t* tq, const uint16_t* tg, int sub, const bf16x8 (&pf)[2], const bf16x8 (&df)[2]) {
+#pragma unroll
+    for (int hb = 0; hb < 2; ++hb) {
+      bf16x8 tg_[DB], tq_[DB];
+#pragma unroll
+      for (int db = 0; db < DB; ++db) {
+        tg_[db] = lds_tr<LD>(tg, 32 * sub + 16 * hb, 32 * db, lane);
+        tq_[db] = lds_tr<LD>(tq, 32 * sub + 16 * hb, 32 * db, lane);
+      }
+#pragma unroll
+      for (int db = 0; db < DB; ++db) {
+        dv[db] = mfma(tg_[db], pf[hb], dv[db]);
+        dk[db] = mfma(tq_[db], df[hb], dk[db]);
+      }
+    }
+  };
+
+  if (first < ntiles) {
+    gload(first);
+    lstore(first & 1);
+    if (first + 1 < ntiles) gload(first + 1);
+  }
+  for (int qt = first; qt < ntiles; ++qt) {
+    const int i0 = qt * BN;
+    __syncthreads();
+    if (qt + 1 < ntiles) lstore((qt + 1) & 1);
+    if (qt + 2 < ntiles) gload(qt + 2);
+    if (k0 >= p.S || (CAUSAL && i0 + BN - 1 < k0)) continue;  // no visible pair for this wavefront
+    const uint16_t* tq = sQ[qt & 1];
+    const uint16_t* tg = sG[qt & 1];
+    const float* tl = sL[qt & 1];
+    const float* td = sD[qt & 1];
+    const bool edge = (i0 + BN > p.S) || (k0 + 32 > p.S) || (CAUSAL && i0 < k0 + 31);
+    f32x16 sa0, pa0, sa1, pa1;
+    bf16x8 pf0[2], df0[2], pf1[2], df1[2];
+    stage_a(tq, tg, 0, sa0, pa0);
+    // sub-block 1 scores on the matrix cores while sub-block 0 goes through the vector ALUs
+    stage_a(tq, tg, 1, sa1, pa1);
+    stage_v(tl, td, i0, 0, sa0, pa0, pf0, df0, edge);
+    // sub-block 0 gradients on the matrix cores while sub-block 1 goes through the vector ALUs
+    stage_b(tq, tg, 0, pf0, df0);
+    stage_v(tl, td, i0, 1, sa1, pa1, pf1, df1, edge);
+    stage_b(tq, tg, 1, pf1, df1);
+  }
+  if (key >= p.S) return;
+  uint16_t* oK = (uint16_t*)p.dK + base + (int64_t)key * p.ss;
+  uint16_t* oV = (uint16_t*)p.dV + base + (int64_t)key * p.ss;
+#pragma unroll
+  for (int db = 0; db < DB; ++db)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const int d0 = 32 * db + 8 * g + 4 * hl;
+      uint2 a, c;
+      a.x = (uint32_t)f2bf(dk[db][4 * g] * p.scale) | ((uint32_t)f2bf(dk[db][4 * g + 1] * p.scale) << 16);
+      a.y = (uint32_t)f2bf(dk[db][4 * g + 2] * p.scale) | ((uint32_t)f2bf(dk[db][4 * g + 3] * p.scale) << 16);
+      c.x = (uint32_t)f2bf(dv[db][4 * g]) | ((uint32_t)f2bf(dv[db][4 * g + 1]) << 16);
+      c.y = (uint32_t)f2bf(dv[db][4 * g + 2]) | ((uint32_t)f2bf(dv[db][4 * g + 3]) << 16);
+      *(uint2*)(oK + d0) = a;
+      *(uint2*)(oV + d0) = c;
+    }
+}
+
+// ---------------------------------------------------------------------------
 // bias gradient (dense accumulator): each wavefront owns one 32x32 block of
 // (query, key) pairs of one head and walks the chunk's rows b in order, adding
 // dS to fp32 registers; a later chunk continues from the stored value, so the
@@ -622,9 +1260,44 @@ __global__ __launch_bounds__(256) void mfma_dbias_kernel(KP p) {
   }
 }
 
+// the specialised kernels serve: no bias or a dense bf16 bias with S % 4 == 0; no mask or the
+// causal mask; a positive scale; more than one 64-key tile's worth of rows
+inline bool fast_ok(const KP& p) {
+  if (p.S <= 64 || !(p.scale > 0.f) || p.mask_kind == 2 || p.bias_kind == 2) return false;
+  if (p.bias_kind == 1 && (!p.bias_bf16 || (p.S & 3))) return false;
+  return true;
+}
+
+// eight-wavefront work-groups (two key-tile groups) when the whole share offers fewer
+// work-groups than two per compute unit and there are enough key tiles to split
+inline bool use_two_groups(const KP& p) {
+  const int64_t wgs = (int64_t)((p.S + 127) / 128) * p.share_units;
+  return wgs < 512 && p.S >= 512;
+}
+
+template <int D, bool RECOMP, int NG>
+void fwd_fast_launch(const KP& p, dim3 g, hipStream_t st) {
+  const bool bias = p.bias_kind == 1, causal = p.mask_kind == 1;
+  if (bias && causal) fwd_fast_kernel<D, true, true, RECOMP, NG><<<g, 256 * NG, 0, st>>>(p);
+  else if (bias) fwd_fast_kernel<D, true, false, RECOMP, NG><<<g, 256 * NG, 0, st>>>(p);
+  else if (causal) fwd_fast_kernel<D, false, true, RECOMP, NG><<<g, 256 * NG, 0, st>>>(p);
+  else fwd_fast_kernel<D, false, false, RECOMP, NG><<<g, 256 * NG, 0, st>>>(p);
+}
+
 template <int D>
 hipError_t fwd_d(const KP& p, bool recompute, hipStream_t st) {
   const int Hc = p.h1 - p.h0, Bc = p.b1 - p.b0;
+  if (fast_ok(p)) {
+    dim3 g((p.S + 127) / 128, Hc, Bc);
+    if (use_two_groups(p)) {
+      if (recompute) fwd_fast_launch<D, true, 2>(p, g, st);
+      else fwd_fast_launch<D, false, 2>(p, g, st);
+    } else {
+      if (recompute) fwd_fast_launch<D, true, 1>(p, g, st);
+      else fwd_fast_launch<D, false, 1>(p, g, st);
+    }
+    return hipGetLastError();
+  }
   if (p.S <= 64) {
     dim3 g((p.S + 63) / 64, Hc, Bc);
     if (recompute) mfma_fwd_kernel<D, 2, true><<<g, 128, 0, st>>>(p);
@@ -636,9 +1309,24 @@ hipError_t fwd_d(const KP& p, bool recompute, hipStream_t st) {
   }
   return hipGetLastError();
 }
+template <int D, int NG>
+void dq_fast_launch(const KP& p, dim3 g, hipStream_t st) {
+  const bool bias = p.bias_kind == 1, causal = p.mask_kind == 1;
+  if (bias && causal) dq_fast_kernel<D, true, true, NG><<<g, 256 * NG, 0, st>>>(p);
+  else if (bias) dq_fast_kernel<D, true, false, NG><<<g, 256 * NG, 0, st>>>(p);
+  else if (causal) dq_fast_kernel<D, false, true, NG><<<g, 256 * NG, 0, st>>>(p);
+  else dq_fast_kernel<D, false, false, NG><<<g, 256 * NG, 0, st>>>(p);
+}
+
 template <int D>
 hipError_t dq_d(const KP& p, hipStream_t st) {
   const int Hc = p.h1 - p.h0, Bc = p.b1 - p.b0;
+  if (fast_ok(p)) {
+    dim3 g((p.S + 127) / 128, Hc, Bc);
+    if (use_two_groups(p)) dq_fast_launch<D, 2>(p, g, st);
+    else dq_fast_launch<D, 1>(p, g, st);
+    return hipGetLastError();
+  }
   if (p.S <= 64) mfma_dq_kernel<D, 2><<<dim3((p.S + 63) / 64, Hc, Bc), 128, 0, st>>>(p);
   else mfma_dq_kernel<D, 4><<<dim3((p.S + 127) / 128, Hc, Bc), 256, 0, st>>>(p);
   return hipGetLastError();
@@ -646,6 +1334,12 @@ hipError_t dq_d(const KP& p, hipStream_t st) {
 template <int D>
 hipError_t dkdv_d(const KP& p, hipStream_t st) {
   const int Hc = p.h1 - p.h0, Bc = p.b1 - p.b0;
+  if (fast_ok(p) && p.bias_kind == 0) {
+    dim3 g((p.S + 127) / 128, Hc, Bc);
+    if (p.mask_kind == 1) dkdv_fast_kernel<D, true><<<g, 256, 0, st>>>(p);
+    else dkdv_fast_kernel<D, false><<<g, 256, 0, st>>>(p);
+    return hipGetLastError();
+  }
   if (p.S <= 64) mfma_dkdv_kernel<D, 2><<<dim3((p.S + 63) / 64, Hc, Bc), 128, 0, st>>>(p);
   else mfma_dkdv_kernel<D, 4><<<dim3((p.S + 127) / 128, Hc, Bc), 256, 0, st>>>(p);
   return hipGetLastError();
