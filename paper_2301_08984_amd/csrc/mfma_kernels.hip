@@ -18,6 +18,8 @@
 // row-major LDS tile with ds_read_b64_tr_b16 (transpose read) in the same row order.
 #include "kparams.h"
 
+#include <type_traits>
+
 namespace ssa {
 namespace {
 
@@ -1100,7 +1102,8 @@ __global__ __launch_bounds__(256) void dkdv_fast_kernel(KP p) {
   };
   // P and dS of one sub-block, as packed bf16 operands
   auto stage_v = [&](const float* tl, const float* td, int i0, int sub, const f32x16& sa, const f32x16& pa,
-                     bf16x8 (&pf)[2], bf16x8 (&df)[2], bool edge) {
+                     bf16x8 (&pf)[2], bf16x8 (&df)[2], auto edge_tag) {
+    constexpr bool edge = decltype(edge_tag)::value;
     float pr[16], ds[16];
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
@@ -1155,16 +1158,47 @@ __global__ __launch_bounds__(256) void dkdv_fast_kernel(KP p) {
     const float* tl = sL[qt & 1];
     const float* td = sD[qt & 1];
     const bool edge = (i0 + BN > p.S) || (k0 + 32 > p.S) || (CAUSAL && i0 < k0 + 31);
-    f32x16 sa0, pa0, sa1, pa1;
-    bf16x8 pf0[2], df0[2], pf1[2], df1[2];
-    stage_a(tq, tg, 0, sa0, pa0);
-    // sub-block 1 scores on the matrix cores while sub-block 0 goes through the vector ALUs
-    stage_a(tq, tg, 1, sa1, pa1);
-    stage_v(tl, td, i0, 0, sa0, pa0, pf0, df0, edge);
-    // sub-block 0 gradients on the matrix cores while sub-block 1 goes through the vector ALUs
-    stage_b(tq, tg, 0, pf0, df0);
-    stage_v(tl, td, i0, 1, sa1, pa1, pf1, df1, edge);
-    stage_b(tq, tg, 1, pf1, df1);
+    // one straight-line block per tile: A0 | A1 with V0 | B0 with V1 | B1, where A = scores and dP
+    // on the matrix cores, V = P and dS on the vector ALUs, B = gradient products
+    auto tile = [&](auto edge_tag) {
+      f32x16 sa0, pa0, sa1, pa1;
+      bf16x8 pf0[2], df0[2], pf1[2], df1[2];
+      stage_a(tq, tg, 0, sa0, pa0);
+      stage_a(tq, tg, 1, sa1, pa1);
+      stage_v(tl, td, i0, 0, sa0, pa0, pf0, df0, edge_tag);
+      stage_b(tq, tg, 0, pf0, df0);
+      stage_v(tl, td, i0, 1, sa1, pa1, pf1, df1, edge_tag);
+      stage_b(tq, tg, 1, pf1, df1);
+      // A0
+      __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+      for (int j = 0; j < 2 * KS - 4; ++j) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      }
+      __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+      // A1 with V0
+      __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+      for (int j = 0; j < 2 * KS; ++j) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+        __builtin_amdgcn_sched_group_barrier(0x002, 8, 0);
+      }
+      // B0 with V1
+      __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
+      for (int j = 0; j < 4 * DB; ++j) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+        __builtin_amdgcn_sched_group_barrier(0x002, 8, 0);
+      }
+      // B1
+      __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
+      for (int j = 0; j < 4 * DB; ++j) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+      }
+    };
+    if (edge) tile(std::true_type{});
+    else tile(std::false_type{});
   }
   if (key >= p.S) return;
   uint16_t* oK = (uint16_t*)p.dK + base + (int64_t)key * p.ss;
