@@ -50,10 +50,15 @@ inline void chunk(const ss_attn_desc* d, int c, int* a, int* b) {
 }
 
 struct WsLayout {
-  size_t lse, delta, dO, dense, total;
+  size_t lse, delta, dO, dense, partial, total;
+  int g0, ngroups;  // short-sequence path: first global row group of the share, and how many it spans
 };
 
-WsLayout bwd_layout(const ss_attn_desc* d) {
+constexpr int SMALL_GW = 8;  // rows per bias-gradient group of the short-sequence kernels
+
+enum Family { FAM_PLAIN = 0, FAM_MFMA = 1, FAM_SMALL = 2 };
+
+WsLayout bwd_layout(const ss_attn_desc* d, bool small) {
   const int64_t n = d->hi - d->lo;
   const int64_t nmax = (n + d->k - 1) / d->k;  // largest chunk of the balanced split
   const int64_t Bc = d->shard_axis == SS_AXIS_ROW ? nmax : d->B;
@@ -66,6 +71,12 @@ WsLayout bwd_layout(const ss_attn_desc* d) {
   if (d->gated) off += align_up((size_t)(Bc * d->S * Hc * d->D) * esize(d->dtype));
   w.dense = off;
   if (d->bias_kind == SS_BIAS_RELPOS) off += align_up((size_t)d->H * d->S * d->S * 4);
+  w.partial = off;
+  const int row_lo = d->shard_axis == SS_AXIS_ROW ? d->lo : 0;
+  const int row_hi = d->shard_axis == SS_AXIS_ROW ? d->hi : d->B;
+  w.g0 = row_lo / SMALL_GW;
+  w.ngroups = (row_hi - 1) / SMALL_GW - w.g0 + 1;
+  if (small && d->bias_kind != SS_BIAS_NONE) off += align_up((size_t)w.ngroups * d->H * d->S * d->S * 4);
   w.total = off;
   return w;
 }
@@ -79,7 +90,18 @@ KP base_params(const ss_attn_desc* d) {
   p.mask_kind = d->mask_kind; p.mask_period = d->mask_period > 0 ? d->mask_period : 1;
   p.win_h = d->win_h; p.win_w = d->win_w; p.gated = d->gated;
   p.share_units = (d->hi - d->lo) * (d->shard_axis == SS_AXIS_HEAD ? d->B : d->H);
+  p.share_b0 = d->shard_axis == SS_AXIS_ROW ? d->lo : 0;
+  p.sm_gw = SMALL_GW;
   return p;
+}
+
+Family family_of(const ss_attn_desc* d) {
+  if (d->flags & SS_FLAG_GENERIC_KERNELS) return FAM_PLAIN;
+  const KP p = base_params(d);
+  const bool bf16 = d->dtype == SS_BF16;
+  if (ssa::small_supported(p, bf16)) return FAM_SMALL;
+  if (ssa::mfma_supported(p, bf16)) return FAM_MFMA;
+  return FAM_PLAIN;
 }
 
 inline void set_chunk(KP& p, const ss_attn_desc* d, int c) {
@@ -143,9 +165,11 @@ const char* ss_strerror(int code) {
 
 const char* ss_attn_kernel_family(const ss_attn_desc* d) {
   if (validate(d) != SS_OK) return nullptr;
-  KP p = base_params(d);
-  const bool mfma = !(d->flags & SS_FLAG_GENERIC_KERNELS) && ssa::mfma_supported(p, d->dtype == SS_BF16);
-  return mfma ? "mfma_bf16" : "plain_fp32";
+  switch (family_of(d)) {
+    case FAM_SMALL: return "mfma_bf16_short";
+    case FAM_MFMA: return "mfma_bf16";
+    default: return "plain_fp32";
+  }
 }
 
 int ss_attn_profile_enable(int on) {
@@ -176,7 +200,7 @@ int ss_attn_workspace_bytes(const ss_attn_desc* d, size_t* fwd_bytes, size_t* bw
   const int rc = validate(d);
   if (rc != SS_OK) return rc;
   if (fwd_bytes) *fwd_bytes = 0;
-  if (bwd_bytes) *bwd_bytes = bwd_layout(d).total;
+  if (bwd_bytes) *bwd_bytes = bwd_layout(d, family_of(d) == FAM_SMALL).total;
   return SS_OK;
 }
 
@@ -206,10 +230,11 @@ int ss_attn_fwd(const ss_attn_desc* d, const void* Q, const void* K, const void*
   KP p = base_params(d);
   p.Q = Q; p.K = K; p.V = V; p.G = G; p.Y = Y; p.bias = bias; p.region = region_ids;
   p.lse_out = lse; p.lse_sb = (int64_t)d->H * d->S; p.lse_sh = d->S;
-  const bool mfma = !(d->flags & SS_FLAG_GENERIC_KERNELS) && ssa::mfma_supported(p, bf16);
+  const Family fam = family_of(d);
   for (int c = 0; c < d->k; ++c) {
     set_chunk(p, d, c);
-    if (mfma) SS_LAUNCH(SS_K_FWD, ssa::launch_mfma_fwd(p, false, st), "forward");
+    if (fam == FAM_SMALL) SS_LAUNCH(SS_K_FWD, ssa::launch_small_fwd(p, st), "forward (short)");
+    else if (fam == FAM_MFMA) SS_LAUNCH(SS_K_FWD, ssa::launch_mfma_fwd(p, false, st), "forward");
     else SS_LAUNCH(SS_K_FWD, ssa::launch_generic_fwd(p, bf16, false, st), "forward (generic)");
   }
   return SS_OK;
@@ -225,7 +250,8 @@ int ss_attn_bwd(const ss_attn_desc* d, const void* Q, const void* K, const void*
   if (d->bias_kind != SS_BIAS_NONE && !bias) return SS_ERR_NULL;
   if (d->mask_kind == SS_MASK_REGION && !region_ids) return SS_ERR_NULL;
   if (d->gated && (!G || !dG)) return SS_ERR_NULL;
-  const WsLayout w = bwd_layout(d);
+  const Family fam = family_of(d);
+  const WsLayout w = bwd_layout(d, fam == FAM_SMALL);
   if (!workspace || workspace_bytes < w.total || ((uintptr_t)workspace % ALIGN)) return SS_ERR_WORKSPACE;
   hipStream_t st = (hipStream_t)hip_stream;
   const bool bf16 = d->dtype == SS_BF16;
@@ -236,7 +262,7 @@ int ss_attn_bwd(const ss_attn_desc* d, const void* Q, const void* K, const void*
   KP p = base_params(d);
   p.Q = Q; p.K = K; p.V = V; p.G = G; p.dY = dY; p.bias = bias; p.region = region_ids;
   p.dQ = dQ; p.dK = dK; p.dV = dV; p.dG = dG;
-  const bool mfma = !(d->flags & SS_FLAG_GENERIC_KERNELS) && ssa::mfma_supported(p, bf16);
+  const bool mfma = fam == FAM_MFMA;
   float* dense = nullptr;
   if (want_dbias) {
     dense = d->bias_kind == SS_BIAS_DENSE ? dBias : (float*)(ws + w.dense);
@@ -266,6 +292,25 @@ int ss_attn_bwd(const ss_attn_desc* d, const void* Q, const void* K, const void*
     // the first chunk that touches a bias-gradient entry starts its sum: for a HEAD split every
     // chunk owns its heads; for a ROW split chunk 0 starts and later chunks continue in row order
     p.dbias_accumulate = (d->shard_axis == SS_AXIS_ROW && c > 0) ? 1 : 0;
+    if (fam == FAM_SMALL) {
+      // one fused kernel per chunk; group partial sums of the bias gradient live in the workspace
+      // across chunks and are reduced once the last chunk that touches them is enqueued
+      p.sm_partial = want_dbias ? (float*)(ws + w.partial) : nullptr;
+      p.sm_g0 = w.g0;
+      SS_LAUNCH(SS_K_DKDV, ssa::launch_small_bwd(p, st), "backward (short)");
+      if (want_dbias && (d->shard_axis == SS_AXIS_HEAD || c == d->k - 1)) {
+        const int h0 = d->shard_axis == SS_AXIS_HEAD ? p.h0 : 0;
+        const int h1 = d->shard_axis == SS_AXIS_HEAD ? p.h1 : d->H;
+        SS_LAUNCH(SS_K_DBIAS,
+                  ssa::launch_small_group_reduce(p.sm_partial, dense, w.ngroups, d->H, h0, h1, d->S, st),
+                  "bias gradient group reduce");
+        if (d->bias_kind == SS_BIAS_RELPOS)
+          SS_LAUNCH(SS_K_TABLE_REDUCE,
+                    ssa::launch_relpos_reduce(dense, dBias, h0, h1, d->S, d->win_h, d->win_w, st),
+                    "relative-position table reduce");
+      }
+      continue;
+    }
     if (mfma) {
       SS_LAUNCH(SS_K_RECOMPUTE, ssa::launch_mfma_fwd(p, true, st), "recompute");
       SS_LAUNCH(SS_K_DQ, ssa::launch_mfma_dq(p, st), "dQ");

@@ -30,6 +30,11 @@ struct KP {
   // shapes and the chunk
   int B, H, S, D;
   int b0, b1, h0, h1;
+  // short-sequence path: bias-gradient partial sums per group of sm_gw consecutive global rows,
+  // [group - sm_g0][H][S*S] fp32 in the workspace (nullptr: bias gradient not wanted)
+  float* sm_partial;
+  int sm_gw, sm_g0;
+  int share_b0;     // first row of the whole share
   int share_units;  // (row, head) pairs in the whole share [lo,hi): kernel-shape choices use this, never the chunk
   float scale;
   int bias_kind, bias_bf16, mask_kind, mask_period, win_h, win_w, gated;
@@ -44,6 +49,13 @@ hipError_t launch_generic_dbias(const KP& p, bool bf16, hipStream_t st);
 hipError_t launch_relpos_reduce(const float* dense, float* table, int h0, int h1, int S, int win_h,
                                 int win_w, hipStream_t st);
 hipError_t launch_fill_zero(float* p, size_t n, hipStream_t st);
+
+bool small_supported(const KP& p, bool bf16);
+hipError_t launch_small_fwd(const KP& p, hipStream_t st);
+hipError_t launch_small_bwd(const KP& p, hipStream_t st);
+// sums the group partials into dense[h][i][j] for heads [h0,h1); overwrites part of `partial`
+hipError_t launch_small_group_reduce(float* partial, float* dense, int ngroups, int H, int h0, int h1, int S,
+                                     hipStream_t st);
 
 bool mfma_supported(const KP& p, bool bf16);
 hipError_t launch_mfma_fwd(const KP& p, bool recompute, hipStream_t st);

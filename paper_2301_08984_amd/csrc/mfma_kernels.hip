@@ -16,75 +16,12 @@
 // An accumulator block is reused as the B operand of the next product with its
 // registers 8t..8t+7 as the eight k-slots; the matching A operand is read from a
 // row-major LDS tile with ds_read_b64_tr_b16 (transpose read) in the same row order.
-#include "kparams.h"
+#include "mfma_common.h"
 
 #include <type_traits>
 
 namespace ssa {
 namespace {
-
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(16))) float f32x16;
-typedef __attribute__((ext_vector_type(4))) short s16x4;
-typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
-typedef __attribute__((ext_vector_type(4))) float f32x4;
-
-constexpr float LOG2E = 1.4426950408889634f;
-constexpr float LN2 = 0.6931471805599453f;
-constexpr int BN = 64;            // rows of a staged LDS tile
-constexpr int MAX_RELPOS_S = 256;
-constexpr int MAX_RELPOS_R = 1024;
-
-__device__ inline float bf2f(uint16_t u) { return __uint_as_float(((uint32_t)u) << 16); }
-__device__ inline uint16_t f2bf(float f) {
-  uint32_t u = __float_as_uint(f);
-  u += 0x7fffu + ((u >> 16) & 1u);
-  return (uint16_t)(u >> 16);
-}
-__device__ inline float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }  // v_exp_f32
-__device__ inline float half_max(float x) {
-  auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
-}
-__device__ inline float half_sum(float x) {
-  auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
-}
-__device__ inline f32x16 mfma(bf16x8 a, bf16x8 b, f32x16 c) {
-  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
-}
-__device__ inline bf16x8 zero8() {
-  union { u32x4 u; bf16x8 v; } z;
-  z.u = u32x4{0, 0, 0, 0};
-  return z.v;
-}
-// eight fp32 -> one bf16x8 operand (round to nearest even)
-__device__ inline bf16x8 pack8(const float* x) {
-  bf16x8 o;
-#pragma unroll
-  for (int e = 0; e < 8; ++e) o[e] = (__bf16)x[e];
-  return o;
-}
-
-// Row-major bf16 tile in LDS, `LD` elements per row.
-// natural operand: row = r, eight consecutive columns starting at 16*ks + 8*hl
-template <int LD>
-__device__ inline bf16x8 lds_nat(const uint16_t* t, int row, int ks, int hl) {
-  return *(const bf16x8*)(t + row * LD + 16 * ks + 8 * hl);
-}
-// transposed operand for the product whose k-slots are accumulator registers 8t..8t+7 of a
-// 32-row block: lane gets column (cbase + l%32) of rows rbase + {0..3, 8..11} + 4*hl
-template <int LD>
-__device__ inline bf16x8 lds_tr(const uint16_t* t, int rbase, int cbase, int lane) {
-  const int i = lane & 15, bk = lane >> 4;
-  const int row = rbase + 4 * (bk >> 1) + (i >> 2);
-  const int col = cbase + 16 * (bk & 1) + 4 * (i & 3);
-  typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
-  union { s16x4 h[2]; bf16x8 v; } o;
-  o.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(t + row * LD + col));
-  o.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(t + (row + 8) * LD + col));
-  return o.v;
-}
 
 // cooperative copy of a [BN x D] tile (rows row0.., zero past `rows_valid`) into LDS
 template <int D, int LD, int NT>
@@ -159,88 +96,6 @@ __device__ inline void relpos_setup(const KP& p, int h, int* cidx, float* table,
   for (int r = tid; r < R; r += nt)
     table[r] = p.bias_bf16 ? bf2f(((const uint16_t*)p.bias)[(int64_t)h * R + r]) : ((const float*)p.bias)[(int64_t)h * R + r];
   bc.c0 = (p.win_h - 1) * (2 * p.win_w - 1) + (p.win_w - 1);
-}
-
-__device__ inline int key_of(int v, int hl) { return 8 * (v >> 2) + 4 * hl + (v & 3); }
-
-// forward epilogue: normalise, gate, store Y (and LSE); recompute mode: gate gradient,
-// pre-gated dO copy, Delta = rowsum(dO*O) and LSE into the workspace
-template <int DB, bool RECOMP>
-__device__ inline void fwd_epilogue(const KP& p, f32x16 (&oacc)[DB], float m, float l, int b, int h, int q,
-                                    int hl, int64_t base) {
-  if (q >= p.S) return;
-  l = half_sum(l);
-  const float inv = 1.f / l;
-  const float lse = (m + log2f(l)) * LN2;
-  const int64_t row = base + (int64_t)q * p.ss;
-  if (!RECOMP) {
-    uint16_t* Yr = (uint16_t*)p.Y + row;
-    const uint16_t* Gr = (const uint16_t*)p.G + row;
-#pragma unroll
-    for (int db = 0; db < DB; ++db)
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const int d0 = 32 * db + 8 * g + 4 * hl;
-        float o[4];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) o[e] = oacc[db][4 * g + e] * inv;
-        if (p.gated) {
-          const uint2 gu = *(const uint2*)(Gr + d0);
-          const float gl[4] = {__uint_as_float(gu.x << 16), __uint_as_float(gu.x & 0xffff0000u),
-                               __uint_as_float(gu.y << 16), __uint_as_float(gu.y & 0xffff0000u)};
-#pragma unroll
-          for (int e = 0; e < 4; ++e) o[e] *= 1.f / (1.f + fast_exp2(-gl[e] * LOG2E));
-        }
-        uint2 out;
-        out.x = (uint32_t)f2bf(o[0]) | ((uint32_t)f2bf(o[1]) << 16);
-        out.y = (uint32_t)f2bf(o[2]) | ((uint32_t)f2bf(o[3]) << 16);
-        *(uint2*)(Yr + d0) = out;
-      }
-    if (p.lse_out && hl == 0) p.lse_out[(int64_t)b * p.lse_sb + (int64_t)h * p.lse_sh + q] = lse;
-  } else {
-    const uint16_t* dYr = (const uint16_t*)p.dY + row;
-    const uint16_t* Gr = (const uint16_t*)p.G + row;
-    uint16_t* dGr = (uint16_t*)p.dG + row;
-    uint16_t* dOr = (uint16_t*)p.dO_out + (int64_t)b * p.do_sb + (int64_t)q * p.do_ss + (int64_t)h * p.do_sh;
-    float part = 0.f;
-#pragma unroll
-    for (int db = 0; db < DB; ++db)
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const int d0 = 32 * db + 8 * g + 4 * hl;
-        const uint2 du = *(const uint2*)(dYr + d0);
-        float go[4] = {__uint_as_float(du.x << 16), __uint_as_float(du.x & 0xffff0000u),
-                       __uint_as_float(du.y << 16), __uint_as_float(du.y & 0xffff0000u)};
-        float o[4];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) o[e] = oacc[db][4 * g + e] * inv;
-        if (p.gated) {
-          const uint2 gu = *(const uint2*)(Gr + d0);
-          const float gl[4] = {__uint_as_float(gu.x << 16), __uint_as_float(gu.x & 0xffff0000u),
-                               __uint_as_float(gu.y << 16), __uint_as_float(gu.y & 0xffff0000u)};
-          uint16_t dg[4], dor[4];
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const float gt = 1.f / (1.f + fast_exp2(-gl[e] * LOG2E));
-            dg[e] = f2bf(go[e] * o[e] * gt * (1.f - gt));
-            dor[e] = f2bf(go[e] * gt);
-            go[e] = bf2f(dor[e]);  // the later kernels read the rounded copy
-          }
-          uint2 o1, o2;
-          o1.x = (uint32_t)dg[0] | ((uint32_t)dg[1] << 16); o1.y = (uint32_t)dg[2] | ((uint32_t)dg[3] << 16);
-          o2.x = (uint32_t)dor[0] | ((uint32_t)dor[1] << 16); o2.y = (uint32_t)dor[2] | ((uint32_t)dor[3] << 16);
-          *(uint2*)(dGr + d0) = o1;
-          *(uint2*)(dOr + d0) = o2;
-        }
-#pragma unroll
-        for (int e = 0; e < 4; ++e) part = fmaf(go[e], o[e], part);
-      }
-    part = half_sum(part);
-    if (hl == 0) {
-      p.delta[(int64_t)b * p.dl_sb + (int64_t)h * p.dl_sh + q] = part;
-      if (p.lse_out) p.lse_out[(int64_t)b * p.lse_sb + (int64_t)h * p.lse_sh + q] = lse;
-    }
-  }
 }
 
 // ---------------------------------------------------------------------------

@@ -1,0 +1,433 @@
+// Whole-sequence-in-registers attention kernels for short sequences (S <= 64) with
+// head size 32, bf16: the shape of window attention (7x7 = 49 tokens per window).
+//
+// One wavefront owns one (row b, head h) pair at a time and keeps its entire
+// padded 64x64 score matrix in MFMA accumulators, so the softmax is exact in one
+// pass, nothing is rescaled, and the backward needs no separate recompute pass,
+// no Delta pass and no O: Delta_i = sum_j P_ij dP_ij is taken from registers.
+// The backward is ONE kernel per chunk: pass 1 (lane = query) yields LSE, Delta
+// and dQ; pass 2 (lane = key) re-derives P from LSE and yields dK, dV and the
+// bias-gradient contribution.
+//
+// Bias gradient.  Rows are grouped by GW consecutive global row indices.  A
+// wavefront walks one group in row order, summing dS into registers, and stores
+// the group's partial sum [S,S] to the workspace; a group cut by a chunk boundary
+// is continued from the stored partial by the next chunk, so the order of
+// additions never depends on k.  After the last chunk the partials are summed
+// over groups in index order (dense gradient), and for a relative-position table
+// gathered per table entry in a fixed order.
+#include "mfma_common.h"
+
+namespace ssa {
+namespace {
+
+constexpr int SD = 32;        // head size
+constexpr int SLD = SD + 8;   // LDS row stride of the per-wave tiles (elements)
+constexpr int BLD = 68;       // LDS row stride of the bias tile (elements)
+constexpr int FWD_ROWS_PER_WAVE = 8;
+
+struct WaveLds {
+  uint16_t t0[64 * SLD];  // forward: V ; backward: K
+  uint16_t t1[64 * SLD];  // backward: dO
+  uint16_t t2[64 * SLD];  // backward: Q
+  float lse2[64];
+  float delta[64];
+  int rid[64];
+};
+
+// builds bias[q][k] (raw bf16 value; -inf where the pair can never be attended: padding,
+// causal) for head h; caller syncs
+__device__ inline void build_bias_tile(const KP& p, int h, uint16_t* tile, int tid, int nt) {
+  const int R = (2 * p.win_h - 1) * (2 * p.win_w - 1);
+  for (int idx = tid; idx < 64 * 64; idx += nt) {
+    const int q = idx >> 6, k = idx & 63;
+    uint16_t v = 0;
+    if (q >= p.S || k >= p.S || (p.mask_kind == 1 && k > q)) {
+      v = 0xff80;  // -inf
+    } else if (p.bias_kind == 1) {
+      const int64_t off = ((int64_t)h * p.S + q) * p.S + k;
+      v = p.bias_bf16 ? ((const uint16_t*)p.bias)[off] : f2bf(((const float*)p.bias)[off]);
+    } else if (p.bias_kind == 2) {
+      const int yq = q / p.win_w, xq = q - yq * p.win_w, yk = k / p.win_w, xk = k - yk * p.win_w;
+      const int r = (yq - yk + p.win_h - 1) * (2 * p.win_w - 1) + (xq - xk + p.win_w - 1);
+      const int64_t off = (int64_t)h * R + r;
+      v = p.bias_bf16 ? ((const uint16_t*)p.bias)[off] : f2bf(((const float*)p.bias)[off]);
+    }
+    tile[q * BLD + k] = v;
+  }
+}
+
+// natural-layout operand fragments of a [<=64 x 32] activation slice: frag[blk][ks]
+__device__ inline void load_nat(const uint16_t* base, int64_t row_stride, int S, int r, int hl, bf16x8 (&f)[2][2]) {
+#pragma unroll
+  for (int blk = 0; blk < 2; ++blk) {
+    const int row = min(32 * blk + r, S - 1);
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) f[blk][ks] = *(const bf16x8*)(base + (int64_t)row * row_stride + 16 * ks + 8 * hl);
+  }
+}
+// natural-layout fragment of rows 32*blk.. of a per-wave LDS tile
+__device__ inline bf16x8 tile_nat(const uint16_t* t, int blk, int ks, int r, int hl) {
+  return *(const bf16x8*)(t + (32 * blk + r) * SLD + 16 * ks + 8 * hl);
+}
+__device__ inline void store_tile(uint16_t* t, int r, int hl, const bf16x8 (&f)[2][2]) {
+#pragma unroll
+  for (int blk = 0; blk < 2; ++blk)
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) *(bf16x8*)(t + (32 * blk + r) * SLD + 16 * ks + 8 * hl) = f[blk][ks];
+}
+// orders this wavefront's LDS writes before its following LDS reads
+__device__ inline void wave_lds_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// scores of query block qb against both key blocks, lane = query: x = s*c1 + bias*log2e, masked -> -inf
+__device__ inline void scores_by_query(const KP& p, const bf16x8 (&kf)[2][2], const bf16x8 (&qf)[2][2], int qb,
+                                       const uint16_t* bias_tile, const int* rid, int q, int hl, float c1,
+                                       float (&x)[2][16]) {
+  const int my_rid = p.mask_kind == 2 ? rid[q] : 0;
+#pragma unroll
+  for (int kb = 0; kb < 2; ++kb) {
+    f32x16 sa;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) sa[v] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) sa = mfma(kf[kb][ks], qf[qb][ks], sa);
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const int kbase = 32 * kb + 8 * g + 4 * hl;
+      const uint2 u = *(const uint2*)(bias_tile + q * BLD + kbase);
+      const float bl[4] = {__uint_as_float(u.x << 16), __uint_as_float(u.x & 0xffff0000u),
+                           __uint_as_float(u.y << 16), __uint_as_float(u.y & 0xffff0000u)};
+      int4 rk = {0, 0, 0, 0};
+      if (p.mask_kind == 2) rk = *(const int4*)(rid + kbase);
+      const int rks[4] = {rk.x, rk.y, rk.z, rk.w};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        float t = fmaf(sa[4 * g + e], c1, bl[e] * LOG2E);
+        if (p.mask_kind == 2) t = rks[e] != my_rid ? -INFINITY : t;
+        x[kb][4 * g + e] = t;
+      }
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// forward: grid (ceil(rows/32), heads); each wavefront takes 8 consecutive rows
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void small_fwd_kernel(KP p) {
+  __shared__ __attribute__((aligned(16))) uint16_t bias_tile[64 * BLD];
+  __shared__ __attribute__((aligned(16))) WaveLds wl[4];
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, r = lane & 31, hl = lane >> 5;
+  const int h = p.h0 + blockIdx.y;
+  build_bias_tile(p, h, bias_tile, tid, 256);
+  __syncthreads();
+  WaveLds& L = wl[w];
+  const float c1 = p.scale * LOG2E;
+  const int bfirst = p.b0 + (blockIdx.x * 4 + w) * FWD_ROWS_PER_WAVE;
+  const int blast = min(bfirst + FWD_ROWS_PER_WAVE, p.b1);
+  for (int b = bfirst; b < blast; ++b) {
+    const int64_t base = (int64_t)b * p.sb + (int64_t)h * p.sh;
+    bf16x8 qf[2][2], kf[2][2], vf[2][2];
+    load_nat((const uint16_t*)p.Q + base, p.ss, p.S, r, hl, qf);
+    load_nat((const uint16_t*)p.K + base, p.ss, p.S, r, hl, kf);
+    load_nat((const uint16_t*)p.V + base, p.ss, p.S, r, hl, vf);
+    if (p.mask_kind == 2) L.rid[lane] = p.region[(int64_t)(b % p.mask_period) * p.S + min(lane, p.S - 1)];
+    store_tile(L.t0, r, hl, vf);
+    wave_lds_sync();
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
+      const int q = 32 * qb + r;
+      float x[2][16];
+      scores_by_query(p, kf, qf, qb, bias_tile, L.rid, q, hl, c1, x);
+      float m = -1e30f;
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) m = fmaxf(m, x[kb][v]);
+      m = half_max(m);
+      float l = 0.f;
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          x[kb][v] = fast_exp2(x[kb][v] - m);
+          l += x[kb][v];
+        }
+      f32x16 oacc[1];
+#pragma unroll
+      for (int v = 0; v < 16; ++v) oacc[0][v] = 0.f;
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int hb = 0; hb < 2; ++hb)
+          oacc[0] = mfma(lds_tr<SLD>(L.t0, 32 * kb + 16 * hb, 0, lane), pack8(&x[kb][8 * hb]), oacc[0]);
+      if (q < p.S) fwd_epilogue<1, false>(p, oacc, m, l, b, h, q, hl, base);
+    }
+    wave_lds_sync();  // the next row's tile stores must not overtake this row's transpose reads
+  }
+}
+
+// ---------------------------------------------------------------------------
+// backward: grid (ceil(groups/4), heads); each wavefront takes one group of rows
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void small_bwd_kernel(KP p) {
+  __shared__ __attribute__((aligned(16))) uint16_t bias_tile[64 * BLD];
+  __shared__ __attribute__((aligned(16))) WaveLds wl[4];
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, r = lane & 31, hl = lane >> 5;
+  const int h = p.h0 + blockIdx.y;
+  build_bias_tile(p, h, bias_tile, tid, 256);
+  __syncthreads();
+  WaveLds& L = wl[w];
+  const float c1 = p.scale * LOG2E;
+  const int g = p.b0 / p.sm_gw + blockIdx.x * 4 + w;  // global group index
+  const int bfirst = max(g * p.sm_gw, p.b0);
+  const int blast = min((g + 1) * p.sm_gw, p.b1);
+  if (bfirst >= blast) return;
+  // bias-gradient accumulators, lane = key: acc[qb][kb][v] for query 32*qb + key_of(v), key 32*kb + r
+  float acc[2][2][16];
+  float* part = nullptr;
+  if (p.sm_partial) {
+    part = p.sm_partial + ((int64_t)(g - p.sm_g0) * p.H + h) * p.S * p.S;
+    const bool resume = max(g * p.sm_gw, p.share_b0) < p.b0;  // an earlier chunk started this group
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int q = 32 * qb + key_of(v, hl), k = 32 * kb + r;
+          acc[qb][kb][v] = (resume && q < p.S && k < p.S) ? part[q * p.S + k] : 0.f;
+        }
+  }
+  for (int b = bfirst; b < blast; ++b) {
+    const int64_t base = (int64_t)b * p.sb + (int64_t)h * p.sh;
+    // K, dO and Q go to this wavefront's LDS tiles (read back both ways); V stays in registers
+    bf16x8 vf[2][2];
+    {
+      bf16x8 tmp[2][2];
+      load_nat((const uint16_t*)p.K + base, p.ss, p.S, r, hl, tmp);
+      store_tile(L.t0, r, hl, tmp);
+      load_nat((const uint16_t*)p.dO + (int64_t)b * p.do_sb + (int64_t)h * p.do_sh, p.do_ss, p.S, r, hl, tmp);
+      store_tile(L.t1, r, hl, tmp);
+      load_nat((const uint16_t*)p.Q + base, p.ss, p.S, r, hl, tmp);
+      store_tile(L.t2, r, hl, tmp);
+    }
+    load_nat((const uint16_t*)p.V + base, p.ss, p.S, r, hl, vf);
+    if (p.mask_kind == 2) L.rid[lane] = p.region[(int64_t)(b % p.mask_period) * p.S + min(lane, p.S - 1)];
+    wave_lds_sync();
+    // ---- pass 1, lane = query: exact softmax, Delta, dQ
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
+      const int q = 32 * qb + r;
+      float x[2][16];
+      bf16x8 qf[2][2], gq_[2];
+      {
+        bf16x8 kf[2][2];
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+          kf[0][ks] = tile_nat(L.t0, 0, ks, r, hl);
+          kf[1][ks] = tile_nat(L.t0, 1, ks, r, hl);
+          qf[qb][ks] = tile_nat(L.t2, qb, ks, r, hl);
+          gq_[ks] = tile_nat(L.t1, qb, ks, r, hl);
+        }
+        scores_by_query(p, kf, qf, qb, bias_tile, L.rid, q, hl, c1, x);
+      }
+      float m = -1e30f;
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) m = fmaxf(m, x[kb][v]);
+      m = half_max(m);
+      float l = 0.f;
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          x[kb][v] = fast_exp2(x[kb][v] - m);
+          l += x[kb][v];
+        }
+      l = half_sum(l);
+      l = q < p.S ? l : 1.f;  // padded queries: keep the statistics finite
+      const float inv = 1.f / l;
+      f32x16 pa[2];
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) pa[kb][v] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) pa[kb] = mfma(vf[kb][ks], gq_[ks], pa[kb]);
+      }
+      float dl = 0.f;
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          x[kb][v] *= inv;
+          dl = fmaf(x[kb][v], pa[kb][v], dl);
+        }
+      dl = half_sum(dl);
+      if (hl == 0) {
+        L.lse2[q] = m + log2f(l);
+        L.delta[q] = dl;
+      }
+      f32x16 dq;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) dq[v] = 0.f;
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) x[kb][v] *= (pa[kb][v] - dl);
+#pragma unroll
+        for (int hb = 0; hb < 2; ++hb)
+          dq = mfma(lds_tr<SLD>(L.t0, 32 * kb + 16 * hb, 0, lane), pack8(&x[kb][8 * hb]), dq);
+      }
+      if (q < p.S) {
+        uint16_t* out = (uint16_t*)p.dQ + base + (int64_t)q * p.ss;
+#pragma unroll
+        for (int gq = 0; gq < 4; ++gq) {
+          uint2 o;
+          o.x = (uint32_t)f2bf(dq[4 * gq] * p.scale) | ((uint32_t)f2bf(dq[4 * gq + 1] * p.scale) << 16);
+          o.y = (uint32_t)f2bf(dq[4 * gq + 2] * p.scale) | ((uint32_t)f2bf(dq[4 * gq + 3] * p.scale) << 16);
+          *(uint2*)(out + 8 * gq + 4 * hl) = o;
+        }
+      }
+    }
+    wave_lds_sync();  // LSE / Delta written by half of the lanes, read by all
+    // ---- pass 2, lane = key: P from LSE, dS, dK, dV, bias-gradient contribution
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+      const int key = 32 * kb + r;
+      const int my_rid = p.mask_kind == 2 ? L.rid[key] : 0;
+      f32x16 dk, dv;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) { dk[v] = 0.f; dv[v] = 0.f; }
+      const bf16x8 kk0 = tile_nat(L.t0, kb, 0, r, hl), kk1 = tile_nat(L.t0, kb, 1, r, hl);
+#pragma unroll
+      for (int qb = 0; qb < 2; ++qb) {
+        f32x16 sa, pa;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) { sa[v] = 0.f; pa[v] = 0.f; }
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+          sa = mfma(tile_nat(L.t2, qb, ks, r, hl), ks == 0 ? kk0 : kk1, sa);
+          pa = mfma(tile_nat(L.t1, qb, ks, r, hl), vf[kb][ks], pa);
+        }
+        float pr[16], ds[16];
+#pragma unroll
+        for (int gq = 0; gq < 4; ++gq) {
+          const int qbase = 32 * qb + 8 * gq + 4 * hl;
+          const f32x4 l4 = *(const f32x4*)(L.lse2 + qbase);
+          const f32x4 d4 = *(const f32x4*)(L.delta + qbase);
+          int4 rq = {0, 0, 0, 0};
+          if (p.mask_kind == 2) rq = *(const int4*)(L.rid + qbase);
+          const int rqs[4] = {rq.x, rq.y, rq.z, rq.w};
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const float bl = bf2f(bias_tile[(qbase + e) * BLD + key]) * LOG2E;
+            float t = fmaf(sa[4 * gq + e], c1, bl) - l4[e];
+            if (p.mask_kind == 2) t = rqs[e] != my_rid ? -INFINITY : t;
+            const float pe = fast_exp2(t);
+            pr[4 * gq + e] = pe;
+            ds[4 * gq + e] = pe * (pa[4 * gq + e] - d4[e]);
+          }
+        }
+        if (part) {
+#pragma unroll
+          for (int v = 0; v < 16; ++v) acc[qb][kb][v] += ds[v];
+        }
+#pragma unroll
+        for (int hb = 0; hb < 2; ++hb) {
+          dv = mfma(lds_tr<SLD>(L.t1, 32 * qb + 16 * hb, 0, lane), pack8(&pr[8 * hb]), dv);
+          dk = mfma(lds_tr<SLD>(L.t2, 32 * qb + 16 * hb, 0, lane), pack8(&ds[8 * hb]), dk);
+        }
+      }
+      if (key < p.S) {
+        uint16_t* oK = (uint16_t*)p.dK + base + (int64_t)key * p.ss;
+        uint16_t* oV = (uint16_t*)p.dV + base + (int64_t)key * p.ss;
+#pragma unroll
+        for (int gd = 0; gd < 4; ++gd) {
+          uint2 a, c;
+          a.x = (uint32_t)f2bf(dk[4 * gd] * p.scale) | ((uint32_t)f2bf(dk[4 * gd + 1] * p.scale) << 16);
+          a.y = (uint32_t)f2bf(dk[4 * gd + 2] * p.scale) | ((uint32_t)f2bf(dk[4 * gd + 3] * p.scale) << 16);
+          c.x = (uint32_t)f2bf(dv[4 * gd]) | ((uint32_t)f2bf(dv[4 * gd + 1]) << 16);
+          c.y = (uint32_t)f2bf(dv[4 * gd + 2]) | ((uint32_t)f2bf(dv[4 * gd + 3]) << 16);
+          *(uint2*)(oK + 8 * gd + 4 * hl) = a;
+          *(uint2*)(oV + 8 * gd + 4 * hl) = c;
+        }
+      }
+    }
+    wave_lds_sync();  // next row's tile stores after this row's reads
+  }
+  if (part) {
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int q = 32 * qb + key_of(v, hl), k = 32 * kb + r;
+          if (q < p.S && k < p.S) part[q * p.S + k] = acc[qb][kb][v];
+        }
+  }
+}
+
+// Two-level, fixed-shape sum over groups.  Level 1 folds every slice of SLICE consecutive groups
+// into the slice's first group (in place, ascending order); level 2 adds the slice sums in
+// ascending order into dense[h][i][j].  The tree depends only on the group count.
+constexpr int SLICE = 32;
+__global__ __launch_bounds__(256) void small_group_fold_kernel(float* partial, int ngroups, int H, int h0, int nh,
+                                                               int SS) {
+  const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (t >= (int64_t)nh * SS) return;
+  const int h = h0 + (int)(t / SS), ij = (int)(t % SS);
+  const int g0 = blockIdx.y * SLICE, g1 = min(g0 + SLICE, ngroups);
+  float a = 0.f;
+  for (int g = g0; g < g1; ++g) a += partial[((int64_t)g * H + h) * SS + ij];
+  partial[((int64_t)g0 * H + h) * SS + ij] = a;
+}
+__global__ __launch_bounds__(256) void small_group_reduce_kernel(const float* partial, float* dense, int ngroups,
+                                                                 int H, int h0, int nh, int SS) {
+  const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (t >= (int64_t)nh * SS) return;
+  const int h = h0 + (int)(t / SS), ij = (int)(t % SS);
+  float a = 0.f;
+  for (int g = 0; g < ngroups; g += SLICE) a += partial[((int64_t)g * H + h) * SS + ij];
+  dense[(int64_t)h * SS + ij] = a;
+}
+
+}  // namespace
+
+bool small_supported(const KP& p, bool bf16) {
+  return bf16 && p.D == SD && p.S <= 64 && !p.gated && p.scale > 0.f;
+}
+
+hipError_t launch_small_fwd(const KP& p, hipStream_t st) {
+  const int rows = p.b1 - p.b0;
+  dim3 g((rows + 4 * FWD_ROWS_PER_WAVE - 1) / (4 * FWD_ROWS_PER_WAVE), p.h1 - p.h0);
+  small_fwd_kernel<<<g, 256, 0, st>>>(p);
+  return hipGetLastError();
+}
+
+hipError_t launch_small_bwd(const KP& p, hipStream_t st) {
+  const int ng = (p.b1 - 1) / p.sm_gw - p.b0 / p.sm_gw + 1;
+  dim3 g((ng + 3) / 4, p.h1 - p.h0);
+  small_bwd_kernel<<<g, 256, 0, st>>>(p);
+  return hipGetLastError();
+}
+
+hipError_t launch_small_group_reduce(float* partial, float* dense, int ngroups, int H, int h0, int h1, int S,
+                                     hipStream_t st) {
+  const int64_t n = (int64_t)(h1 - h0) * S * S;
+  const unsigned bx = (unsigned)((n + 255) / 256);
+  small_group_fold_kernel<<<dim3(bx, (ngroups + SLICE - 1) / SLICE), 256, 0, st>>>(partial, ngroups, H, h0, h1 - h0,
+                                                                                  S * S);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  small_group_reduce_kernel<<<bx, 256, 0, st>>>(partial, dense, ngroups, H, h0, h1 - h0, S * S);
+  return hipGetLastError();
+}
+
+}  // namespace ssa

@@ -116,7 +116,9 @@ def test_workspace_shrinks_with_k():
 
 
 def test_kernel_family_selection():
-    assert ss.ss_attn_kernel_family(_desc()) == "mfma_bf16"
+    assert ss.ss_attn_kernel_family(_desc(S=128)) == "mfma_bf16"
+    assert ss.ss_attn_kernel_family(_desc(S=64)) == "mfma_bf16_short"
+    assert ss.ss_attn_kernel_family(_desc(S=64, gated=True)) == "mfma_bf16"
     assert ss.ss_attn_kernel_family(_desc(D=128)) == "mfma_bf16"
     assert ss.ss_attn_kernel_family(_desc(D=48)) == "plain_fp32"
     assert ss.ss_attn_kernel_family(_desc(dtype=ss.SS_F32)) == "plain_fp32"
@@ -131,4 +133,5 @@ def test_kernel_family_selection():
                          bias_kind={None: 0, "dense": 1, "relpos": 2}[w["bias"]], win=w.get("win", (0, 0)),
                          mask_kind={None: 0, "causal": 1, "region": 2}[w["mask"]], mask_period=256,
                          gated=w["gated"])
-        assert ss.ss_attn_kernel_family(d) == ("plain_fp32" if w["dtype"] == "f32" else "mfma_bf16"), name
+        want = "plain_fp32" if w["dtype"] == "f32" else ("mfma_bf16_short" if w["S"] <= 64 else "mfma_bf16")
+        assert ss.ss_attn_kernel_family(d) == want, name
