@@ -50,7 +50,7 @@ inline void chunk(const ss_attn_desc* d, int c, int* a, int* b) {
 }
 
 struct WsLayout {
-  size_t lse, delta, dO, dense, partial, total;
+  size_t lse, delta, dO, dense, partial, biasT, total;
   int g0, ngroups;  // short-sequence path: first global row group of the share, and how many it spans
 };
 
@@ -77,6 +77,8 @@ WsLayout bwd_layout(const ss_attn_desc* d, bool small) {
   w.g0 = row_lo / SMALL_GW;
   w.ngroups = (row_hi - 1) / SMALL_GW - w.g0 + 1;
   if (small && d->bias_kind != SS_BIAS_NONE) off += align_up((size_t)w.ngroups * d->H * d->S * d->S * 4);
+  w.biasT = off;
+  if (d->bias_kind == SS_BIAS_DENSE && d->bias_dtype == SS_BF16) off += align_up((size_t)d->H * d->S * d->S * 2);
   w.total = off;
   return w;
 }
@@ -263,6 +265,12 @@ int ss_attn_bwd(const ss_attn_desc* d, const void* Q, const void* K, const void*
   p.Q = Q; p.K = K; p.V = V; p.G = G; p.dY = dY; p.bias = bias; p.region = region_ids;
   p.dQ = dQ; p.dK = dK; p.dV = dV; p.dG = dG;
   const bool mfma = fam == FAM_MFMA;
+  if (mfma && ssa::mfma_wants_bias_transpose(p)) {
+    // the K-stationary kernels read bias[h][i][j] along i: give them a transposed copy, once per call
+    const int h0 = d->shard_axis == SS_AXIS_HEAD ? d->lo : 0, h1 = d->shard_axis == SS_AXIS_HEAD ? d->hi : d->H;
+    SS_LAUNCH(SS_K_TABLE_REDUCE, ssa::launch_bias_transpose(bias, ws + w.biasT, d->S, h0, h1, st), "bias transpose");
+    p.biasT = ws + w.biasT;
+  }
   float* dense = nullptr;
   if (want_dbias) {
     dense = d->bias_kind == SS_BIAS_DENSE ? dBias : (float*)(ws + w.dense);

@@ -24,6 +24,7 @@ struct KP {
   int64_t dl_sb, dl_sh;
   // bias / mask
   const void* bias;     // dense [H,S,S] or table [H,R]
+  const void* biasT;    // workspace copy of a dense bf16 bias with the last two axes swapped (or nullptr)
   const int32_t* region;
   float* dbias_acc;     // dense fp32 [H,S,S] accumulator (caller's dBias, or workspace for RELPOS)
   int dbias_accumulate; // 0: this chunk starts the sum, 1: continue from the stored value
@@ -62,5 +63,7 @@ hipError_t launch_mfma_fwd(const KP& p, bool recompute, hipStream_t st);
 hipError_t launch_mfma_dq(const KP& p, hipStream_t st);
 hipError_t launch_mfma_dkdv(const KP& p, hipStream_t st);
 hipError_t launch_mfma_dbias(const KP& p, hipStream_t st);
+bool mfma_wants_bias_transpose(const KP& p);  // the backward kernels read a transposed bias copy
+hipError_t launch_bias_transpose(const void* bias, void* biasT, int S, int h0, int h1, hipStream_t st);
 
 }  // namespace ssa

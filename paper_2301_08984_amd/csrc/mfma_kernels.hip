@@ -871,7 +871,7 @@ __global__ __launch_bounds__(256 * NG) __attribute__((amdgpu_waves_per_eu(2, 2))
 }
 
 // ---------------------------------------------------------------------------
-// dK, dV without bias (optionally causal), one wavefront per SIMD.  Each wavefront
+// dK, dV (optional dense bf16 bias read from its transposed copy, optional causal mask).  Each wavefront
 // keeps a 32-key block of K and V and both gradient accumulators in registers and
 // walks the queries in 32-row sub-blocks with a software pipeline: while the vector
 // ALUs turn the scores of sub-block j into P and dS, the matrix cores already
@@ -879,7 +879,7 @@ __global__ __launch_bounds__(256 * NG) __attribute__((amdgpu_waves_per_eu(2, 2))
 // Q / dO tiles (64 rows) are double-buffered in LDS, one barrier per tile; the next
 // tile travels global -> registers meanwhile.
 // ---------------------------------------------------------------------------
-template <int D, bool CAUSAL>
+template <int D, bool BIAS, bool CAUSAL>
 __global__ __launch_bounds__(256) void dkdv_fast_kernel(KP p) {
   constexpr int KS = D / 16, DB = D / 32, LD = D + 16, NT = 256;
   constexpr int CPR = D / 8, CPT = BN * CPR / NT;
@@ -899,6 +899,8 @@ __global__ __launch_bounds__(256) void dkdv_fast_kernel(KP p) {
   const uint16_t* dOb = (const uint16_t*)p.dO + (int64_t)b * p.do_sb + (int64_t)h * p.do_sh;
   const float* lse_b = p.lse + (int64_t)b * p.lse_sb + (int64_t)h * p.lse_sh;
   const float* dl_b = p.delta + (int64_t)b * p.dl_sb + (int64_t)h * p.dl_sh;
+  // transposed bias copy: biasT[h][key][query], four consecutive queries per 8-byte load
+  const uint16_t* biasT_row = BIAS ? (const uint16_t*)p.biasT + ((int64_t)h * p.S + kc) * p.S : nullptr;
 
   bf16x8 kf[KS], vf[KS];
 #pragma unroll
@@ -957,16 +959,22 @@ __global__ __launch_bounds__(256) void dkdv_fast_kernel(KP p) {
   };
   // P and dS of one sub-block, as packed bf16 operands
   auto stage_v = [&](const float* tl, const float* td, int i0, int sub, const f32x16& sa, const f32x16& pa,
-                     bf16x8 (&pf)[2], bf16x8 (&df)[2], auto edge_tag) {
+                     const uint2* bz, bf16x8 (&pf)[2], bf16x8 (&df)[2], auto edge_tag) {
     constexpr bool edge = decltype(edge_tag)::value;
     float pr[16], ds[16];
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
       const f32x4 l4 = *(const f32x4*)(tl + 32 * sub + 8 * g + 4 * hl);
       const f32x4 d4 = *(const f32x4*)(td + 32 * sub + 8 * g + 4 * hl);
+      float bl[4] = {0.f, 0.f, 0.f, 0.f};
+      if (BIAS) {
+        const uint2 u = bz[4 * sub + g];
+        bl[0] = __uint_as_float(u.x << 16) * LOG2E; bl[1] = __uint_as_float(u.x & 0xffff0000u) * LOG2E;
+        bl[2] = __uint_as_float(u.y << 16) * LOG2E; bl[3] = __uint_as_float(u.y & 0xffff0000u) * LOG2E;
+      }
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
-        float pe = fast_exp2(fmaf(sa[4 * g + e], c1, -l4[e]));
+        float pe = fast_exp2(fmaf(sa[4 * g + e], c1, bl[e] - l4[e]));
         if (edge) {
           const int i = i0 + 32 * sub + 8 * g + 4 * hl + e;
           const bool dead = i >= p.S || key >= p.S || (CAUSAL && key > i);
@@ -1015,14 +1023,19 @@ __global__ __launch_bounds__(256) void dkdv_fast_kernel(KP p) {
     const bool edge = (i0 + BN > p.S) || (k0 + 32 > p.S) || (CAUSAL && i0 < k0 + 31);
     // one straight-line block per tile: A0 | A1 with V0 | B0 with V1 | B1, where A = scores and dP
     // on the matrix cores, V = P and dS on the vector ALUs, B = gradient products
+    uint2 bz[8];
+    if (BIAS) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) bz[j] = *(const uint2*)(biasT_row + min(i0 + 8 * j + 4 * hl, p.S - 4));
+    }
     auto tile = [&](auto edge_tag) {
       f32x16 sa0, pa0, sa1, pa1;
       bf16x8 pf0[2], df0[2], pf1[2], df1[2];
       stage_a(tq, tg, 0, sa0, pa0);
       stage_a(tq, tg, 1, sa1, pa1);
-      stage_v(tl, td, i0, 0, sa0, pa0, pf0, df0, edge_tag);
+      stage_v(tl, td, i0, 0, sa0, pa0, bz, pf0, df0, edge_tag);
       stage_b(tq, tg, 0, pf0, df0);
-      stage_v(tl, td, i0, 1, sa1, pa1, pf1, df1, edge_tag);
+      stage_v(tl, td, i0, 1, sa1, pa1, bz, pf1, df1, edge_tag);
       stage_b(tq, tg, 1, pf1, df1);
       // A0
       __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
@@ -1149,6 +1162,112 @@ __global__ __launch_bounds__(256) void mfma_dbias_kernel(KP p) {
   }
 }
 
+// ---------------------------------------------------------------------------
+// bias gradient, specialised (dense bf16 bias, no region mask): one wavefront owns a
+// 32-key x 32-query block of one head, keeps the bias and the running sum in registers
+// (lane = query, registers = keys) and walks the chunk's rows in order; the operands
+// of row b+1 are fetched while row b is computed.  Continuing from the stored value
+// on later chunks keeps the order of additions independent of k.
+// ---------------------------------------------------------------------------
+template <int D, bool CAUSAL>
+__global__ __launch_bounds__(256) void dbias_fast_kernel(KP p) {
+  constexpr int KS = D / 16;
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, r = lane & 31, hl = lane >> 5;
+  const int h = p.h0 + blockIdx.z;
+  const int q0 = blockIdx.y * 32;
+  const int k0 = (blockIdx.x * 4 + w) * 32;
+  if (k0 >= p.S) return;
+  const int q = q0 + r, qc = min(q, p.S - 1);
+  const int kr = min(k0 + r, p.S - 1);  // key row this lane supplies to the A operands
+  float* dst = p.dbias_acc + ((int64_t)h * p.S + qc) * p.S;
+  if (CAUSAL && k0 > q0 + 31) {  // block entirely above the diagonal: gradient is zero
+    if (!p.dbias_accumulate && q < p.S) {
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int kb = k0 + 8 * g + 4 * hl;
+        if (kb + 3 < p.S) *(f32x4*)(dst + kb) = f32x4{0.f, 0.f, 0.f, 0.f};
+        else for (int e = 0; e < 4; ++e) if (kb + e < p.S) dst[kb + e] = 0.f;
+      }
+    }
+    return;
+  }
+  float acc[16], bz[16];
+#pragma unroll
+  for (int v = 0; v < 16; ++v) {
+    const int k = min(k0 + key_of(v, hl), p.S - 1);
+    acc[v] = p.dbias_accumulate ? dst[k] : 0.f;
+    bz[v] = bf2f(((const uint16_t*)p.bias)[((int64_t)h * p.S + qc) * p.S + k]) * LOG2E;
+  }
+  const float c1 = p.scale * LOG2E;
+  const int64_t row_q = (int64_t)h * p.sh + (int64_t)qc * p.ss;
+  const int64_t row_k = (int64_t)h * p.sh + (int64_t)kr * p.ss;
+  const int64_t row_g = (int64_t)h * p.do_sh + (int64_t)qc * p.do_ss;
+  const int64_t st_off = (int64_t)h * p.lse_sh + qc, dl_off = (int64_t)h * p.dl_sh + qc;
+  bf16x8 fq[2][KS], fk[2][KS], fv[2][KS], fg[2][KS];
+  float lse2[2], dlt[2];
+  auto fetch = [&](int b, int slot) {
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      const int c = 16 * ks + 8 * hl;
+      fq[slot][ks] = *(const bf16x8*)((const uint16_t*)p.Q + (int64_t)b * p.sb + row_q + c);
+      fk[slot][ks] = *(const bf16x8*)((const uint16_t*)p.K + (int64_t)b * p.sb + row_k + c);
+      fv[slot][ks] = *(const bf16x8*)((const uint16_t*)p.V + (int64_t)b * p.sb + row_k + c);
+      fg[slot][ks] = *(const bf16x8*)((const uint16_t*)p.dO + (int64_t)b * p.do_sb + row_g + c);
+    }
+    lse2[slot] = p.lse[(int64_t)b * p.lse_sb + st_off] * LOG2E;
+    dlt[slot] = p.delta[(int64_t)b * p.dl_sb + dl_off];
+  };
+  auto step = [&](int slot, bool valid) {
+    f32x16 sa, pa;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) { sa[v] = 0.f; pa[v] = 0.f; }
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      sa = mfma(fk[slot][ks], fq[slot][ks], sa);
+      pa = mfma(fv[slot][ks], fg[slot][ks], pa);
+    }
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const float e = fast_exp2(fmaf(sa[v], c1, bz[v] - lse2[slot]));
+      float t = valid ? pa[v] - dlt[slot] : 0.f;
+      if (CAUSAL) t = k0 + key_of(v, hl) > q ? 0.f : t;
+      // one explicit fused multiply-add; a padding row contributes e * 0
+      acc[v] = __builtin_fmaf(e, t, acc[v]);
+    }
+  };
+  // rows are taken in pairs aligned to even global row indices, so a given row always runs
+  // through the same copy of the arithmetic whatever the chunk boundaries are; a pair that
+  // sticks out of the chunk is completed by a padding row of weight zero
+  const int bs = p.b0 & ~1;
+  fetch(max(bs, p.b0), 0);
+  for (int b = bs; b < p.b1; b += 2) {
+    fetch(min(b + 1, p.b1 - 1), 1);
+    step(0, b >= p.b0);
+    if (b + 2 < p.b1) fetch(b + 2, 0);
+    step(1, b + 1 < p.b1);
+  }
+  if (q < p.S) {
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const int kb = k0 + 8 * g + 4 * hl;
+      if (kb + 3 < p.S) *(f32x4*)(dst + kb) = f32x4{acc[4 * g], acc[4 * g + 1], acc[4 * g + 2], acc[4 * g + 3]};
+      else for (int e = 0; e < 4; ++e) if (kb + e < p.S) dst[kb + e] = acc[4 * g + e];
+    }
+  }
+}
+
+// biasT[h][j][i] = bias[h][i][j] (bf16), 32x32 tiles through LDS; heads [h0,h1)
+__global__ __launch_bounds__(256) void bias_transpose_kernel(const uint16_t* src, uint16_t* dst, int S, int h0) {
+  __shared__ uint16_t t[32][33];
+  const int h = h0 + blockIdx.z, i0 = blockIdx.y * 32, j0 = blockIdx.x * 32;
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+  for (int y = ty; y < 32; y += 8)
+    if (i0 + y < S && j0 + tx < S) t[y][tx] = src[((int64_t)h * S + i0 + y) * S + j0 + tx];
+  __syncthreads();
+  for (int y = ty; y < 32; y += 8)
+    if (j0 + y < S && i0 + tx < S) dst[((int64_t)h * S + j0 + y) * S + i0 + tx] = t[tx][y];
+}
+
 // the specialised kernels serve: no bias or a dense bf16 bias with S % 4 == 0; no mask or the
 // causal mask; a positive scale; more than one 64-key tile's worth of rows
 inline bool fast_ok(const KP& p) {
@@ -1223,10 +1342,13 @@ hipError_t dq_d(const KP& p, hipStream_t st) {
 template <int D>
 hipError_t dkdv_d(const KP& p, hipStream_t st) {
   const int Hc = p.h1 - p.h0, Bc = p.b1 - p.b0;
-  if (fast_ok(p) && p.bias_kind == 0) {
+  if (fast_ok(p)) {
     dim3 g((p.S + 127) / 128, Hc, Bc);
-    if (p.mask_kind == 1) dkdv_fast_kernel<D, true><<<g, 256, 0, st>>>(p);
-    else dkdv_fast_kernel<D, false><<<g, 256, 0, st>>>(p);
+    const bool bias = p.bias_kind == 1, causal = p.mask_kind == 1;
+    if (bias && causal) dkdv_fast_kernel<D, true, true><<<g, 256, 0, st>>>(p);
+    else if (bias) dkdv_fast_kernel<D, true, false><<<g, 256, 0, st>>>(p);
+    else if (causal) dkdv_fast_kernel<D, false, true><<<g, 256, 0, st>>>(p);
+    else dkdv_fast_kernel<D, false, false><<<g, 256, 0, st>>>(p);
     return hipGetLastError();
   }
   if (p.S <= 64) mfma_dkdv_kernel<D, 2><<<dim3((p.S + 63) / 64, Hc, Bc), 128, 0, st>>>(p);
@@ -1235,6 +1357,12 @@ hipError_t dkdv_d(const KP& p, hipStream_t st) {
 }
 template <int D>
 hipError_t dbias_d(const KP& p, hipStream_t st) {
+  if (fast_ok(p) && p.bias_kind == 1) {
+    dim3 g((p.S + 127) / 128, (p.S + 31) / 32, p.h1 - p.h0);
+    if (p.mask_kind == 1) dbias_fast_kernel<D, true><<<g, 256, 0, st>>>(p);
+    else dbias_fast_kernel<D, false><<<g, 256, 0, st>>>(p);
+    return hipGetLastError();
+  }
   dim3 g((p.S + 127) / 128, (p.S + 31) / 32, p.h1 - p.h0);
   mfma_dbias_kernel<D><<<g, 256, 0, st>>>(p);
   return hipGetLastError();
@@ -1262,5 +1390,13 @@ hipError_t launch_mfma_fwd(const KP& p, bool recompute, hipStream_t st) { SS_DIS
 hipError_t launch_mfma_dq(const KP& p, hipStream_t st) { SS_DISPATCH_D(dq_d, p, st) }
 hipError_t launch_mfma_dkdv(const KP& p, hipStream_t st) { SS_DISPATCH_D(dkdv_d, p, st) }
 hipError_t launch_mfma_dbias(const KP& p, hipStream_t st) { SS_DISPATCH_D(dbias_d, p, st) }
+
+bool mfma_wants_bias_transpose(const KP& p) { return fast_ok(p) && p.bias_kind == 1; }
+
+hipError_t launch_bias_transpose(const void* bias, void* biasT, int S, int h0, int h1, hipStream_t st) {
+  dim3 g((S + 31) / 32, (S + 31) / 32, h1 - h0);
+  bias_transpose_kernel<<<g, 256, 0, st>>>((const uint16_t*)bias, (uint16_t*)biasT, S, h0);
+  return hipGetLastError();
+}
 
 }  // namespace ssa
