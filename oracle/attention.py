@@ -224,6 +224,33 @@ def attn_backward(p: AttnProblem, dY, axis=AXIS_HEAD, lo=0, hi=None):
     return out
 
 
+def bias_grad_rows(p: AttnProblem, dY, h: int, queries, lo=0, hi=None):
+    """Dense bias gradient restricted to chosen query rows: dBias[h, i, :] for i in
+    `queries`, summed over rows b in [lo,hi).  Row i of the softmax and of dS depends on
+    row i of Q, dY and G only, so it is evaluated from the definition without forming the
+    other rows; used to check full-size runs on sampled rows.  Returns [len(queries), S]."""
+    if p.bias is None or p.bias[0] != "dense":
+        raise ValueError("dense bias only")
+    hi = p.B if hi is None else hi
+    dY = np.asarray(dY, dtype=np.float64)
+    out = np.zeros((len(queries), p.S))
+    for b in range(lo, hi):
+        Km, Vm = p.K[b, :, h, :], p.V[b, :, h, :]
+        M = p.masked(b)
+        for n, i in enumerate(queries):
+            s = p.scale * (Km @ p.Q[b, i, h, :]) + np.asarray(p.bias[1], dtype=np.float64)[h, i]
+            if M is not None:
+                s = np.where(M[i], -np.inf, s)
+            e = np.exp(s - np.max(s))
+            pr = e / np.sum(e)
+            dO = dY[b, i, h, :]
+            if p.G is not None:
+                dO = dO * _sigmoid(p.G[b, i, h, :])
+            dP = Vm @ dO
+            out[n] += pr * (dP - np.sum(pr * dP))
+    return out
+
+
 # ----------------------------------------------------------------------------
 # The co-shard form (Section 2): k sub-operators run one after another on the
 # same device; split-axis outputs are concatenated, gradients of tensors that

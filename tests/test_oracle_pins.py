@@ -375,3 +375,13 @@ def test_planted_mistakes_are_caught():
     assert not np.allclose(g["dQ"][0, :, 0], wrong_transposed, rtol=1e-6)
     assert not np.allclose(g["dQ"][0, :, 0], wrong_noscale, rtol=1e-6)
     np.testing.assert_allclose(g["dQ"][0, :, 0], bdQ, rtol=1e-10, atol=1e-12)
+
+
+def test_bias_grad_rows_equals_rows_of_full_gradient():
+    rng = np.random.default_rng(14)
+    for case in (dict(bias="dense", gated=True), dict(bias="dense", mask="causal")):
+        p, dY = _problem(rng, B=4, H=2, S=7, D=3, **case)
+        full = orc.attn_backward(p, dY, orc.AXIS_ROW, 1, 4)["dBias"]
+        for h in range(p.H):
+            got = orc.bias_grad_rows(p, dY, h, [0, 3, 6], 1, 4)
+            np.testing.assert_allclose(got, full[h][[0, 3, 6]], rtol=1e-11, atol=1e-13)
