@@ -114,6 +114,8 @@ def main():
     ap.add_argument("--k", type=int, default=None, help="co-shard factor of the timed steps")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the per-k table and the instrumented pass")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run one 256 MiB device copy (a known-size kernel to scale rocprofv3 counters by)")
     a = ap.parse_args()
     if a.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (no collectives, no sharding across GPUs); "
@@ -140,6 +142,12 @@ def main():
         dc.fwd(d, want_lse=False)
         dc.bwd(d)
 
+    if a.calibration_copy:
+        src = torch.zeros(256 << 20, dtype=torch.uint8, device=dc.dev)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(a.warmup):
         step(desc)
     torch.cuda.synchronize()

@@ -75,6 +75,26 @@ __device__ inline bf16x8 lds_tr(const uint16_t* t, int rbase, int cbase, int lan
   return o.v;
 }
 
+// Work-groups are handed to the 8 XCDs round-robin in launch order, and each XCD has its own L2.
+// This maps the hardware block id to a logical (x, y, z) such that blocks with consecutive
+// logical ids (same head and row, neighbouring tiles: the ones that re-read the same K/V or
+// Q/dO) run on the same XCD.  A bijection on [0, gridDim.x*gridDim.y*gridDim.z).
+struct BlockId { int x, y, z; };
+__device__ inline BlockId xcd_block_id() {
+  constexpr int NX = 8;
+  const int gx = gridDim.x, gy = gridDim.y;
+  const int n = gx * gy * gridDim.z;
+  const int lin = blockIdx.x + gx * (blockIdx.y + gy * blockIdx.z);
+  const int xcd = lin % NX, idx = lin / NX;
+  const int v = xcd * (n / NX) + min(xcd, n % NX) + idx;
+  BlockId b;
+  b.x = v % gx;
+  const int yz = v / gx;
+  b.y = yz % gy;
+  b.z = yz / gy;
+  return b;
+}
+
 __device__ inline int key_of(int v, int hl) { return 8 * (v >> 2) + 4 * hl + (v & 3); }
 
 // forward epilogue: normalise, gate, store Y (and LSE); recompute mode: gate gradient,

@@ -304,8 +304,9 @@ __global__ __launch_bounds__(256 * NG) __attribute__((amdgpu_waves_per_eu(2, 2))
   const int lane = tid & 63, w = tid >> 6, r = lane & 31, hl = lane >> 5;
   uint16_t* sK = smem + grp * TILE_ELEMS;
   uint16_t* sV = sK + BN * LDK;
-  const int h = p.h0 + blockIdx.y, b = p.b0 + blockIdx.z;
-  const int qblk = (gridDim.x - 1 - blockIdx.x) * 128;  // long (late) causal blocks first
+  const BlockId blk = xcd_block_id();
+  const int h = p.h0 + blk.y, b = p.b0 + blk.z;
+  const int qblk = (gridDim.x - 1 - blk.x) * 128;  // long (late) causal blocks first
   const int q0 = qblk + 32 * w, q = q0 + r;
   const int qc = min(q, p.S - 1);
   const int64_t base = (int64_t)b * p.sb + (int64_t)h * p.sh;
@@ -727,8 +728,9 @@ __global__ __launch_bounds__(256 * NG) __attribute__((amdgpu_waves_per_eu(2, 2))
   const int lane = tid & 63, w = tid >> 6, r = lane & 31, hl = lane >> 5;
   uint16_t* sK = smem + grp * TILE_ELEMS;
   uint16_t* sV = sK + BN * LDK;
-  const int h = p.h0 + blockIdx.y, b = p.b0 + blockIdx.z;
-  const int qblk = (gridDim.x - 1 - blockIdx.x) * 128;
+  const BlockId blk = xcd_block_id();
+  const int h = p.h0 + blk.y, b = p.b0 + blk.z;
+  const int qblk = (gridDim.x - 1 - blk.x) * 128;
   const int q0 = qblk + 32 * w, q = q0 + r;
   const int qc = min(q, p.S - 1);
   const int64_t base = (int64_t)b * p.sb + (int64_t)h * p.sh;
@@ -888,8 +890,9 @@ __global__ __launch_bounds__(256) void dkdv_fast_kernel(KP p) {
   __shared__ __attribute__((aligned(16))) float sL[2][BN];
   __shared__ __attribute__((aligned(16))) float sD[2][BN];
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, r = lane & 31, hl = lane >> 5;
-  const int h = p.h0 + blockIdx.y, b = p.b0 + blockIdx.z;
-  const int kblk = blockIdx.x * 128;  // early key blocks see the most queries under a causal mask
+  const BlockId blk = xcd_block_id();
+  const int h = p.h0 + blk.y, b = p.b0 + blk.z;
+  const int kblk = blk.x * 128;  // early key blocks see the most queries under a causal mask
   const int k0 = kblk + 32 * w, key = k0 + r;
   const int kc = min(key, p.S - 1);
   const int64_t base = (int64_t)b * p.sb + (int64_t)h * p.sh;
