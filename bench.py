@@ -114,8 +114,9 @@ def main():
     ap.add_argument("--k", type=int, default=None, help="co-shard factor of the timed steps")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the per-k table and the instrumented pass")
+    ap.add_argument("--no-per-k", action="store_true", help="skip the table over the workload's other k")
     ap.add_argument("--calibration-copy", action="store_true",
-                    help="also run one 256 MiB device copy (a known-size kernel to scale rocprofv3 counters by)")
+                    help="also run one 1 GiB device copy (a known-size kernel to scale rocprofv3 counters by)")
     a = ap.parse_args()
     if a.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (no collectives, no sharding across GPUs); "
@@ -143,7 +144,7 @@ def main():
         dc.bwd(d)
 
     if a.calibration_copy:
-        src = torch.zeros(256 << 20, dtype=torch.uint8, device=dc.dev)
+        src = torch.zeros(1 << 30, dtype=torch.uint8, device=dc.dev)
         dst = torch.empty_like(src)
         dst.copy_(src)
         torch.cuda.synchronize()
@@ -194,6 +195,13 @@ def main():
             ach = kernel_bytes(w, dom, units, ext) / dur / 1e9
             roof = {"bound": "hbm", "achieved": ach, "peak": PEAK_HBM / 1e9, "unit": "GB/s",
                     "frac": ach * 1e9 / PEAK_HBM, "traffic": None}
+        # HBM bytes per launch of that kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
+        # same command (calibrated by a known-size copy), recorded under profiles/
+        try:
+            with open(os.path.join(ROOT, "profiles", "hbm_traffic.json")) as fh:
+                roof["traffic"] = json.load(fh).get(a.workload, {}).get(dom)
+        except OSError:
+            pass
         roof["kernel"] = dom
         roof["avg_launch_us"] = per_kernel[dom]["avg_us"]
         out["roofline"] = roof
@@ -202,7 +210,7 @@ def main():
         # throughput, workspace and peak HBM bytes for every co-shard factor of the workload
         table = []
         caller = dc.caller_bytes()
-        for k in sorted(set(ks) | {k_main}):
+        for k in ([] if a.no_per_k else sorted(set(ks) | {k_main})):
             d = dc.desc(w["axis"], 0, ext, k)
             _, wsb = ss.ss_attn_workspace_bytes(d)
             dc.workspace(d)

@@ -931,7 +931,7 @@ __global__ __launch_bounds__(256) void dkdv_fast_kernel(KP p) {
     }
     if (tid < 2 * BN) {
       const int i = min(qt * BN + (tid & (BN - 1)), p.S - 1);
-      pstat = tid < BN ? lse_b[i] * LOG2E : dl_b[i];
+      pstat = tid < BN ? lse_b[i] : dl_b[i];  // LSE is scaled when stored to LDS, not on the in-flight load
     }
   };
   auto lstore = [&](int buf) {
@@ -941,7 +941,7 @@ __global__ __launch_bounds__(256) void dkdv_fast_kernel(KP p) {
       *(u32x4*)(&sQ[buf][row * LD + col]) = pq[c];
       *(u32x4*)(&sG[buf][row * LD + col]) = pg[c];
     }
-    if (tid < BN) sL[buf][tid] = pstat;
+    if (tid < BN) sL[buf][tid] = pstat * LOG2E;
     else if (tid < 2 * BN) sD[buf][tid - BN] = pstat;
   };
   // scores and dP of one 32-query sub-block
@@ -1176,9 +1176,10 @@ template <int D, bool CAUSAL>
 __global__ __launch_bounds__(256) void dbias_fast_kernel(KP p) {
   constexpr int KS = D / 16;
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, r = lane & 31, hl = lane >> 5;
-  const int h = p.h0 + blockIdx.z;
-  const int q0 = blockIdx.y * 32;
-  const int k0 = (blockIdx.x * 4 + w) * 32;
+  const BlockId blk = xcd_block_id();  // one head's blocks share an XCD: its rows are fetched into one L2
+  const int h = p.h0 + blk.z;
+  const int q0 = blk.y * 32;
+  const int k0 = (blk.x * 4 + w) * 32;
   if (k0 >= p.S) return;
   const int q = q0 + r, qc = min(q, p.S - 1);
   const int kr = min(k0 + r, p.S - 1);  // key row this lane supplies to the A operands
@@ -1206,8 +1207,9 @@ __global__ __launch_bounds__(256) void dbias_fast_kernel(KP p) {
   const int64_t row_k = (int64_t)h * p.sh + (int64_t)kr * p.ss;
   const int64_t row_g = (int64_t)h * p.do_sh + (int64_t)qc * p.do_ss;
   const int64_t st_off = (int64_t)h * p.lse_sh + qc, dl_off = (int64_t)h * p.dl_sh + qc;
-  bf16x8 fq[2][KS], fk[2][KS], fv[2][KS], fg[2][KS];
-  float lse2[2], dlt[2];
+  constexpr int NS = D <= 32 ? 4 : 2;  // operand slots: rows b+1 .. b+NS-1 are in flight while row b is computed
+  bf16x8 fq[NS][KS], fk[NS][KS], fv[NS][KS], fg[NS][KS];
+  float lse2[NS], dlt[NS];
   auto fetch = [&](int b, int slot) {
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
@@ -1217,10 +1219,11 @@ __global__ __launch_bounds__(256) void dbias_fast_kernel(KP p) {
       fv[slot][ks] = *(const bf16x8*)((const uint16_t*)p.V + (int64_t)b * p.sb + row_k + c);
       fg[slot][ks] = *(const bf16x8*)((const uint16_t*)p.dO + (int64_t)b * p.do_sb + row_g + c);
     }
-    lse2[slot] = p.lse[(int64_t)b * p.lse_sb + st_off] * LOG2E;
+    lse2[slot] = p.lse[(int64_t)b * p.lse_sb + st_off];  // scaled at use: no arithmetic on in-flight loads
     dlt[slot] = p.delta[(int64_t)b * p.dl_sb + dl_off];
   };
   auto step = [&](int slot, bool valid) {
+    const float lse2s = lse2[slot] * LOG2E;
     f32x16 sa, pa;
 #pragma unroll
     for (int v = 0; v < 16; ++v) { sa[v] = 0.f; pa[v] = 0.f; }
@@ -1231,23 +1234,26 @@ __global__ __launch_bounds__(256) void dbias_fast_kernel(KP p) {
     }
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
-      const float e = fast_exp2(fmaf(sa[v], c1, bz[v] - lse2[slot]));
+      const float e = fast_exp2(fmaf(sa[v], c1, bz[v] - lse2s));
       float t = valid ? pa[v] - dlt[slot] : 0.f;
       if (CAUSAL) t = k0 + key_of(v, hl) > q ? 0.f : t;
       // one explicit fused multiply-add; a padding row contributes e * 0
       acc[v] = __builtin_fmaf(e, t, acc[v]);
     }
   };
-  // rows are taken in pairs aligned to even global row indices, so a given row always runs
-  // through the same copy of the arithmetic whatever the chunk boundaries are; a pair that
-  // sticks out of the chunk is completed by a padding row of weight zero
-  const int bs = p.b0 & ~1;
-  fetch(max(bs, p.b0), 0);
-  for (int b = bs; b < p.b1; b += 2) {
-    fetch(min(b + 1, p.b1 - 1), 1);
-    step(0, b >= p.b0);
-    if (b + 2 < p.b1) fetch(b + 2, 0);
-    step(1, b + 1 < p.b1);
+  // rows are taken in groups of NS aligned to multiples of NS of the global row index, row b
+  // always using slot b % NS: a given row passes through the same copy of the arithmetic whatever
+  // the chunk boundaries are; rows of a group outside the chunk are padding rows of weight zero
+  const int bs = p.b0 - p.b0 % NS;
+  auto clampb = [&](int b) { return min(max(b, p.b0), p.b1 - 1); };
+#pragma unroll
+  for (int s_ = 0; s_ < NS - 1; ++s_) fetch(clampb(bs + s_), s_);
+  for (int b = bs; b < p.b1; b += NS) {
+#pragma unroll
+    for (int s_ = 0; s_ < NS; ++s_) {
+      fetch(clampb(b + s_ + NS - 1), (s_ + NS - 1) % NS);
+      step(s_, b + s_ >= p.b0 && b + s_ < p.b1);
+    }
   }
   if (q < p.S) {
 #pragma unroll
