@@ -1,0 +1,375 @@
+// Specialised dK/dV and bias-gradient kernels, and the bias transpose (see the comments above each).
+#include "mfma_common.h"
+
+#include <type_traits>
+
+namespace ssa {
+namespace {
+
+// ---------------------------------------------------------------------------
+// dK, dV (optional dense bf16 bias read from its transposed copy, optional causal mask).  Each wavefront
+// keeps a 32-key block of K and V and both gradient accumulators in registers and
+// walks the queries in 32-row sub-blocks with a software pipeline: while the vector
+// ALUs turn the scores of sub-block j into P and dS, the matrix cores already
+// produce the scores of sub-block j+1 and consume P/dS of sub-block j-1.
+// Q / dO tiles (64 rows) are double-buffered in LDS, one barrier per tile; the next
+// tile travels global -> registers meanwhile.
+// ---------------------------------------------------------------------------
+template <int D, bool BIAS, bool CAUSAL>
+__global__ __launch_bounds__(256) void dkdv_fast_kernel(KP p) {
+  constexpr int KS = D / 16, DB = D / 32, LD = D + 16, NT = 256;
+  constexpr int CPR = D / 8, CPT = BN * CPR / NT;
+  __shared__ __attribute__((aligned(16))) uint16_t sQ[2][BN * LD];
+  __shared__ __attribute__((aligned(16))) uint16_t sG[2][BN * LD];
+  __shared__ __attribute__((aligned(16))) float sL[2][BN];
+  __shared__ __attribute__((aligned(16))) float sD[2][BN];
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, r = lane & 31, hl = lane >> 5;
+  const BlockId blk = xcd_block_id();
+  const int h = p.h0 + blk.y, b = p.b0 + blk.z;
+  const int kblk = blk.x * 128;  // early key blocks see the most queries under a causal mask
+  const int k0 = kblk + 32 * w, key = k0 + r;
+  const int kc = min(key, p.S - 1);
+  const int64_t base = (int64_t)b * p.sb + (int64_t)h * p.sh;
+  const uint16_t* Qb = (const uint16_t*)p.Q + base;
+  const uint16_t* Kb = (const uint16_t*)p.K + base;
+  const uint16_t* Vb = (const uint16_t*)p.V + base;
+  const uint16_t* dOb = (const uint16_t*)p.dO + (int64_t)b * p.do_sb + (int64_t)h * p.do_sh;
+  const float* lse_b = p.lse + (int64_t)b * p.lse_sb + (int64_t)h * p.lse_sh;
+  const float* dl_b = p.delta + (int64_t)b * p.dl_sb + (int64_t)h * p.dl_sh;
+  // transposed bias copy: biasT[h][key][query], four consecutive queries per 8-byte load
+  const uint16_t* biasT_row = BIAS ? (const uint16_t*)p.biasT + ((int64_t)h * p.S + kc) * p.S : nullptr;
+
+  bf16x8 kf[KS], vf[KS];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) {
+    kf[ks] = *(const bf16x8*)(Kb + (int64_t)kc * p.ss + 16 * ks + 8 * hl);
+    vf[ks] = *(const bf16x8*)(Vb + (int64_t)kc * p.ss + 16 * ks + 8 * hl);
+  }
+  f32x16 dk[DB], dv[DB];
+#pragma unroll
+  for (int db = 0; db < DB; ++db)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) { dk[db][v] = 0.f; dv[db][v] = 0.f; }
+  const float c1 = p.scale * LOG2E;
+  const int ntiles = (p.S + BN - 1) / BN;
+  const int first = CAUSAL ? kblk / BN : 0;  // queries before the block's first key see none of it
+
+  u32x4 pq[CPT], pg[CPT];
+  float pstat = 0.f;
+  auto gload = [&](int qt) {
+#pragma unroll
+    for (int c = 0; c < CPT; ++c) {
+      const int idx = tid + c * NT, row = min(qt * BN + idx / CPR, p.S - 1), col = (idx % CPR) * 8;
+      pq[c] = *(const u32x4*)(Qb + (int64_t)row * p.ss + col);
+      pg[c] = *(const u32x4*)(dOb + (int64_t)row * p.do_ss + col);
+    }
+    if (tid < 2 * BN) {
+      const int i = min(qt * BN + (tid & (BN - 1)), p.S - 1);
+      pstat = tid < BN ? lse_b[i] : dl_b[i];  // LSE is scaled when stored to LDS, not on the in-flight load
+    }
+  };
+  auto lstore = [&](int buf) {
+#pragma unroll
+    for (int c = 0; c < CPT; ++c) {
+      const int idx = tid + c * NT, row = idx / CPR, col = (idx % CPR) * 8;
+      *(u32x4*)(&sQ[buf][row * LD + col]) = pq[c];
+      *(u32x4*)(&sG[buf][row * LD + col]) = pg[c];
+    }
+    if (tid < BN) sL[buf][tid] = pstat * LOG2E;
+    else if (tid < 2 * BN) sD[buf][tid - BN] = pstat;
+  };
+  // scores and dP of one 32-query sub-block
+  auto stage_a = [&](const uint16_t* tq, const uint16_t* tg, int sub, f32x16& sa, f32x16& pa) {
+    bf16x8 fq[KS], fg[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      fq[ks] = lds_nat<LD>(tq, 32 * sub + r, ks, hl);
+      fg[ks] = lds_nat<LD>(tg, 32 * sub + r, ks, hl);
+    }
+#pragma unroll
+    for (int v = 0; v < 16; ++v) { sa[v] = 0.f; pa[v] = 0.f; }
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      sa = mfma(fq[ks], kf[ks], sa);
+      pa = mfma(fg[ks], vf[ks], pa);
+    }
+  };
+  // P and dS of one sub-block, as packed bf16 operands
+  auto stage_v = [&](const float* tl, const float* td, int i0, int sub, const f32x16& sa, const f32x16& pa,
+                     const uint2* bz, bf16x8 (&pf)[2], bf16x8 (&df)[2], auto edge_tag) {
+    constexpr bool edge = decltype(edge_tag)::value;
+    float pr[16], ds[16];
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const f32x4 l4 = *(const f32x4*)(tl + 32 * sub + 8 * g + 4 * hl);
+      const f32x4 d4 = *(const f32x4*)(td + 32 * sub + 8 * g + 4 * hl);
+      float bl[4] = {0.f, 0.f, 0.f, 0.f};
+      if (BIAS) {
+        const uint2 u = bz[4 * sub + g];
+        bl[0] = __uint_as_float(u.x << 16) * LOG2E; bl[1] = __uint_as_float(u.x & 0xffff0000u) * LOG2E;
+        bl[2] = __uint_as_float(u.y << 16) * LOG2E; bl[3] = __uint_as_float(u.y & 0xffff0000u) * LOG2E;
+      }
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        float pe = fast_exp2(fmaf(sa[4 * g + e], c1, bl[e] - l4[e]));
+        if (edge) {
+          const int i = i0 + 32 * sub + 8 * g + 4 * hl + e;
+          const bool dead = i >= p.S || key >= p.S || (CAUSAL && key > i);
+          pe = dead ? 0.f : pe;
+        }
+        pr[4 * g + e] = pe;
+        ds[4 * g + e] = pe * (pa[4 * g + e] - d4[e]);
+      }
+    }
+    pf[0] = pack8(&pr[0]); pf[1] = pack8(&pr[8]);
+    df[0] = pack8(&ds[0]); df[1] = pack8(&ds[8]);
+  };
+  // dV += dO^T P, dK += Q^T dS for one sub-block
+  auto stage_b = [&](const uint16_t* tq, const uint16_t* tg, int sub, const bf16x8 (&pf)[2], const bf16x8 (&df)[2]) {
+#pragma unroll
+    for (int hb = 0; hb < 2; ++hb) {
+      bf16x8 tg_[DB], tq_[DB];
+#pragma unroll
+      for (int db = 0; db < DB; ++db) {
+        tg_[db] = lds_tr<LD>(tg, 32 * sub + 16 * hb, 32 * db, lane);
+        tq_[db] = lds_tr<LD>(tq, 32 * sub + 16 * hb, 32 * db, lane);
+      }
+#pragma unroll
+      for (int db = 0; db < DB; ++db) {
+        dv[db] = mfma(tg_[db], pf[hb], dv[db]);
+        dk[db] = mfma(tq_[db], df[hb], dk[db]);
+      }
+    }
+  };
+
+  if (first < ntiles) {
+    gload(first);
+    lstore(first & 1);
+    if (first + 1 < ntiles) gload(first + 1);
+  }
+  for (int qt = first; qt < ntiles; ++qt) {
+    const int i0 = qt * BN;
+    __syncthreads();
+    if (qt + 1 < ntiles) lstore((qt + 1) & 1);
+    if (qt + 2 < ntiles) gload(qt + 2);
+    if (k0 >= p.S || (CAUSAL && i0 + BN - 1 < k0)) continue;  // no visible pair for this wavefront
+    const uint16_t* tq = sQ[qt & 1];
+    const uint16_t* tg = sG[qt & 1];
+    const float* tl = sL[qt & 1];
+    const float* td = sD[qt & 1];
+    const bool edge = (i0 + BN > p.S) || (k0 + 32 > p.S) || (CAUSAL && i0 < k0 + 31);
+    // one straight-line block per tile: A0 | A1 with V0 | B0 with V1 | B1, where A = scores and dP
+    // on the matrix cores, V = P and dS on the vector ALUs, B = gradient products
+    uint2 bz[8];
+    if (BIAS) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) bz[j] = *(const uint2*)(biasT_row + min(i0 + 8 * j + 4 * hl, p.S - 4));
+    }
+    auto tile = [&](auto edge_tag) {
+      f32x16 sa0, pa0, sa1, pa1;
+      bf16x8 pf0[2], df0[2], pf1[2], df1[2];
+      stage_a(tq, tg, 0, sa0, pa0);
+      stage_a(tq, tg, 1, sa1, pa1);
+      stage_v(tl, td, i0, 0, sa0, pa0, bz, pf0, df0, edge_tag);
+      stage_b(tq, tg, 0, pf0, df0);
+      stage_v(tl, td, i0, 1, sa1, pa1, bz, pf1, df1, edge_tag);
+      stage_b(tq, tg, 1, pf1, df1);
+      // A0
+      __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+      for (int j = 0; j < 2 * KS - 4; ++j) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      }
+      __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+      // A1 with V0
+      __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+      for (int j = 0; j < 2 * KS; ++j) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+        __builtin_amdgcn_sched_group_barrier(0x002, 8, 0);
+      }
+      // B0 with V1
+      __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
+      for (int j = 0; j < 4 * DB; ++j) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+        __builtin_amdgcn_sched_group_barrier(0x002, 8, 0);
+      }
+      // B1
+      __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
+      for (int j = 0; j < 4 * DB; ++j) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+      }
+    };
+    if (edge) tile(std::true_type{});
+    else tile(std::false_type{});
+  }
+  if (key >= p.S) return;
+  uint16_t* oK = (uint16_t*)p.dK + base + (int64_t)key * p.ss;
+  uint16_t* oV = (uint16_t*)p.dV + base + (int64_t)key * p.ss;
+#pragma unroll
+  for (int db = 0; db < DB; ++db)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const int d0 = 32 * db + 8 * g + 4 * hl;
+      uint2 a, c;
+      a.x = (uint32_t)f2bf(dk[db][4 * g] * p.scale) | ((uint32_t)f2bf(dk[db][4 * g + 1] * p.scale) << 16);
+      a.y = (uint32_t)f2bf(dk[db][4 * g + 2] * p.scale) | ((uint32_t)f2bf(dk[db][4 * g + 3] * p.scale) << 16);
+      c.x = (uint32_t)f2bf(dv[db][4 * g]) | ((uint32_t)f2bf(dv[db][4 * g + 1]) << 16);
+      c.y = (uint32_t)f2bf(dv[db][4 * g + 2]) | ((uint32_t)f2bf(dv[db][4 * g + 3]) << 16);
+      *(uint2*)(oK + d0) = a;
+      *(uint2*)(oV + d0) = c;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// bias gradient, specialised (dense bf16 bias, no region mask): one wavefront owns a
+// 32-key x 32-query block of one head, keeps the bias and the running sum in registers
+// (lane = query, registers = keys) and walks the chunk's rows in order; the operands
+// of row b+1 are fetched while row b is computed.  Continuing from the stored value
+// on later chunks keeps the order of additions independent of k.
+// ---------------------------------------------------------------------------
+template <int D, bool CAUSAL>
+__global__ __launch_bounds__(256) void dbias_fast_kernel(KP p) {
+  constexpr int KS = D / 16;
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, r = lane & 31, hl = lane >> 5;
+  const BlockId blk = xcd_block_id();  // one head's blocks share an XCD: its rows are fetched into one L2
+  const int h = p.h0 + blk.z;
+  const int q0 = blk.y * 32;
+  const int k0 = (blk.x * 4 + w) * 32;
+  if (k0 >= p.S) return;
+  const int q = q0 + r, qc = min(q, p.S - 1);
+  const int kr = min(k0 + r, p.S - 1);  // key row this lane supplies to the A operands
+  float* dst = p.dbias_acc + ((int64_t)h * p.S + qc) * p.S;
+  if (CAUSAL && k0 > q0 + 31) {  // block entirely above the diagonal: gradient is zero
+    if (!p.dbias_accumulate && q < p.S) {
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int kb = k0 + 8 * g + 4 * hl;
+        if (kb + 3 < p.S) *(f32x4*)(dst + kb) = f32x4{0.f, 0.f, 0.f, 0.f};
+        else for (int e = 0; e < 4; ++e) if (kb + e < p.S) dst[kb + e] = 0.f;
+      }
+    }
+    return;
+  }
+  float acc[16], bz[16];
+#pragma unroll
+  for (int v = 0; v < 16; ++v) {
+    const int k = min(k0 + key_of(v, hl), p.S - 1);
+    acc[v] = p.dbias_accumulate ? dst[k] : 0.f;
+    bz[v] = bf2f(((const uint16_t*)p.bias)[((int64_t)h * p.S + qc) * p.S + k]) * LOG2E;
+  }
+  const float c1 = p.scale * LOG2E;
+  const int64_t row_q = (int64_t)h * p.sh + (int64_t)qc * p.ss;
+  const int64_t row_k = (int64_t)h * p.sh + (int64_t)kr * p.ss;
+  const int64_t row_g = (int64_t)h * p.do_sh + (int64_t)qc * p.do_ss;
+  const int64_t st_off = (int64_t)h * p.lse_sh + qc, dl_off = (int64_t)h * p.dl_sh + qc;
+  constexpr int NS = D <= 32 ? 4 : 2;  // operand slots: rows b+1 .. b+NS-1 are in flight while row b is computed
+  bf16x8 fq[NS][KS], fk[NS][KS], fv[NS][KS], fg[NS][KS];
+  float lse2[NS], dlt[NS];
+  auto fetch = [&](int b, int slot) {
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      const int c = 16 * ks + 8 * hl;
+      fq[slot][ks] = *(const bf16x8*)((const uint16_t*)p.Q + (int64_t)b * p.sb + row_q + c);
+      fk[slot][ks] = *(const bf16x8*)((const uint16_t*)p.K + (int64_t)b * p.sb + row_k + c);
+      fv[slot][ks] = *(const bf16x8*)((const uint16_t*)p.V + (int64_t)b * p.sb + row_k + c);
+      fg[slot][ks] = *(const bf16x8*)((const uint16_t*)p.dO + (int64_t)b * p.do_sb + row_g + c);
+    }
+    lse2[slot] = p.lse[(int64_t)b * p.lse_sb + st_off];  // scaled at use: no arithmetic on in-flight loads
+    dlt[slot] = p.delta[(int64_t)b * p.dl_sb + dl_off];
+  };
+  auto step = [&](int slot, bool valid) {
+    const float lse2s = lse2[slot] * LOG2E;
+    f32x16 sa, pa;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) { sa[v] = 0.f; pa[v] = 0.f; }
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      sa = mfma(fk[slot][ks], fq[slot][ks], sa);
+      pa = mfma(fv[slot][ks], fg[slot][ks], pa);
+    }
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const float e = fast_exp2(fmaf(sa[v], c1, bz[v] - lse2s));
+      float t = valid ? pa[v] - dlt[slot] : 0.f;
+      if (CAUSAL) t = k0 + key_of(v, hl) > q ? 0.f : t;
+      // one explicit fused multiply-add; a padding row contributes e * 0
+      acc[v] = __builtin_fmaf(e, t, acc[v]);
+    }
+  };
+  // rows are taken in groups of NS aligned to multiples of NS of the global row index, row b
+  // always using slot b % NS: a given row passes through the same copy of the arithmetic whatever
+  // the chunk boundaries are; rows of a group outside the chunk are padding rows of weight zero
+  const int bs = p.b0 - p.b0 % NS;
+  auto clampb = [&](int b) { return min(max(b, p.b0), p.b1 - 1); };
+#pragma unroll
+  for (int s_ = 0; s_ < NS - 1; ++s_) fetch(clampb(bs + s_), s_);
+  for (int b = bs; b < p.b1; b += NS) {
+#pragma unroll
+    for (int s_ = 0; s_ < NS; ++s_) {
+      fetch(clampb(b + s_ + NS - 1), (s_ + NS - 1) % NS);
+      step(s_, b + s_ >= p.b0 && b + s_ < p.b1);
+    }
+  }
+  if (q < p.S) {
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const int kb = k0 + 8 * g + 4 * hl;
+      if (kb + 3 < p.S) *(f32x4*)(dst + kb) = f32x4{acc[4 * g], acc[4 * g + 1], acc[4 * g + 2], acc[4 * g + 3]};
+      else for (int e = 0; e < 4; ++e) if (kb + e < p.S) dst[kb + e] = acc[4 * g + e];
+    }
+  }
+}
+
+// biasT[h][j][i] = bias[h][i][j] (bf16), 32x32 tiles through LDS; heads [h0,h1)
+__global__ __launch_bounds__(256) void bias_transpose_kernel(const uint16_t* src, uint16_t* dst, int S, int h0) {
+  __shared__ uint16_t t[32][33];
+  const int h = h0 + blockIdx.z, i0 = blockIdx.y * 32, j0 = blockIdx.x * 32;
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+  for (int y = ty; y < 32; y += 8)
+    if (i0 + y < S && j0 + tx < S) t[y][tx] = src[((int64_t)h * S + i0 + y) * S + j0 + tx];
+  __syncthreads();
+  for (int y = ty; y < 32; y += 8)
+    if (j0 + y < S && i0 + tx < S) dst[((int64_t)h * S + j0 + y) * S + i0 + tx] = t[tx][y];
+}
+
+
+template <int D>
+hipError_t dkdv_d(const KP& p, hipStream_t st) {
+  dim3 g((p.S + 127) / 128, p.h1 - p.h0, p.b1 - p.b0);
+  const bool bias = p.bias_kind == 1, causal = p.mask_kind == 1;
+  if (bias && causal) dkdv_fast_kernel<D, true, true><<<g, 256, 0, st>>>(p);
+  else if (bias) dkdv_fast_kernel<D, true, false><<<g, 256, 0, st>>>(p);
+  else if (causal) dkdv_fast_kernel<D, false, true><<<g, 256, 0, st>>>(p);
+  else dkdv_fast_kernel<D, false, false><<<g, 256, 0, st>>>(p);
+  return hipGetLastError();
+}
+template <int D>
+hipError_t dbias_d(const KP& p, hipStream_t st) {
+  dim3 g((p.S + 127) / 128, (p.S + 31) / 32, p.h1 - p.h0);
+  if (p.mask_kind == 1) dbias_fast_kernel<D, true><<<g, 256, 0, st>>>(p);
+  else dbias_fast_kernel<D, false><<<g, 256, 0, st>>>(p);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+#define SS_FAST_DISPATCH_D(fn, ...)               \
+  switch (p.D) {                                  \
+    case 32: return fn<32>(__VA_ARGS__);          \
+    case 64: return fn<64>(__VA_ARGS__);          \
+    case 128: return fn<128>(__VA_ARGS__);        \
+    default: return hipErrorInvalidValue;         \
+  }
+hipError_t launch_fast_dkdv(const KP& p, hipStream_t st) { SS_FAST_DISPATCH_D(dkdv_d, p, st) }
+hipError_t launch_fast_dbias(const KP& p, hipStream_t st) { SS_FAST_DISPATCH_D(dbias_d, p, st) }
+
+hipError_t launch_bias_transpose(const void* bias, void* biasT, int S, int h0, int h1, hipStream_t st) {
+  dim3 g((S + 31) / 32, (S + 31) / 32, h1 - h0);
+  bias_transpose_kernel<<<g, 256, 0, st>>>((const uint16_t*)bias, (uint16_t*)biasT, S, h0);
+  return hipGetLastError();
+}
+
+}  // namespace ssa

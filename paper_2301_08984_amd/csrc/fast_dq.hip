@@ -1,0 +1,201 @@
+// Specialised dQ kernel (see the comment above the kernel).
+#include "mfma_common.h"
+
+#include <type_traits>
+
+namespace ssa {
+namespace {
+
+// ---------------------------------------------------------------------------
+// dQ, specialised like the forward (dense bf16 bias / causal at compile time, NG key-tile
+// groups).  Q and dO fragments stay in registers; per 32-key block the scores and dP come
+// from the matrix cores, dS from the vector ALUs, and dQ^T += K^T dS^T reads the same K
+// tile transposed.
+// ---------------------------------------------------------------------------
+template <int D, bool BIAS, bool CAUSAL, int NG>
+__global__ __launch_bounds__(256 * NG) __attribute__((amdgpu_waves_per_eu(2, 2))) void dq_fast_kernel(KP p) {
+  constexpr int KS = D / 16, DB = D / 32, NT = 256;
+  constexpr int LDK = D + 16, LDV = D + 8;
+  constexpr int CPR = D / 8, CPT = BN * CPR / NT;
+  constexpr int TILE_ELEMS = BN * LDK + BN * LDV;
+  constexpr int MERGE_ELEMS = NG > 1 ? 256 * (16 * DB) * 2 : 0;
+  constexpr int LDS_ELEMS = NG * TILE_ELEMS > MERGE_ELEMS ? NG * TILE_ELEMS : MERGE_ELEMS;
+  __shared__ __attribute__((aligned(16))) uint16_t smem[LDS_ELEMS];
+  const int tid = threadIdx.x & 255, grp = threadIdx.x >> 8;
+  const int lane = tid & 63, w = tid >> 6, r = lane & 31, hl = lane >> 5;
+  uint16_t* sK = smem + grp * TILE_ELEMS;
+  uint16_t* sV = sK + BN * LDK;
+  const BlockId blk = xcd_block_id();
+  const int h = p.h0 + blk.y, b = p.b0 + blk.z;
+  const int qblk = (gridDim.x - 1 - blk.x) * 128;
+  const int q0 = qblk + 32 * w, q = q0 + r;
+  const int qc = min(q, p.S - 1);
+  const int64_t base = (int64_t)b * p.sb + (int64_t)h * p.sh;
+  const uint16_t* Qb = (const uint16_t*)p.Q + base;
+  const uint16_t* Kb = (const uint16_t*)p.K + base;
+  const uint16_t* Vb = (const uint16_t*)p.V + base;
+  const uint16_t* dOb = (const uint16_t*)p.dO + (int64_t)b * p.do_sb + (int64_t)h * p.do_sh;
+  const uint16_t* bias_row = BIAS ? (const uint16_t*)p.bias + ((int64_t)h * p.S + qc) * p.S : nullptr;
+
+  bf16x8 qf[KS], gf[KS];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) {
+    qf[ks] = *(const bf16x8*)(Qb + (int64_t)qc * p.ss + 16 * ks + 8 * hl);
+    gf[ks] = *(const bf16x8*)(dOb + (int64_t)qc * p.do_ss + 16 * ks + 8 * hl);
+  }
+  const float lse2 = p.lse[(int64_t)b * p.lse_sb + (int64_t)h * p.lse_sh + qc] * LOG2E;
+  const float delta = p.delta[(int64_t)b * p.dl_sb + (int64_t)h * p.dl_sh + qc];
+  f32x16 acc[DB];
+#pragma unroll
+  for (int db = 0; db < DB; ++db)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[db][v] = 0.f;
+  const float c1 = p.scale * LOG2E;
+
+  int ntiles = (p.S + BN - 1) / BN;
+  if (CAUSAL) ntiles = min(ntiles, (min(qblk + 128, p.S) + BN - 1) / BN);
+  int wtiles = ntiles;
+  if (CAUSAL) wtiles = min(ntiles, (min(q0 + 32, p.S) + BN - 1) / BN);
+  if (q0 >= p.S) wtiles = 0;
+
+  u32x4 pk[CPT], pv[CPT];
+  auto gload = [&](int kt) {
+#pragma unroll
+    for (int c = 0; c < CPT; ++c) {
+      const int idx = tid + c * NT, row = min(kt * BN + idx / CPR, p.S - 1), col = (idx % CPR) * 8;
+      pk[c] = *(const u32x4*)(Kb + (int64_t)row * p.ss + col);
+      pv[c] = *(const u32x4*)(Vb + (int64_t)row * p.ss + col);
+    }
+  };
+  if (grp < ntiles) gload(grp);
+  const int nit = (ntiles + NG - 1) / NG;
+  for (int it = 0; it < nit; ++it) {
+    const int kt = it * NG + grp;
+    const int k0 = kt * BN;
+    __syncthreads();
+    if (kt < ntiles) {
+#pragma unroll
+      for (int c = 0; c < CPT; ++c) {
+        const int idx = tid + c * NT, row = idx / CPR, col = (idx % CPR) * 8;
+        *(u32x4*)(sK + row * LDK + col) = pk[c];
+        *(u32x4*)(sV + row * LDV + col) = pv[c];
+      }
+      if (kt + NG < ntiles) gload(kt + NG);
+    }
+    __syncthreads();
+    if (kt >= wtiles) continue;
+    const bool edge = (k0 + BN > p.S) || (CAUSAL && k0 + BN - 1 > q0);
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+      uint2 bz[4];
+      if (BIAS) {
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+          bz[g] = *(const uint2*)(bias_row + min(k0 + 32 * kb + 8 * g + 4 * hl, p.S - 4));
+      }
+      f32x16 sa, pa;
+      {
+        bf16x8 fk[KS], fv[KS];
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+          fk[ks] = lds_nat<LDK>(sK, 32 * kb + r, ks, hl);
+          fv[ks] = lds_nat<LDV>(sV, 32 * kb + r, ks, hl);
+        }
+#pragma unroll
+        for (int v = 0; v < 16; ++v) { sa[v] = 0.f; pa[v] = 0.f; }
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+          sa = mfma(fk[ks], qf[ks], sa);
+          pa = mfma(fv[ks], gf[ks], pa);
+        }
+      }
+      float ds[16];
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        float bl[4] = {0.f, 0.f, 0.f, 0.f};
+        if (BIAS) {
+          bl[0] = __uint_as_float(bz[g].x << 16) * LOG2E; bl[1] = __uint_as_float(bz[g].x & 0xffff0000u) * LOG2E;
+          bl[2] = __uint_as_float(bz[g].y << 16) * LOG2E; bl[3] = __uint_as_float(bz[g].y & 0xffff0000u) * LOG2E;
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          float pe = fast_exp2(fmaf(sa[4 * g + e], c1, bl[e] - lse2));
+          if (edge) {
+            const int key = k0 + 32 * kb + 8 * g + 4 * hl + e;
+            const bool dead = key >= p.S || (CAUSAL && key > q);
+            pe = dead ? 0.f : pe;
+          }
+          ds[4 * g + e] = pe * (pa[4 * g + e] - delta);
+        }
+      }
+#pragma unroll
+      for (int hb = 0; hb < 2; ++hb) {
+        const bf16x8 df = pack8(&ds[8 * hb]);
+        bf16x8 kt_[DB];
+#pragma unroll
+        for (int db = 0; db < DB; ++db) kt_[db] = lds_tr<LDK>(sK, 32 * kb + 16 * hb, 32 * db, lane);
+#pragma unroll
+        for (int db = 0; db < DB; ++db) acc[db] = mfma(kt_[db], df, acc[db]);
+      }
+    }
+  }
+  if (NG > 1) {
+    float* mb = (float*)smem + (size_t)tid * (16 * DB);
+    __syncthreads();
+    if (grp == 1) {
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) mb[16 * db + v] = acc[db][v];
+    }
+    __syncthreads();
+    if (grp == 1) return;
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[db][v] += mb[16 * db + v];
+  }
+  if (q >= p.S) return;
+  uint16_t* out = (uint16_t*)p.dQ + base + (int64_t)q * p.ss;
+#pragma unroll
+  for (int db = 0; db < DB; ++db)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const int d0 = 32 * db + 8 * g + 4 * hl;
+      uint2 o;
+      o.x = (uint32_t)f2bf(acc[db][4 * g] * p.scale) | ((uint32_t)f2bf(acc[db][4 * g + 1] * p.scale) << 16);
+      o.y = (uint32_t)f2bf(acc[db][4 * g + 2] * p.scale) | ((uint32_t)f2bf(acc[db][4 * g + 3] * p.scale) << 16);
+      *(uint2*)(out + d0) = o;
+    }
+}
+
+template <int D, int NG>
+void dq_fast_launch(const KP& p, dim3 g, hipStream_t st) {
+  const bool bias = p.bias_kind == 1, causal = p.mask_kind == 1;
+  if (bias && causal) dq_fast_kernel<D, true, true, NG><<<g, 256 * NG, 0, st>>>(p);
+  else if (bias) dq_fast_kernel<D, true, false, NG><<<g, 256 * NG, 0, st>>>(p);
+  else if (causal) dq_fast_kernel<D, false, true, NG><<<g, 256 * NG, 0, st>>>(p);
+  else dq_fast_kernel<D, false, false, NG><<<g, 256 * NG, 0, st>>>(p);
+}
+
+
+template <int D>
+hipError_t dq_d(const KP& p, hipStream_t st) {
+  dim3 g((p.S + 127) / 128, p.h1 - p.h0, p.b1 - p.b0);
+  if (use_two_groups(p)) dq_fast_launch<D, 2>(p, g, st);
+  else dq_fast_launch<D, 1>(p, g, st);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+#define SS_FAST_DISPATCH_D(fn, ...)               \
+  switch (p.D) {                                  \
+    case 32: return fn<32>(__VA_ARGS__);          \
+    case 64: return fn<64>(__VA_ARGS__);          \
+    case 128: return fn<128>(__VA_ARGS__);        \
+    default: return hipErrorInvalidValue;         \
+  }
+hipError_t launch_fast_dq(const KP& p, hipStream_t st) { SS_FAST_DISPATCH_D(dq_d, p, st) }
+
+}  // namespace ssa

@@ -1,0 +1,267 @@
+// Specialised forward / recompute kernel (see the comment above the kernel).
+#include "mfma_common.h"
+
+#include <type_traits>
+
+namespace ssa {
+namespace {
+
+// ---------------------------------------------------------------------------
+// forward / recompute, specialised at compile time on the presence of a dense bf16
+// bias and of the causal mask.  The inner loop is straight-line code: loads are
+// clamped instead of guarded, and tiles that need no per-element masking (all keys
+// below the causal diagonal and inside S) take a path without compares.
+//
+// NG = 2 doubles the work-group to eight wavefronts: group g takes the key tiles
+// kt = g, g+2, ... with its own LDS tiles and its own (O, m, l); the two partial
+// softmax results are merged through LDS at the end.  Two wavefronts then share
+// every SIMD, so one's softmax arithmetic overlaps the other's matrix products,
+// and the serial chain of key tiles per wavefront is half as long.  It is chosen
+// from the size of the whole share, never from the chunk, so results do not
+// depend on k.
+// ---------------------------------------------------------------------------
+template <int D, bool BIAS, bool CAUSAL, bool RECOMP, int NG>
+__global__ __launch_bounds__(256 * NG) __attribute__((amdgpu_waves_per_eu(2, 2))) void fwd_fast_kernel(KP p) {
+  constexpr int KS = D / 16, DB = D / 32, NT = 256;
+  constexpr int LDK = D + 8, LDV = D + 16;  // row pads chosen for conflict-free b128 / transpose reads
+  constexpr int CPR = D / 8, CPT = BN * CPR / NT;
+  constexpr int TILE_ELEMS = BN * LDK + BN * LDV;
+  constexpr int MERGE_ELEMS = NG > 1 ? 256 * (16 * DB + 2) * 2 : 0;  // in uint16 units
+  constexpr int LDS_ELEMS = NG * TILE_ELEMS > MERGE_ELEMS ? NG * TILE_ELEMS : MERGE_ELEMS;
+  __shared__ __attribute__((aligned(16))) uint16_t smem[LDS_ELEMS];
+  const int tid = threadIdx.x & 255, grp = threadIdx.x >> 8;
+  const int lane = tid & 63, w = tid >> 6, r = lane & 31, hl = lane >> 5;
+  uint16_t* sK = smem + grp * TILE_ELEMS;
+  uint16_t* sV = sK + BN * LDK;
+  const BlockId blk = xcd_block_id();
+  const int h = p.h0 + blk.y, b = p.b0 + blk.z;
+  const int qblk = (gridDim.x - 1 - blk.x) * 128;  // long (late) causal blocks first
+  const int q0 = qblk + 32 * w, q = q0 + r;
+  const int qc = min(q, p.S - 1);
+  const int64_t base = (int64_t)b * p.sb + (int64_t)h * p.sh;
+  const uint16_t* Qb = (const uint16_t*)p.Q + base;
+  const uint16_t* Kb = (const uint16_t*)p.K + base;
+  const uint16_t* Vb = (const uint16_t*)p.V + base;
+  const uint16_t* bias_row = BIAS ? (const uint16_t*)p.bias + ((int64_t)h * p.S + qc) * p.S : nullptr;
+
+  bf16x8 qf[KS];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) qf[ks] = *(const bf16x8*)(Qb + (int64_t)qc * p.ss + 16 * ks + 8 * hl);
+  f32x16 oacc[DB];
+#pragma unroll
+  for (int db = 0; db < DB; ++db)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) oacc[db][v] = 0.f;
+  float m = -1e30f, l = 0.f;
+  const float c1 = p.scale * LOG2E;
+
+  int ntiles = (p.S + BN - 1) / BN;
+  if (CAUSAL) ntiles = min(ntiles, (min(qblk + 128, p.S) + BN - 1) / BN);
+  int wtiles = ntiles;  // tiles holding at least one key visible to this wavefront
+  if (CAUSAL) wtiles = min(ntiles, (min(q0 + 32, p.S) + BN - 1) / BN);
+  if (q0 >= p.S) wtiles = 0;
+
+  u32x4 pk[CPT], pv[CPT];
+  auto gload = [&](int kt) {
+#pragma unroll
+    for (int c = 0; c < CPT; ++c) {
+      const int idx = tid + c * NT, row = min(kt * BN + idx / CPR, p.S - 1), col = (idx % CPR) * 8;
+      pk[c] = *(const u32x4*)(Kb + (int64_t)row * p.ss + col);
+      pv[c] = *(const u32x4*)(Vb + (int64_t)row * p.ss + col);
+    }
+  };
+  if (grp < ntiles) gload(grp);
+  const int nit = (ntiles + NG - 1) / NG;
+  for (int it = 0; it < nit; ++it) {
+    const int kt = it * NG + grp;
+    const int k0 = kt * BN;
+    __syncthreads();
+    if (kt < ntiles) {
+#pragma unroll
+      for (int c = 0; c < CPT; ++c) {
+        const int idx = tid + c * NT, row = idx / CPR, col = (idx % CPR) * 8;
+        *(u32x4*)(sK + row * LDK + col) = pk[c];
+        *(u32x4*)(sV + row * LDV + col) = pv[c];
+      }
+      if (kt + NG < ntiles) gload(kt + NG);
+    }
+    __syncthreads();
+    if (kt >= wtiles) continue;
+    uint2 bz[8];
+    if (BIAS) {
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+          bz[4 * kb + g] = *(const uint2*)(bias_row + min(k0 + 32 * kb + 8 * g + 4 * hl, p.S - 4));
+    }
+    f32x16 sa[2];
+    {
+      // operand reads run ahead of the matrix cores; the two score blocks alternate so that
+      // consecutive MFMAs never wait on each other's accumulator
+      bf16x8 fa[KS], fb[KS];
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        fa[ks] = lds_nat<LDK>(sK, r, ks, hl);
+        fb[ks] = lds_nat<LDK>(sK, 32 + r, ks, hl);
+      }
+#pragma unroll
+      for (int v = 0; v < 16; ++v) { sa[0][v] = 0.f; sa[1][v] = 0.f; }
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        sa[0] = mfma(fa[ks], qf[ks], sa[0]);
+        sa[1] = mfma(fb[ks], qf[ks], sa[1]);
+      }
+      __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+#pragma unroll
+      for (int j = 0; j < 2 * KS - 4; ++j) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      }
+      __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+    }
+    const bool edge = (k0 + BN > p.S) || (CAUSAL && k0 + BN - 1 > q0);
+    if (BIAS) {
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const uint2 u = bz[4 * kb + g];
+          sa[kb][4 * g + 0] = fmaf(sa[kb][4 * g + 0], c1, __uint_as_float(u.x << 16) * LOG2E);
+          sa[kb][4 * g + 1] = fmaf(sa[kb][4 * g + 1], c1, __uint_as_float(u.x & 0xffff0000u) * LOG2E);
+          sa[kb][4 * g + 2] = fmaf(sa[kb][4 * g + 2], c1, __uint_as_float(u.y << 16) * LOG2E);
+          sa[kb][4 * g + 3] = fmaf(sa[kb][4 * g + 3], c1, __uint_as_float(u.y & 0xffff0000u) * LOG2E);
+        }
+    }
+    if (edge) {
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int key = k0 + 32 * kb + key_of(v, hl);
+          const bool dead = key >= p.S || (CAUSAL && key > q);
+          sa[kb][v] = dead ? -INFINITY : sa[kb][v];
+        }
+    }
+    float rmax = -INFINITY;
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) rmax = fmaxf(rmax, sa[kb][v]);
+    if (!BIAS) rmax *= c1;  // scale > 0 on this path
+    rmax = half_max(rmax);
+    // the running maximum is raised only when exceeded by more than 2^8, so the O rescale is
+    // skipped on most tiles; probabilities stay below 2^8, harmless in fp32/bf16 range
+    if (__builtin_amdgcn_ballot_w64(rmax > m + 8.f) != 0) {
+      const float mn = fmaxf(m, rmax);
+      const float alpha = fast_exp2(m - mn);
+      m = mn;
+      l *= alpha;
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) oacc[db][v] *= alpha;
+    }
+    float lsum = 0.f;
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        sa[kb][v] = BIAS ? fast_exp2(sa[kb][v] - m) : fast_exp2(fmaf(sa[kb][v], c1, -m));
+        lsum += sa[kb][v];
+      }
+    l += lsum;
+    {
+      bf16x8 pf[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        float tmp[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) tmp[e] = sa[j >> 1][8 * (j & 1) + e];
+        pf[j] = pack8(tmp);
+      }
+      // V^T fragments of step j+1 are fetched while step j multiplies
+      bf16x8 vf[2][DB];
+#pragma unroll
+      for (int db = 0; db < DB; ++db) vf[0][db] = lds_tr<LDV>(sV, 0, 32 * db, lane);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        if (j + 1 < 4) {
+#pragma unroll
+          for (int db = 0; db < DB; ++db) vf[(j + 1) & 1][db] = lds_tr<LDV>(sV, 16 * (j + 1), 32 * db, lane);
+        }
+#pragma unroll
+        for (int db = 0; db < DB; ++db) oacc[db] = mfma(vf[j & 1][db], pf[j], oacc[db]);
+      }
+      __builtin_amdgcn_sched_group_barrier(0x100, 2 * DB, 1);
+#pragma unroll
+      for (int j = 0; j < 3 * DB; ++j) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 1);
+        __builtin_amdgcn_sched_group_barrier(0x100, 2, 1);
+      }
+      __builtin_amdgcn_sched_group_barrier(0x008, DB, 1);
+    }
+  }
+  if (NG > 1) {
+    // merge the two groups' partial softmax results; group 1 hands (O, m, l) to group 0
+    float* mb = (float*)smem + (size_t)tid * (16 * DB + 2);
+    __syncthreads();
+    if (grp == 1) {
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) mb[16 * db + v] = oacc[db][v];
+      mb[16 * DB] = m;
+      mb[16 * DB + 1] = l;
+    }
+    __syncthreads();
+    if (grp == 1) return;
+    const float m1 = mb[16 * DB], l1 = mb[16 * DB + 1];
+    const float mn = fmaxf(m, m1);
+    const float a0 = fast_exp2(m - mn), a1 = fast_exp2(m1 - mn);
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) oacc[db][v] = oacc[db][v] * a0 + mb[16 * db + v] * a1;
+    l = l * a0 + l1 * a1;
+    m = mn;
+  }
+  if (q >= p.S) return;
+  fwd_epilogue<DB, RECOMP>(p, oacc, m, l, b, h, q, hl, base);
+}
+
+template <int D, bool RECOMP, int NG>
+void fwd_fast_launch(const KP& p, dim3 g, hipStream_t st) {
+  const bool bias = p.bias_kind == 1, causal = p.mask_kind == 1;
+  if (bias && causal) fwd_fast_kernel<D, true, true, RECOMP, NG><<<g, 256 * NG, 0, st>>>(p);
+  else if (bias) fwd_fast_kernel<D, true, false, RECOMP, NG><<<g, 256 * NG, 0, st>>>(p);
+  else if (causal) fwd_fast_kernel<D, false, true, RECOMP, NG><<<g, 256 * NG, 0, st>>>(p);
+  else fwd_fast_kernel<D, false, false, RECOMP, NG><<<g, 256 * NG, 0, st>>>(p);
+}
+
+
+template <int D>
+hipError_t fwd_d(const KP& p, bool recompute, hipStream_t st) {
+  dim3 g((p.S + 127) / 128, p.h1 - p.h0, p.b1 - p.b0);
+  if (use_two_groups(p)) {
+    if (recompute) fwd_fast_launch<D, true, 2>(p, g, st);
+    else fwd_fast_launch<D, false, 2>(p, g, st);
+  } else {
+    if (recompute) fwd_fast_launch<D, true, 1>(p, g, st);
+    else fwd_fast_launch<D, false, 1>(p, g, st);
+  }
+  return hipGetLastError();
+}
+
+}  // namespace
+
+#define SS_FAST_DISPATCH_D(fn, ...)               \
+  switch (p.D) {                                  \
+    case 32: return fn<32>(__VA_ARGS__);          \
+    case 64: return fn<64>(__VA_ARGS__);          \
+    case 128: return fn<128>(__VA_ARGS__);        \
+    default: return hipErrorInvalidValue;         \
+  }
+hipError_t launch_fast_fwd(const KP& p, bool recompute, hipStream_t st) { SS_FAST_DISPATCH_D(fwd_d, p, recompute, st) }
+
+}  // namespace ssa

@@ -177,5 +177,27 @@ __device__ inline void fwd_epilogue(const KP& p, f32x16 (&oacc)[DB], float m, fl
   }
 }
 
+// the specialised kernels serve: no bias or a dense bf16 bias with S % 4 == 0; no mask or the
+// causal mask; a positive scale; more than one 64-key tile's worth of rows
+inline bool fast_ok(const KP& p) {
+  if (p.S <= 64 || !(p.scale > 0.f) || p.mask_kind == 2 || p.bias_kind == 2) return false;
+  if (p.bias_kind == 1 && (!p.bias_bf16 || (p.S & 3))) return false;
+  return true;
+}
+
+// eight-wavefront work-groups (two key-tile groups) when the whole share offers fewer
+// work-groups than two per compute unit and there are enough key tiles to split
+inline bool use_two_groups(const KP& p) {
+  const int64_t wgs = (int64_t)((p.S + 127) / 128) * p.share_units;
+  return wgs < 512 && p.S >= 512;
+}
+
 }  // namespace
+
+// specialised kernels, one translation unit each
+hipError_t launch_fast_fwd(const KP& p, bool recompute, hipStream_t st);
+hipError_t launch_fast_dq(const KP& p, hipStream_t st);
+hipError_t launch_fast_dkdv(const KP& p, hipStream_t st);
+hipError_t launch_fast_dbias(const KP& p, hipStream_t st);
+
 }  // namespace ssa
