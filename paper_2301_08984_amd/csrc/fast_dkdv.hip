@@ -15,9 +15,9 @@ namespace {
 // Q / dO tiles (64 rows) are double-buffered in LDS, one barrier per tile; the next
 // tile travels global -> registers meanwhile.
 // ---------------------------------------------------------------------------
-template <int D, bool BIAS, bool CAUSAL>
-__global__ __launch_bounds__(256) void dkdv_fast_kernel(KP p) {
-  constexpr int KS = D / 16, DB = D / 32, LD = D + 16, NT = 256;
+template <int D, bool BIAS, bool CAUSAL, int NW>
+__global__ __launch_bounds__(64 * NW) void dkdv_fast_kernel(KP p) {
+  constexpr int KS = D / 16, DB = D / 32, LD = D + 16, NT = 64 * NW, BK = 32 * NW;
   constexpr int CPR = D / 8, CPT = BN * CPR / NT;
   __shared__ __attribute__((aligned(16))) uint16_t sQ[2][BN * LD];
   __shared__ __attribute__((aligned(16))) uint16_t sG[2][BN * LD];
@@ -26,7 +26,7 @@ __global__ __launch_bounds__(256) void dkdv_fast_kernel(KP p) {
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, r = lane & 31, hl = lane >> 5;
   const BlockId blk = xcd_block_id();
   const int h = p.h0 + blk.y, b = p.b0 + blk.z;
-  const int kblk = blk.x * 128;  // early key blocks see the most queries under a causal mask
+  const int kblk = blk.x * BK;  // early key blocks see the most queries under a causal mask
   const int k0 = kblk + 32 * w, key = k0 + r;
   const int kc = min(key, p.S - 1);
   const int64_t base = (int64_t)b * p.sb + (int64_t)h * p.sh;
@@ -336,14 +336,20 @@ __global__ __launch_bounds__(256) void bias_transpose_kernel(const uint16_t* src
 }
 
 
+template <int D, int NW>
+void dkdv_fast_launch(const KP& p, hipStream_t st) {
+  const dim3 g((p.S + 32 * NW - 1) / (32 * NW), p.h1 - p.h0, p.b1 - p.b0);
+  const bool bias = p.bias_kind == 1, causal = p.mask_kind == 1;
+  if (bias && causal) dkdv_fast_kernel<D, true, true, NW><<<g, 64 * NW, 0, st>>>(p);
+  else if (bias) dkdv_fast_kernel<D, true, false, NW><<<g, 64 * NW, 0, st>>>(p);
+  else if (causal) dkdv_fast_kernel<D, false, true, NW><<<g, 64 * NW, 0, st>>>(p);
+  else dkdv_fast_kernel<D, false, false, NW><<<g, 64 * NW, 0, st>>>(p);
+}
 template <int D>
 hipError_t dkdv_d(const KP& p, hipStream_t st) {
-  dim3 g((p.S + 127) / 128, p.h1 - p.h0, p.b1 - p.b0);
-  const bool bias = p.bias_kind == 1, causal = p.mask_kind == 1;
-  if (bias && causal) dkdv_fast_kernel<D, true, true><<<g, 256, 0, st>>>(p);
-  else if (bias) dkdv_fast_kernel<D, true, false><<<g, 256, 0, st>>>(p);
-  else if (causal) dkdv_fast_kernel<D, false, true><<<g, 256, 0, st>>>(p);
-  else dkdv_fast_kernel<D, false, false><<<g, 256, 0, st>>>(p);
+  // small shares: 64-key work-groups, so that twice as many compute units get one
+  if (wg_shape(p) == WG_2x4) dkdv_fast_launch<D, 2>(p, st);
+  else dkdv_fast_launch<D, 4>(p, st);
   return hipGetLastError();
 }
 template <int D>

@@ -12,22 +12,22 @@ namespace {
 // from the matrix cores, dS from the vector ALUs, and dQ^T += K^T dS^T reads the same K
 // tile transposed.
 // ---------------------------------------------------------------------------
-template <int D, bool BIAS, bool CAUSAL, int NG>
-__global__ __launch_bounds__(256 * NG) __attribute__((amdgpu_waves_per_eu(2, 2))) void dq_fast_kernel(KP p) {
-  constexpr int KS = D / 16, DB = D / 32, NT = 256;
+template <int D, bool BIAS, bool CAUSAL, int QW, int NG>
+__global__ __launch_bounds__(64 * QW * NG) __attribute__((amdgpu_waves_per_eu(2, 2))) void dq_fast_kernel(KP p) {
+  constexpr int KS = D / 16, DB = D / 32, NT = 64 * QW, BM = 32 * QW;
   constexpr int LDK = D + 16, LDV = D + 8;
   constexpr int CPR = D / 8, CPT = BN * CPR / NT;
   constexpr int TILE_ELEMS = BN * LDK + BN * LDV;
-  constexpr int MERGE_ELEMS = NG > 1 ? 256 * (16 * DB) * 2 : 0;
+  constexpr int MERGE_ELEMS = NT * (16 * DB) * 2 * (NG - 1);
   constexpr int LDS_ELEMS = NG * TILE_ELEMS > MERGE_ELEMS ? NG * TILE_ELEMS : MERGE_ELEMS;
   __shared__ __attribute__((aligned(16))) uint16_t smem[LDS_ELEMS];
-  const int tid = threadIdx.x & 255, grp = threadIdx.x >> 8;
+  const int tid = threadIdx.x % NT, grp = threadIdx.x / NT;
   const int lane = tid & 63, w = tid >> 6, r = lane & 31, hl = lane >> 5;
   uint16_t* sK = smem + grp * TILE_ELEMS;
   uint16_t* sV = sK + BN * LDK;
   const BlockId blk = xcd_block_id();
   const int h = p.h0 + blk.y, b = p.b0 + blk.z;
-  const int qblk = (gridDim.x - 1 - blk.x) * 128;
+  const int qblk = (gridDim.x - 1 - blk.x) * BM;
   const int q0 = qblk + 32 * w, q = q0 + r;
   const int qc = min(q, p.S - 1);
   const int64_t base = (int64_t)b * p.sb + (int64_t)h * p.sh;
@@ -53,7 +53,7 @@ __global__ __launch_bounds__(256 * NG) __attribute__((amdgpu_waves_per_eu(2, 2))
   const float c1 = p.scale * LOG2E;
 
   int ntiles = (p.S + BN - 1) / BN;
-  if (CAUSAL) ntiles = min(ntiles, (min(qblk + 128, p.S) + BN - 1) / BN);
+  if (CAUSAL) ntiles = min(ntiles, (min(qblk + BM, p.S) + BN - 1) / BN);
   int wtiles = ntiles;
   if (CAUSAL) wtiles = min(ntiles, (min(q0 + 32, p.S) + BN - 1) / BN);
   if (q0 >= p.S) wtiles = 0;
@@ -140,20 +140,25 @@ __global__ __launch_bounds__(256 * NG) __attribute__((amdgpu_waves_per_eu(2, 2))
     }
   }
   if (NG > 1) {
+    // groups 1.. hand their partial dQ to group 0, which adds them in group order
+    constexpr int SLOT = NT * 16 * DB;
     float* mb = (float*)smem + (size_t)tid * (16 * DB);
     __syncthreads();
-    if (grp == 1) {
+    if (grp > 0) {
+      float* my = mb + (size_t)(grp - 1) * SLOT;
 #pragma unroll
       for (int db = 0; db < DB; ++db)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) mb[16 * db + v] = acc[db][v];
+        for (int v = 0; v < 16; ++v) my[16 * db + v] = acc[db][v];
     }
     __syncthreads();
-    if (grp == 1) return;
+    if (grp > 0) return;
 #pragma unroll
-    for (int db = 0; db < DB; ++db)
+    for (int g = 1; g < NG; ++g)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) acc[db][v] += mb[16 * db + v];
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[db][v] += mb[(size_t)(g - 1) * SLOT + 16 * db + v];
   }
   if (q >= p.S) return;
   uint16_t* out = (uint16_t*)p.dQ + base + (int64_t)q * p.ss;
@@ -169,21 +174,23 @@ __global__ __launch_bounds__(256 * NG) __attribute__((amdgpu_waves_per_eu(2, 2))
     }
 }
 
-template <int D, int NG>
-void dq_fast_launch(const KP& p, dim3 g, hipStream_t st) {
+template <int D, int QW, int NG>
+void dq_fast_launch(const KP& p, hipStream_t st) {
+  const dim3 g((p.S + 32 * QW - 1) / (32 * QW), p.h1 - p.h0, p.b1 - p.b0);
   const bool bias = p.bias_kind == 1, causal = p.mask_kind == 1;
-  if (bias && causal) dq_fast_kernel<D, true, true, NG><<<g, 256 * NG, 0, st>>>(p);
-  else if (bias) dq_fast_kernel<D, true, false, NG><<<g, 256 * NG, 0, st>>>(p);
-  else if (causal) dq_fast_kernel<D, false, true, NG><<<g, 256 * NG, 0, st>>>(p);
-  else dq_fast_kernel<D, false, false, NG><<<g, 256 * NG, 0, st>>>(p);
+  if (bias && causal) dq_fast_kernel<D, true, true, QW, NG><<<g, 64 * QW * NG, 0, st>>>(p);
+  else if (bias) dq_fast_kernel<D, true, false, QW, NG><<<g, 64 * QW * NG, 0, st>>>(p);
+  else if (causal) dq_fast_kernel<D, false, true, QW, NG><<<g, 64 * QW * NG, 0, st>>>(p);
+  else dq_fast_kernel<D, false, false, QW, NG><<<g, 64 * QW * NG, 0, st>>>(p);
 }
-
 
 template <int D>
 hipError_t dq_d(const KP& p, hipStream_t st) {
-  dim3 g((p.S + 127) / 128, p.h1 - p.h0, p.b1 - p.b0);
-  if (use_two_groups(p)) dq_fast_launch<D, 2>(p, g, st);
-  else dq_fast_launch<D, 1>(p, g, st);
+  switch (wg_shape(p)) {
+    case WG_4x2: dq_fast_launch<D, 4, 2>(p, st); break;
+    case WG_2x4: dq_fast_launch<D, 2, 4>(p, st); break;
+    default: dq_fast_launch<D, 4, 1>(p, st); break;
+  }
   return hipGetLastError();
 }
 

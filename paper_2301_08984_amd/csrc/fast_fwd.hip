@@ -12,30 +12,32 @@ namespace {
 // clamped instead of guarded, and tiles that need no per-element masking (all keys
 // below the causal diagonal and inside S) take a path without compares.
 //
-// NG = 2 doubles the work-group to eight wavefronts: group g takes the key tiles
-// kt = g, g+2, ... with its own LDS tiles and its own (O, m, l); the two partial
-// softmax results are merged through LDS at the end.  Two wavefronts then share
-// every SIMD, so one's softmax arithmetic overlaps the other's matrix products,
-// and the serial chain of key tiles per wavefront is half as long.  It is chosen
-// from the size of the whole share, never from the chunk, so results do not
-// depend on k.
+// A work-group is QW query wavefronts (32 queries each) times NG key-tile groups:
+// group g takes the key tiles kt = g, g+NG, ... with its own LDS tiles and its own
+// (O, m, l); the partial softmax results are merged through LDS at the end, in
+// group order.  With NG > 1 two wavefronts share every SIMD, so one's softmax
+// arithmetic overlaps the other's matrix products, and the serial chain of key
+// tiles per wavefront is NG times shorter; small shares use fewer query wavefronts
+// and more groups so that more compute units get a work-group.  The shape is
+// chosen from the size of the whole share, never from the chunk, so results do
+// not depend on k.
 // ---------------------------------------------------------------------------
-template <int D, bool BIAS, bool CAUSAL, bool RECOMP, int NG>
-__global__ __launch_bounds__(256 * NG) __attribute__((amdgpu_waves_per_eu(2, 2))) void fwd_fast_kernel(KP p) {
-  constexpr int KS = D / 16, DB = D / 32, NT = 256;
+template <int D, bool BIAS, bool CAUSAL, bool RECOMP, int QW, int NG>
+__global__ __launch_bounds__(64 * QW * NG) __attribute__((amdgpu_waves_per_eu(2, 2))) void fwd_fast_kernel(KP p) {
+  constexpr int KS = D / 16, DB = D / 32, NT = 64 * QW, BM = 32 * QW;
   constexpr int LDK = D + 8, LDV = D + 16;  // row pads chosen for conflict-free b128 / transpose reads
   constexpr int CPR = D / 8, CPT = BN * CPR / NT;
   constexpr int TILE_ELEMS = BN * LDK + BN * LDV;
-  constexpr int MERGE_ELEMS = NG > 1 ? 256 * (16 * DB + 2) * 2 : 0;  // in uint16 units
+  constexpr int MERGE_ELEMS = NT * (16 * DB + 2) * 2 * (NG - 1);  // in uint16 units
   constexpr int LDS_ELEMS = NG * TILE_ELEMS > MERGE_ELEMS ? NG * TILE_ELEMS : MERGE_ELEMS;
   __shared__ __attribute__((aligned(16))) uint16_t smem[LDS_ELEMS];
-  const int tid = threadIdx.x & 255, grp = threadIdx.x >> 8;
+  const int tid = threadIdx.x % NT, grp = threadIdx.x / NT;
   const int lane = tid & 63, w = tid >> 6, r = lane & 31, hl = lane >> 5;
   uint16_t* sK = smem + grp * TILE_ELEMS;
   uint16_t* sV = sK + BN * LDK;
   const BlockId blk = xcd_block_id();
   const int h = p.h0 + blk.y, b = p.b0 + blk.z;
-  const int qblk = (gridDim.x - 1 - blk.x) * 128;  // long (late) causal blocks first
+  const int qblk = (gridDim.x - 1 - blk.x) * BM;  // long (late) causal blocks first
   const int q0 = qblk + 32 * w, q = q0 + r;
   const int qc = min(q, p.S - 1);
   const int64_t base = (int64_t)b * p.sb + (int64_t)h * p.sh;
@@ -56,7 +58,7 @@ __global__ __launch_bounds__(256 * NG) __attribute__((amdgpu_waves_per_eu(2, 2))
   const float c1 = p.scale * LOG2E;
 
   int ntiles = (p.S + BN - 1) / BN;
-  if (CAUSAL) ntiles = min(ntiles, (min(qblk + 128, p.S) + BN - 1) / BN);
+  if (CAUSAL) ntiles = min(ntiles, (min(qblk + BM, p.S) + BN - 1) / BN);
   int wtiles = ntiles;  // tiles holding at least one key visible to this wavefront
   if (CAUSAL) wtiles = min(ntiles, (min(q0 + 32, p.S) + BN - 1) / BN);
   if (q0 >= p.S) wtiles = 0;
@@ -203,54 +205,62 @@ __global__ __launch_bounds__(256 * NG) __attribute__((amdgpu_waves_per_eu(2, 2))
     }
   }
   if (NG > 1) {
-    // merge the two groups' partial softmax results; group 1 hands (O, m, l) to group 0
+    // merge the groups' partial softmax results: groups 1.. hand (O, m, l) to group 0, which folds
+    // them in group order
+    constexpr int SLOT = NT * (16 * DB + 2);
     float* mb = (float*)smem + (size_t)tid * (16 * DB + 2);
     __syncthreads();
-    if (grp == 1) {
+    if (grp > 0) {
+      float* my = mb + (size_t)(grp - 1) * SLOT;
 #pragma unroll
       for (int db = 0; db < DB; ++db)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) mb[16 * db + v] = oacc[db][v];
-      mb[16 * DB] = m;
-      mb[16 * DB + 1] = l;
+        for (int v = 0; v < 16; ++v) my[16 * db + v] = oacc[db][v];
+      my[16 * DB] = m;
+      my[16 * DB + 1] = l;
     }
     __syncthreads();
-    if (grp == 1) return;
-    const float m1 = mb[16 * DB], l1 = mb[16 * DB + 1];
-    const float mn = fmaxf(m, m1);
-    const float a0 = fast_exp2(m - mn), a1 = fast_exp2(m1 - mn);
+    if (grp > 0) return;
 #pragma unroll
-    for (int db = 0; db < DB; ++db)
+    for (int g = 1; g < NG; ++g) {
+      const float* o = mb + (size_t)(g - 1) * SLOT;
+      const float m1 = o[16 * DB], l1 = o[16 * DB + 1];
+      const float mn = fmaxf(m, m1);
+      const float a0 = fast_exp2(m - mn), a1 = fast_exp2(m1 - mn);
 #pragma unroll
-      for (int v = 0; v < 16; ++v) oacc[db][v] = oacc[db][v] * a0 + mb[16 * db + v] * a1;
-    l = l * a0 + l1 * a1;
-    m = mn;
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) oacc[db][v] = oacc[db][v] * a0 + o[16 * db + v] * a1;
+      l = l * a0 + l1 * a1;
+      m = mn;
+    }
   }
   if (q >= p.S) return;
   fwd_epilogue<DB, RECOMP>(p, oacc, m, l, b, h, q, hl, base);
 }
 
-template <int D, bool RECOMP, int NG>
-void fwd_fast_launch(const KP& p, dim3 g, hipStream_t st) {
+template <int D, bool RECOMP, int QW, int NG>
+void fwd_fast_launch(const KP& p, hipStream_t st) {
+  const dim3 g((p.S + 32 * QW - 1) / (32 * QW), p.h1 - p.h0, p.b1 - p.b0);
   const bool bias = p.bias_kind == 1, causal = p.mask_kind == 1;
-  if (bias && causal) fwd_fast_kernel<D, true, true, RECOMP, NG><<<g, 256 * NG, 0, st>>>(p);
-  else if (bias) fwd_fast_kernel<D, true, false, RECOMP, NG><<<g, 256 * NG, 0, st>>>(p);
-  else if (causal) fwd_fast_kernel<D, false, true, RECOMP, NG><<<g, 256 * NG, 0, st>>>(p);
-  else fwd_fast_kernel<D, false, false, RECOMP, NG><<<g, 256 * NG, 0, st>>>(p);
+  if (bias && causal) fwd_fast_kernel<D, true, true, RECOMP, QW, NG><<<g, 64 * QW * NG, 0, st>>>(p);
+  else if (bias) fwd_fast_kernel<D, true, false, RECOMP, QW, NG><<<g, 64 * QW * NG, 0, st>>>(p);
+  else if (causal) fwd_fast_kernel<D, false, true, RECOMP, QW, NG><<<g, 64 * QW * NG, 0, st>>>(p);
+  else fwd_fast_kernel<D, false, false, RECOMP, QW, NG><<<g, 64 * QW * NG, 0, st>>>(p);
 }
 
-
-template <int D>
-hipError_t fwd_d(const KP& p, bool recompute, hipStream_t st) {
-  dim3 g((p.S + 127) / 128, p.h1 - p.h0, p.b1 - p.b0);
-  if (use_two_groups(p)) {
-    if (recompute) fwd_fast_launch<D, true, 2>(p, g, st);
-    else fwd_fast_launch<D, false, 2>(p, g, st);
-  } else {
-    if (recompute) fwd_fast_launch<D, true, 1>(p, g, st);
-    else fwd_fast_launch<D, false, 1>(p, g, st);
+template <int D, bool RECOMP>
+hipError_t fwd_r(const KP& p, hipStream_t st) {
+  switch (wg_shape(p)) {
+    case WG_4x2: fwd_fast_launch<D, RECOMP, 4, 2>(p, st); break;
+    case WG_2x4: fwd_fast_launch<D, RECOMP, 2, 4>(p, st); break;
+    default: fwd_fast_launch<D, RECOMP, 4, 1>(p, st); break;
   }
   return hipGetLastError();
+}
+template <int D>
+hipError_t fwd_d(const KP& p, bool recompute, hipStream_t st) {
+  return recompute ? fwd_r<D, true>(p, st) : fwd_r<D, false>(p, st);
 }
 
 }  // namespace

@@ -185,11 +185,16 @@ inline bool fast_ok(const KP& p) {
   return true;
 }
 
-// eight-wavefront work-groups (two key-tile groups) when the whole share offers fewer
-// work-groups than two per compute unit and there are enough key tiles to split
-inline bool use_two_groups(const KP& p) {
+// Work-group shape of the forward / dQ kernels: query wavefronts x key-tile groups.  Large shares
+// use 4x1 (many independent work-groups per compute unit); when the whole share offers fewer than
+// two 128-query work-groups per compute unit the key tiles are split over groups inside the
+// work-group (4x2), and below one per compute unit the work-group also covers fewer queries (2x4).
+// Decided from the share, never from the chunk.
+enum WgShape { WG_4x1, WG_4x2, WG_2x4 };
+inline WgShape wg_shape(const KP& p) {
   const int64_t wgs = (int64_t)((p.S + 127) / 128) * p.share_units;
-  return wgs < 512 && p.S >= 512;
+  if (wgs >= 512 || p.S < 512) return WG_4x1;
+  return wgs >= 256 ? WG_4x2 : WG_2x4;
 }
 
 }  // namespace
