@@ -51,14 +51,16 @@ inline void chunk(const ss_attn_desc* d, int c, int* a, int* b) {
 
 struct WsLayout {
   size_t lse, delta, dO, dense, partial, biasT, total;
-  int g0, ngroups;  // short-sequence path: first global row group of the share, and how many it spans
+  int gw, g0, ngroups;  // grouped bias-gradient sums: rows per group (0: none), first group, group count
 };
 
 constexpr int SMALL_GW = 8;  // rows per bias-gradient group of the short-sequence kernels
 
 enum Family { FAM_PLAIN = 0, FAM_MFMA = 1, FAM_SMALL = 2 };
 
-WsLayout bwd_layout(const ss_attn_desc* d, bool small) {
+KP base_params(const ss_attn_desc* d);
+
+WsLayout bwd_layout(const ss_attn_desc* d, Family fam) {
   const int64_t n = d->hi - d->lo;
   const int64_t nmax = (n + d->k - 1) / d->k;  // largest chunk of the balanced split
   const int64_t Bc = d->shard_axis == SS_AXIS_ROW ? nmax : d->B;
@@ -74,9 +76,17 @@ WsLayout bwd_layout(const ss_attn_desc* d, bool small) {
   w.partial = off;
   const int row_lo = d->shard_axis == SS_AXIS_ROW ? d->lo : 0;
   const int row_hi = d->shard_axis == SS_AXIS_ROW ? d->hi : d->B;
-  w.g0 = row_lo / SMALL_GW;
-  w.ngroups = (row_hi - 1) / SMALL_GW - w.g0 + 1;
-  if (small && d->bias_kind != SS_BIAS_NONE) off += align_up((size_t)w.ngroups * d->H * d->S * d->S * 4);
+  // rows per group: fixed for the short-sequence kernels, shape-dependent for the tiled kernel
+  w.gw = 0;
+  if (d->bias_kind != SS_BIAS_NONE) {
+    if (fam == FAM_SMALL) w.gw = SMALL_GW;
+    else if (fam == FAM_MFMA) w.gw = ssa::mfma_dbias_group_rows(base_params(d));
+  }
+  if (w.gw > 0) {
+    w.g0 = row_lo / w.gw;
+    w.ngroups = (row_hi - 1) / w.gw - w.g0 + 1;
+    off += align_up((size_t)w.ngroups * d->H * d->S * d->S * 4);
+  }
   w.biasT = off;
   if (d->bias_kind == SS_BIAS_DENSE && d->bias_dtype == SS_BF16) off += align_up((size_t)d->H * d->S * d->S * 2);
   w.total = off;
@@ -202,7 +212,7 @@ int ss_attn_workspace_bytes(const ss_attn_desc* d, size_t* fwd_bytes, size_t* bw
   const int rc = validate(d);
   if (rc != SS_OK) return rc;
   if (fwd_bytes) *fwd_bytes = 0;
-  if (bwd_bytes) *bwd_bytes = bwd_layout(d, family_of(d) == FAM_SMALL).total;
+  if (bwd_bytes) *bwd_bytes = bwd_layout(d, family_of(d)).total;
   return SS_OK;
 }
 
@@ -253,7 +263,7 @@ int ss_attn_bwd(const ss_attn_desc* d, const void* Q, const void* K, const void*
   if (d->mask_kind == SS_MASK_REGION && !region_ids) return SS_ERR_NULL;
   if (d->gated && (!G || !dG)) return SS_ERR_NULL;
   const Family fam = family_of(d);
-  const WsLayout w = bwd_layout(d, fam == FAM_SMALL);
+  const WsLayout w = bwd_layout(d, fam);
   if (!workspace || workspace_bytes < w.total || ((uintptr_t)workspace % ALIGN)) return SS_ERR_WORKSPACE;
   hipStream_t st = (hipStream_t)hip_stream;
   const bool bf16 = d->dtype == SS_BF16;
@@ -323,7 +333,21 @@ int ss_attn_bwd(const ss_attn_desc* d, const void* Q, const void* K, const void*
       SS_LAUNCH(SS_K_RECOMPUTE, ssa::launch_mfma_fwd(p, true, st), "recompute");
       SS_LAUNCH(SS_K_DQ, ssa::launch_mfma_dq(p, st), "dQ");
       SS_LAUNCH(SS_K_DKDV, ssa::launch_mfma_dkdv(p, st), "dK/dV");
-      if (want_dbias) SS_LAUNCH(SS_K_DBIAS, ssa::launch_mfma_dbias(p, st), "dBias");
+      if (want_dbias) {
+        if (w.gw > 0) {  // grouped sum: partials in the workspace, reduced after the last chunk that adds to them
+          p.sm_partial = (float*)(ws + w.partial);
+          p.sm_gw = w.gw;
+          p.sm_g0 = w.g0;
+        }
+        SS_LAUNCH(SS_K_DBIAS, ssa::launch_mfma_dbias(p, st), "dBias");
+        if (w.gw > 0 && (d->shard_axis == SS_AXIS_HEAD || c == d->k - 1)) {
+          const int h0 = d->shard_axis == SS_AXIS_HEAD ? p.h0 : 0;
+          const int h1 = d->shard_axis == SS_AXIS_HEAD ? p.h1 : d->H;
+          SS_LAUNCH(SS_K_DBIAS,
+                    ssa::launch_small_group_reduce(p.sm_partial, dense, w.ngroups, d->H, h0, h1, d->S, st),
+                    "bias gradient group reduce");
+        }
+      }
     } else {
       SS_LAUNCH(SS_K_RECOMPUTE, ssa::launch_generic_fwd(p, bf16, true, st), "recompute (generic)");
       SS_LAUNCH(SS_K_DQ, ssa::launch_generic_dq(p, bf16, st), "dQ (generic)");

@@ -323,6 +323,121 @@ __global__ __launch_bounds__(256) void dbias_fast_kernel(KP p) {
   }
 }
 
+// ---------------------------------------------------------------------------
+// bias gradient, LDS-tiled: a work-group owns a 64-query x 64-key tile of one head (four
+// wavefronts, 32x32 each, lane = query) and walks rows in order; every row's Q, dO, K, V
+// slices of the tile are fetched once per work-group with fully coalesced loads, staged in
+// double-buffered LDS, and read by the four wavefronts (a quarter of the cache-line traffic of
+// per-wavefront fetches).  When one head's tiles are too few to fill the chip the rows are
+// cut into groups of p.sm_gw consecutive global rows (grid z): each (group, tile) sums its
+// rows in order into a partial kept in the workspace, resumed when a chunk boundary cuts the
+// group, and the groups are summed in index order afterwards, so the result never depends
+// on k.  With a single group the sum continues directly in the output.
+// ---------------------------------------------------------------------------
+template <int D, bool CAUSAL>
+__global__ __launch_bounds__(256) void dbias_tile_kernel(KP p) {
+  constexpr int KS = D / 16, LD = D + 8, CPR = D / 8;
+  constexpr int CPT = 64 * CPR / 256;  // 16-byte chunks per thread per tensor tile
+  __shared__ __attribute__((aligned(16))) uint16_t sT[2][4][64 * LD];  // Q, dO, K, V
+  __shared__ float sL[2][64], sD[2][64];
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, r = lane & 31, hl = lane >> 5;
+  const int Hc = p.h1 - p.h0;
+  const int h = p.h0 + (int)blockIdx.z % Hc;
+  const int q0t = blockIdx.y * 64, k0t = blockIdx.x * 64;
+  const int wq = w >> 1, wk = w & 1;
+  const int q0 = q0t + 32 * wq, k0 = k0t + 32 * wk;
+  const int q = q0 + r, qc = min(q, p.S - 1);
+  // rows of this work-group: the chunk, or the part of one row group inside the chunk
+  int bfirst = p.b0, blast = p.b1;
+  float* dst;
+  bool resume;
+  if (p.sm_partial) {
+    const int g = p.b0 / p.sm_gw + (int)blockIdx.z / Hc;
+    bfirst = max(g * p.sm_gw, p.b0);
+    blast = min((g + 1) * p.sm_gw, p.b1);
+    dst = p.sm_partial + ((int64_t)(g - p.sm_g0) * p.H + h) * p.S * p.S + (int64_t)qc * p.S;
+    resume = max(g * p.sm_gw, p.share_b0) < p.b0;
+  } else {
+    dst = p.dbias_acc + ((int64_t)h * p.S + qc) * p.S;
+    resume = p.dbias_accumulate != 0;
+  }
+  if (bfirst >= blast) return;
+  const bool skip = CAUSAL && k0t > q0t + 63;  // whole tile above the diagonal: gradient is zero
+  float acc[16], bz[16];
+#pragma unroll
+  for (int v = 0; v < 16; ++v) {
+    const int k = min(k0 + key_of(v, hl), p.S - 1);
+    acc[v] = (resume && !skip) ? dst[k] : 0.f;
+    bz[v] = bf2f(((const uint16_t*)p.bias)[((int64_t)h * p.S + qc) * p.S + k]) * LOG2E;
+  }
+  const float c1 = p.scale * LOG2E;
+  if (!skip) {
+    // staging: thread -> (tensor-tile row, 16-byte chunk); Q/dO rows q0t.., K/V rows k0t..
+    u32x4 pre[4][CPT];
+    float pstat = 0.f;
+    auto gload = [&](int b) {
+#pragma unroll
+      for (int c = 0; c < CPT; ++c) {
+        const int idx = tid + c * 256, row = idx / CPR, col = (idx % CPR) * 8;
+        const int rq = min(q0t + row, p.S - 1), rk = min(k0t + row, p.S - 1);
+        const int64_t ba = (int64_t)b * p.sb + (int64_t)h * p.sh;
+        pre[0][c] = *(const u32x4*)((const uint16_t*)p.Q + ba + (int64_t)rq * p.ss + col);
+        pre[1][c] = *(const u32x4*)((const uint16_t*)p.dO + (int64_t)b * p.do_sb + (int64_t)h * p.do_sh + (int64_t)rq * p.do_ss + col);
+        pre[2][c] = *(const u32x4*)((const uint16_t*)p.K + ba + (int64_t)rk * p.ss + col);
+        pre[3][c] = *(const u32x4*)((const uint16_t*)p.V + ba + (int64_t)rk * p.ss + col);
+      }
+      if (tid < 128) {
+        const int i = min(q0t + (tid & 63), p.S - 1);
+        pstat = tid < 64 ? p.lse[(int64_t)b * p.lse_sb + (int64_t)h * p.lse_sh + i]
+                         : p.delta[(int64_t)b * p.dl_sb + (int64_t)h * p.dl_sh + i];
+      }
+    };
+    auto lstore = [&](int buf) {
+#pragma unroll
+      for (int c = 0; c < CPT; ++c) {
+        const int idx = tid + c * 256, row = idx / CPR, col = (idx % CPR) * 8;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) *(u32x4*)(&sT[buf][t][row * LD + col]) = pre[t][c];
+      }
+      if (tid < 64) sL[buf][tid] = pstat * LOG2E;
+      else if (tid < 128) sD[buf][tid - 64] = pstat;
+    };
+    gload(bfirst);
+    lstore(bfirst & 1);
+    if (bfirst + 1 < blast) gload(bfirst + 1);
+    for (int b = bfirst; b < blast; ++b) {
+      const int buf = b & 1;  // by global row parity: a row always takes the same path
+      __syncthreads();
+      if (b + 1 < blast) lstore(buf ^ 1);
+      if (b + 2 < blast) gload(b + 2);
+      f32x16 sa, pa;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) { sa[v] = 0.f; pa[v] = 0.f; }
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        sa = mfma(lds_nat<LD>(sT[buf][2], 32 * wk + r, ks, hl), lds_nat<LD>(sT[buf][0], 32 * wq + r, ks, hl), sa);
+        pa = mfma(lds_nat<LD>(sT[buf][3], 32 * wk + r, ks, hl), lds_nat<LD>(sT[buf][1], 32 * wq + r, ks, hl), pa);
+      }
+      const float lse2 = sL[buf][32 * wq + r], dlt = sD[buf][32 * wq + r];
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const float e = fast_exp2(fmaf(sa[v], c1, bz[v] - lse2));
+        float t = pa[v] - dlt;
+        if (CAUSAL) t = k0 + key_of(v, hl) > q ? 0.f : t;
+        acc[v] = __builtin_fmaf(e, t, acc[v]);
+      }
+    }
+  }
+  if (q < p.S && !(skip && resume)) {
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const int kb = k0 + 8 * g + 4 * hl;
+      if (kb + 3 < p.S) *(f32x4*)(dst + kb) = f32x4{acc[4 * g], acc[4 * g + 1], acc[4 * g + 2], acc[4 * g + 3]};
+      else for (int e = 0; e < 4; ++e) if (kb + e < p.S) dst[kb + e] = acc[4 * g + e];
+    }
+  }
+}
+
 // biasT[h][j][i] = bias[h][i][j] (bf16), 32x32 tiles through LDS; heads [h0,h1)
 __global__ __launch_bounds__(256) void bias_transpose_kernel(const uint16_t* src, uint16_t* dst, int S, int h0) {
   __shared__ uint16_t t[32][33];
@@ -354,6 +469,14 @@ hipError_t dkdv_d(const KP& p, hipStream_t st) {
 }
 template <int D>
 hipError_t dbias_d(const KP& p, hipStream_t st) {
+  if (p.S % 4 == 0 && p.S >= 64) {
+    int ng = 1;
+    if (p.sm_partial) ng = (p.b1 - 1) / p.sm_gw - p.b0 / p.sm_gw + 1;
+    dim3 g((p.S + 63) / 64, (p.S + 63) / 64, (p.h1 - p.h0) * ng);
+    if (p.mask_kind == 1) dbias_tile_kernel<D, true><<<g, 256, 0, st>>>(p);
+    else dbias_tile_kernel<D, false><<<g, 256, 0, st>>>(p);
+    return hipGetLastError();
+  }
   dim3 g((p.S + 127) / 128, (p.S + 31) / 32, p.h1 - p.h0);
   if (p.mask_kind == 1) dbias_fast_kernel<D, true><<<g, 256, 0, st>>>(p);
   else dbias_fast_kernel<D, false><<<g, 256, 0, st>>>(p);

@@ -190,6 +190,14 @@ inline bool fast_ok(const KP& p) {
 // two 128-query work-groups per compute unit the key tiles are split over groups inside the
 // work-group (4x2), and below one per compute unit the work-group also covers fewer queries (2x4).
 // Decided from the share, never from the chunk.
+// Rows per group of the tiled bias-gradient kernel: 0 = one group (the sum continues in the output);
+// otherwise the share's rows are cut into groups so that about two work-groups per compute unit exist.
+inline int dbias_group_rows(const KP& p) {
+  if (p.bias_kind != 1 || !fast_ok(p)) return 0;
+  const int64_t tiles = (int64_t)((p.S + 63) / 64) * ((p.S + 63) / 64) * p.H;
+  return tiles >= 512 ? 0 : 64;
+}
+
 enum WgShape { WG_4x1, WG_4x2, WG_2x4 };
 inline WgShape wg_shape(const KP& p) {
   const int64_t wgs = (int64_t)((p.S + 127) / 128) * p.share_units;

@@ -634,5 +634,6 @@ hipError_t launch_mfma_dbias(const KP& p, hipStream_t st) {
 }
 
 bool mfma_wants_bias_transpose(const KP& p) { return fast_ok(p) && p.bias_kind == 1; }
+int mfma_dbias_group_rows(const KP& p) { return dbias_group_rows(p); }
 
 }  // namespace ssa
