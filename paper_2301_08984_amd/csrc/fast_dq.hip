@@ -67,12 +67,29 @@ __global__ __launch_bounds__(64 * QW * NG) __attribute__((amdgpu_waves_per_eu(2,
       pv[c] = *(const u32x4*)(Vb + (int64_t)row * p.ss + col);
     }
   };
-  if (grp < ntiles) gload(grp);
+  // the bias slice of the next tile travels with the next K/V tile
+  uint2 bzn[8];
+  auto bload = [&](int kt) {
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int g = 0; g < 4; ++g)
+        bzn[4 * kb + g] = *(const uint2*)(bias_row + min(kt * BN + 32 * kb + 8 * g + 4 * hl, p.S - 4));
+  };
+  if (grp < ntiles) {
+    gload(grp);
+    if (BIAS) bload(grp);
+  }
   const int nit = (ntiles + NG - 1) / NG;
   for (int it = 0; it < nit; ++it) {
     const int kt = it * NG + grp;
     const int k0 = kt * BN;
     __syncthreads();
+    uint2 bzc[8];
+    if (BIAS) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) bzc[j] = bzn[j];
+    }
     if (kt < ntiles) {
 #pragma unroll
       for (int c = 0; c < CPT; ++c) {
@@ -80,7 +97,10 @@ __global__ __launch_bounds__(64 * QW * NG) __attribute__((amdgpu_waves_per_eu(2,
         *(u32x4*)(sK + row * LDK + col) = pk[c];
         *(u32x4*)(sV + row * LDV + col) = pv[c];
       }
-      if (kt + NG < ntiles) gload(kt + NG);
+      if (kt + NG < ntiles) {
+        gload(kt + NG);
+        if (BIAS) bload(kt + NG);
+      }
     }
     __syncthreads();
     if (kt >= wtiles) continue;
@@ -90,8 +110,7 @@ __global__ __launch_bounds__(64 * QW * NG) __attribute__((amdgpu_waves_per_eu(2,
       uint2 bz[4];
       if (BIAS) {
 #pragma unroll
-        for (int g = 0; g < 4; ++g)
-          bz[g] = *(const uint2*)(bias_row + min(k0 + 32 * kb + 8 * g + 4 * hl, p.S - 4));
+        for (int g = 0; g < 4; ++g) bz[g] = bzc[4 * kb + g];
       }
       f32x16 sa, pa;
       {
