@@ -116,7 +116,7 @@ def main():
     ap.add_argument("--no-extras", action="store_true", help="skip the per-k table and the instrumented pass")
     ap.add_argument("--no-per-k", action="store_true", help="skip the table over the workload's other k")
     ap.add_argument("--calibration-copy", action="store_true",
-                    help="also run one 1 GiB device copy (a known-size kernel to scale rocprofv3 counters by)")
+                    help="also run one 1 GiB read + 1 GiB write elementwise kernel (known size, to scale rocprofv3 counters by)")
     a = ap.parse_args()
     if a.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (no collectives, no sharding across GPUs); "
@@ -144,9 +144,11 @@ def main():
         dc.bwd(d)
 
     if a.calibration_copy:
-        src = torch.zeros(1 << 30, dtype=torch.uint8, device=dc.dev)
+        # a plain streaming kernel of known size: reads 1 GiB, writes 1 GiB
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dc.dev)
         dst = torch.empty_like(src)
-        dst.copy_(src)
+        torch.cuda.synchronize()
+        torch.mul(src, 2.0, out=dst)
         torch.cuda.synchronize()
         del src, dst
     for _ in range(a.warmup):

@@ -15,9 +15,10 @@
  * and the backward produces dQ, dK, dV, dG and the bias gradient for dY.
  *
  * All pointers are DEVICE pointers unless said otherwise; the descriptor and
- * the size outputs are HOST memory.  The library allocates no device memory,
- * keeps no state between calls and never synchronises: all work is enqueued on
- * the caller's stream and the call returns while it may still be running.
+ * the size outputs are HOST memory.  The library allocates no device memory and
+ * never synchronises: all work is enqueued on the caller's stream and the call
+ * returns while it may still be running.  It keeps no state between calls, except
+ * the opt-in timing instrumentation at the end of this file.
  */
 #ifndef SS_ATTN_H
 #define SS_ATTN_H
@@ -96,7 +97,9 @@ typedef struct {
  * bytes (host outputs, either may be NULL).  The backward workspace holds one
  * chunk's recomputed softmax statistics and pre-gated output gradient and is
  * reused by every chunk, so it shrinks as k grows; this is what makes
- * peak memory = caller tensors + workspace fall with k (Section 6.3).
+ * peak memory = caller tensors + workspace fall with k (Section 6.3).  Parts that
+ * do not depend on k (a transposed copy of a dense bias, group partial sums of the
+ * bias gradient) are included in the figure.
  * Needs no GPU.  Returns SS_OK or a negative error. */
 int ss_attn_workspace_bytes(const ss_attn_desc* desc, size_t* fwd_bytes, size_t* bwd_bytes);
 
@@ -141,8 +144,10 @@ int ss_attn_bwd(const ss_attn_desc* desc, const void* Q, const void* K, const vo
 const char* ss_strerror(int code);
 
 /* Host-only: which kernel family a descriptor is served by: "mfma_bf16" (bf16
- * activations, D in {32,64,128}) or "plain_fp32" (everything else, and whenever
- * SS_FLAG_GENERIC_KERNELS is set).  NULL for an invalid descriptor. */
+ * activations, D in {32,64,128}), "mfma_bf16_short" (bf16, D = 32, S <= 64, not
+ * gated: one wavefront holds a whole score matrix) or "plain_fp32" (everything
+ * else, and whenever SS_FLAG_GENERIC_KERNELS is set).  NULL for an invalid
+ * descriptor. */
 const char* ss_attn_kernel_family(const ss_attn_desc* desc);
 
 /* Benchmark instrumentation, not part of the method.  While enabled, every kernel
