@@ -462,9 +462,7 @@ void dkdv_fast_launch(const KP& p, hipStream_t st) {
 }
 template <int D>
 hipError_t dkdv_d(const KP& p, hipStream_t st) {
-  // small shares: 64-key work-groups, so that twice as many compute units get one
-  if (wg_shape(p) == WG_2x4) dkdv_fast_launch<D, 2>(p, st);
-  else dkdv_fast_launch<D, 4>(p, st);
+  dkdv_fast_launch<D, 4>(p, st);
   return hipGetLastError();
 }
 template <int D>
@@ -492,7 +490,11 @@ hipError_t dbias_d(const KP& p, hipStream_t st) {
     case 128: return fn<128>(__VA_ARGS__);        \
     default: return hipErrorInvalidValue;         \
   }
-hipError_t launch_fast_dkdv(const KP& p, hipStream_t st) { SS_FAST_DISPATCH_D(dkdv_d, p, st) }
+hipError_t launch_fast_dkdv(const KP& p, hipStream_t st) {
+  // small shares: 32-key work-groups whose wavefronts split the queries
+  if (wg_shape(p) == WG_2x4) return launch_fast_dkdv_wave(p, st);
+  SS_FAST_DISPATCH_D(dkdv_d, p, st)
+}
 hipError_t launch_fast_dbias(const KP& p, hipStream_t st) { SS_FAST_DISPATCH_D(dbias_d, p, st) }
 
 hipError_t launch_bias_transpose(const void* bias, void* biasT, int S, int h0, int h1, hipStream_t st) {

@@ -1,0 +1,288 @@
+// dK/dV kernel for small shares: wavefronts that never wait for each other inside the loop.
+#include "mfma_common.h"
+
+#include <type_traits>
+
+namespace ssa {
+namespace {
+
+// ---------------------------------------------------------------------------
+// dK, dV when the share has too few key blocks to fill the chip with key-stationary
+// work-groups.  A work-group owns one 32-key block; its QG wavefronts all hold that
+// block's K and V fragments and split the queries: wavefront g takes the 32-query
+// sub-tiles first+g, first+g+QG, ...  Every wavefront stages its own sub-tiles
+// (global -> registers -> its private double-buffered LDS slot -> operand reads), so
+// the loop has no barrier: the wavefronts drift apart and one's vector-ALU and
+// staging work overlaps the others' matrix products.  Per step the scores of the
+// next sub-tile run on the matrix cores while the vector ALUs turn the current
+// scores into P and dS, then the gradient products of the current sub-tile follow.
+// The QG partial sums of dK and dV are folded through LDS as a fixed binary tree
+// ((g0+g2)+(g1+g3) for QG = 4), so the result does not depend on timing.
+// ---------------------------------------------------------------------------
+template <int D, bool BIAS, bool CAUSAL, int QG>
+__global__ __launch_bounds__(64 * QG) void dkdv_wave_kernel(KP p) {
+  constexpr int KS = D / 16, DB = D / 32, LD = D + 16, SUB = 32;
+  constexpr int CPR = D / 8, CPT = SUB * CPR / 64;
+  constexpr int MAT = SUB * LD;                  // uint16 elements of one staged matrix
+  constexpr int SLOT = 4 * MAT + 2 * 2 * 2 * SUB;  // two buffers of (Q, dO) + two of (lse, delta) as floats
+  constexpr int MERGE = (QG / 2) * 64 * 32 * DB * 2;
+  constexpr int LDS_ELEMS = QG * SLOT > MERGE ? QG * SLOT : MERGE;
+  __shared__ __attribute__((aligned(16))) uint16_t smem[LDS_ELEMS];
+  const int lane = threadIdx.x & 63, grp = threadIdx.x >> 6, r = lane & 31, hl = lane >> 5;
+  uint16_t* slot = smem + grp * SLOT;
+  float* sstat = (float*)(slot + 4 * MAT);
+  const BlockId blk = xcd_block_id();
+  const int h = p.h0 + blk.y, b = p.b0 + blk.z;
+  const int k0 = blk.x * 32, key = k0 + r;  // early key blocks see the most queries under a causal mask
+  const int kc = min(key, p.S - 1);
+  const int64_t base = (int64_t)b * p.sb + (int64_t)h * p.sh;
+  const uint16_t* Qb = (const uint16_t*)p.Q + base;
+  const uint16_t* Kb = (const uint16_t*)p.K + base;
+  const uint16_t* Vb = (const uint16_t*)p.V + base;
+  const uint16_t* dOb = (const uint16_t*)p.dO + (int64_t)b * p.do_sb + (int64_t)h * p.do_sh;
+  const float* lse_b = p.lse + (int64_t)b * p.lse_sb + (int64_t)h * p.lse_sh;
+  const float* dl_b = p.delta + (int64_t)b * p.dl_sb + (int64_t)h * p.dl_sh;
+  const uint16_t* biasT_row = BIAS ? (const uint16_t*)p.biasT + ((int64_t)h * p.S + kc) * p.S : nullptr;
+
+  bf16x8 kf[KS], vf[KS];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) {
+    kf[ks] = *(const bf16x8*)(Kb + (int64_t)kc * p.ss + 16 * ks + 8 * hl);
+    vf[ks] = *(const bf16x8*)(Vb + (int64_t)kc * p.ss + 16 * ks + 8 * hl);
+  }
+  f32x16 dk[DB], dv[DB];
+#pragma unroll
+  for (int db = 0; db < DB; ++db)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) { dk[db][v] = 0.f; dv[db][v] = 0.f; }
+  const float c1 = p.scale * LOG2E;
+  const int nsub = (p.S + SUB - 1) / SUB;
+  const int first = CAUSAL ? k0 / SUB : 0;  // queries before the block's first key see none of it
+  const int j0 = first + grp;               // this wavefront's sub-tiles: j0, j0+QG, ... < nsub
+  const int n = j0 < nsub ? (nsub - 1 - j0) / QG + 1 : 0;
+  const int jlast = j0 + (n - 1) * QG;
+
+  u32x4 pq[CPT], pg[CPT];
+  float pstat = 0.f;
+  uint2 bzn[4], bzc[4];  // bias slices of the sub-tile in the registers / of the one about to be used
+  auto gload = [&](int j) {
+#pragma unroll
+    for (int c = 0; c < CPT; ++c) {
+      const int idx = lane + c * 64, row = min(j * SUB + idx / CPR, p.S - 1), col = (idx % CPR) * 8;
+      pq[c] = *(const u32x4*)(Qb + (int64_t)row * p.ss + col);
+      pg[c] = *(const u32x4*)(dOb + (int64_t)row * p.do_ss + col);
+    }
+    const int i = min(j * SUB + r, p.S - 1);
+    pstat = hl == 0 ? lse_b[i] : dl_b[i];
+    if (BIAS) {
+#pragma unroll
+      for (int g = 0; g < 4; ++g) bzn[g] = *(const uint2*)(biasT_row + min(j * SUB + 8 * g + 4 * hl, p.S - 4));
+    }
+  };
+  auto lstore = [&](int buf) {
+    uint16_t* tq = slot + buf * 2 * MAT;
+    uint16_t* tg = tq + MAT;
+#pragma unroll
+    for (int c = 0; c < CPT; ++c) {
+      const int idx = lane + c * 64, row = idx / CPR, col = (idx % CPR) * 8;
+      *(u32x4*)(tq + row * LD + col) = pq[c];
+      *(u32x4*)(tg + row * LD + col) = pg[c];
+    }
+    // lanes 0..31: -LSE in the exp2 domain, lanes 32..63: Delta (arithmetic at store time, not on the in-flight load)
+    sstat[buf * 2 * SUB + lane] = hl == 0 ? -pstat * LOG2E : pstat;
+  };
+  // scores and dP of the sub-tile staged in `buf`
+  auto stage_a = [&](int buf, f32x16& sa, f32x16& pa) {
+    const uint16_t* tq = slot + buf * 2 * MAT;
+    const uint16_t* tg = tq + MAT;
+    bf16x8 fq[KS], fg[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      fq[ks] = lds_nat<LD>(tq, r, ks, hl);
+      fg[ks] = lds_nat<LD>(tg, r, ks, hl);
+    }
+#pragma unroll
+    for (int v = 0; v < 16; ++v) { sa[v] = 0.f; pa[v] = 0.f; }
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      sa = mfma(fq[ks], kf[ks], sa);
+      pa = mfma(fg[ks], vf[ks], pa);
+    }
+  };
+  // P and dS as packed bf16 operands
+  auto stage_v = [&](int buf, int i0, const f32x16& sa, const f32x16& pa, const uint2* bz, bf16x8 (&pf)[2],
+                     bf16x8 (&df)[2], auto edge_tag) {
+    constexpr bool edge = decltype(edge_tag)::value;
+    const float* tl = sstat + buf * 2 * SUB;
+    const float* td = tl + SUB;
+    float pr[16], ds[16];
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const f32x4 l4 = *(const f32x4*)(tl + 8 * g + 4 * hl);
+      const f32x4 d4 = *(const f32x4*)(td + 8 * g + 4 * hl);
+      float bl[4] = {0.f, 0.f, 0.f, 0.f};
+      if (BIAS) {
+        const uint2 u = bz[g];
+        bl[0] = __uint_as_float(u.x << 16) * LOG2E; bl[1] = __uint_as_float(u.x & 0xffff0000u) * LOG2E;
+        bl[2] = __uint_as_float(u.y << 16) * LOG2E; bl[3] = __uint_as_float(u.y & 0xffff0000u) * LOG2E;
+      }
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        float pe = fast_exp2(fmaf(sa[4 * g + e], c1, BIAS ? bl[e] + l4[e] : l4[e]));
+        if (edge) {
+          const int i = i0 + 8 * g + 4 * hl + e;
+          const bool dead = i >= p.S || key >= p.S || (CAUSAL && key > i);
+          pe = dead ? 0.f : pe;
+        }
+        pr[4 * g + e] = pe;
+        ds[4 * g + e] = pe * (pa[4 * g + e] - d4[e]);
+      }
+    }
+    pf[0] = pack8(&pr[0]); pf[1] = pack8(&pr[8]);
+    df[0] = pack8(&ds[0]); df[1] = pack8(&ds[8]);
+  };
+  // dV += dO^T P, dK += Q^T dS
+  auto stage_b = [&](int buf, const bf16x8 (&pf)[2], const bf16x8 (&df)[2]) {
+    const uint16_t* tq = slot + buf * 2 * MAT;
+    const uint16_t* tg = tq + MAT;
+#pragma unroll
+    for (int hb = 0; hb < 2; ++hb) {
+      bf16x8 tg_[DB], tq_[DB];
+#pragma unroll
+      for (int db = 0; db < DB; ++db) {
+        tg_[db] = lds_tr<LD>(tg, 16 * hb, 32 * db, lane);
+        tq_[db] = lds_tr<LD>(tq, 16 * hb, 32 * db, lane);
+      }
+#pragma unroll
+      for (int db = 0; db < DB; ++db) {
+        dv[db] = mfma(tg_[db], pf[hb], dv[db]);
+        dk[db] = mfma(tq_[db], df[hb], dk[db]);
+      }
+    }
+  };
+  // one step: sub-tile j sits in LDS buffer `buf` with its scores in (sc, pc); the registers hold
+  // sub-tile j+QG (clamped to the wavefront's last one), which moves to the other buffer and has
+  // its scores computed into (sn, pn) while the vector ALUs work on (sc, pc)
+  auto step = [&](int j, int buf, const f32x16& sc, const f32x16& pc, f32x16& sn, f32x16& pn, auto edge_tag) {
+    uint2 bz[4];
+    if (BIAS) {
+#pragma unroll
+      for (int g = 0; g < 4; ++g) { bz[g] = bzc[g]; bzc[g] = bzn[g]; }
+    }
+    lstore(buf ^ 1);
+    gload(min(j + 2 * QG, jlast));
+    bf16x8 pf[2], df[2];
+    stage_a(buf ^ 1, sn, pn);
+    stage_v(buf, j * SUB, sc, pc, bz, pf, df, edge_tag);
+    stage_b(buf, pf, df);
+    // LDS stores, then next scores (16 matrix ops) under the vector-ALU work, then the gradient products
+    __builtin_amdgcn_sched_group_barrier(0x200, 2 * CPT + 1, 0);
+    __builtin_amdgcn_sched_group_barrier(0x020, 2 * CPT + 2, 0);
+    __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+#pragma unroll
+    for (int q = 0; q < 2 * KS; ++q) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+      __builtin_amdgcn_sched_group_barrier(0x002, 8, 0);
+    }
+    __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
+#pragma unroll
+    for (int q = 0; q < 4 * DB; ++q) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+    }
+  };
+  auto is_edge = [&](int j) { return (j * SUB + SUB > p.S) || (k0 + 32 > p.S) || (CAUSAL && j * SUB < k0 + 31); };
+
+  if (n > 0) {
+    f32x16 sA, pA, sB, pB;
+    gload(j0);
+    lstore(0);
+    if (BIAS) {
+#pragma unroll
+      for (int g = 0; g < 4; ++g) bzc[g] = bzn[g];
+    }
+    gload(min(j0 + QG, jlast));
+    stage_a(0, sA, pA);
+    for (int i = 0; i < n; i += 2) {
+      const int j = j0 + i * QG;
+      if (is_edge(j)) step(j, 0, sA, pA, sB, pB, std::true_type{});
+      else step(j, 0, sA, pA, sB, pB, std::false_type{});
+      if (i + 1 >= n) break;
+      if (is_edge(j + QG)) step(j + QG, 1, sB, pB, sA, pA, std::true_type{});
+      else step(j + QG, 1, sB, pB, sA, pA, std::false_type{});
+    }
+  }
+
+  // fold the wavefronts' partial sums: binary tree over groups, fixed shape
+  if (QG > 1) {
+    float* mb = (float*)smem;
+#pragma unroll
+    for (int s = QG / 2; s >= 1; s >>= 1) {
+      __syncthreads();
+      if (grp >= s && grp < 2 * s) {
+        float* my = mb + (size_t)(grp - s) * (64 * 32 * DB) + lane;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            my[(16 * db + v) * 64] = dk[db][v];
+            my[(16 * DB + 16 * db + v) * 64] = dv[db][v];
+          }
+      }
+      __syncthreads();
+      if (grp < s) {
+        const float* o = mb + (size_t)grp * (64 * 32 * DB) + lane;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            dk[db][v] += o[(16 * db + v) * 64];
+            dv[db][v] += o[(16 * DB + 16 * db + v) * 64];
+          }
+      }
+    }
+    if (grp > 0) return;
+  }
+  if (key >= p.S) return;
+  uint16_t* oK = (uint16_t*)p.dK + base + (int64_t)key * p.ss;
+  uint16_t* oV = (uint16_t*)p.dV + base + (int64_t)key * p.ss;
+#pragma unroll
+  for (int db = 0; db < DB; ++db)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const int d0 = 32 * db + 8 * g + 4 * hl;
+      uint2 a, c;
+      a.x = (uint32_t)f2bf(dk[db][4 * g] * p.scale) | ((uint32_t)f2bf(dk[db][4 * g + 1] * p.scale) << 16);
+      a.y = (uint32_t)f2bf(dk[db][4 * g + 2] * p.scale) | ((uint32_t)f2bf(dk[db][4 * g + 3] * p.scale) << 16);
+      c.x = (uint32_t)f2bf(dv[db][4 * g]) | ((uint32_t)f2bf(dv[db][4 * g + 1]) << 16);
+      c.y = (uint32_t)f2bf(dv[db][4 * g + 2]) | ((uint32_t)f2bf(dv[db][4 * g + 3]) << 16);
+      *(uint2*)(oK + d0) = a;
+      *(uint2*)(oV + d0) = c;
+    }
+}
+
+template <int D>
+hipError_t dkdv_wave_d(const KP& p, hipStream_t st) {
+  constexpr int QG = 4;
+  const dim3 g((p.S + 31) / 32, p.h1 - p.h0, p.b1 - p.b0);
+  const bool bias = p.bias_kind == 1, causal = p.mask_kind == 1;
+  if (bias && causal) dkdv_wave_kernel<D, true, true, QG><<<g, 64 * QG, 0, st>>>(p);
+  else if (bias) dkdv_wave_kernel<D, true, false, QG><<<g, 64 * QG, 0, st>>>(p);
+  else if (causal) dkdv_wave_kernel<D, false, true, QG><<<g, 64 * QG, 0, st>>>(p);
+  else dkdv_wave_kernel<D, false, false, QG><<<g, 64 * QG, 0, st>>>(p);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_fast_dkdv_wave(const KP& p, hipStream_t st) {
+  switch (p.D) {
+    case 32: return dkdv_wave_d<32>(p, st);
+    case 64: return dkdv_wave_d<64>(p, st);
+    case 128: return dkdv_wave_d<128>(p, st);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+}  // namespace ssa
