@@ -31,7 +31,16 @@ __global__ __launch_bounds__(64 * QG) void dkdv_wave_kernel(KP p) {
   const int lane = threadIdx.x & 63, grp = threadIdx.x >> 6, r = lane & 31, hl = lane >> 5;
   uint16_t* slot = smem + grp * SLOT;
   float* sstat = (float*)(slot + 4 * MAT);
-  const BlockId blk = xcd_block_id();
+  // heaviest key blocks first over the whole launch (block 0 of every head, then block 1, ...): when
+  // there are more work-groups than compute units the late, light ones fill in behind the early ones
+  BlockId blk;
+  {
+    const int units = gridDim.y * gridDim.z;
+    const int lin = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);
+    blk.x = lin / units;
+    blk.y = (lin % units) % gridDim.y;
+    blk.z = (lin % units) / gridDim.y;
+  }
   const int h = p.h0 + blk.y, b = p.b0 + blk.z;
   const int k0 = blk.x * 32, key = k0 + r;  // early key blocks see the most queries under a causal mask
   const int kc = min(key, p.S - 1);
@@ -216,29 +225,30 @@ __global__ __launch_bounds__(64 * QG) void dkdv_wave_kernel(KP p) {
 
   // fold the wavefronts' partial sums: binary tree over groups, fixed shape
   if (QG > 1) {
-    float* mb = (float*)smem;
+    f32x4* mb = (f32x4*)smem;
 #pragma unroll
     for (int s = QG / 2; s >= 1; s >>= 1) {
       __syncthreads();
       if (grp >= s && grp < 2 * s) {
-        float* my = mb + (size_t)(grp - s) * (64 * 32 * DB) + lane;
+        f32x4* my = mb + (size_t)(grp - s) * (64 * 8 * DB) + lane;
 #pragma unroll
         for (int db = 0; db < DB; ++db)
 #pragma unroll
-          for (int v = 0; v < 16; ++v) {
-            my[(16 * db + v) * 64] = dk[db][v];
-            my[(16 * DB + 16 * db + v) * 64] = dv[db][v];
+          for (int g = 0; g < 4; ++g) {
+            my[(4 * db + g) * 64] = f32x4{dk[db][4 * g], dk[db][4 * g + 1], dk[db][4 * g + 2], dk[db][4 * g + 3]};
+            my[(4 * DB + 4 * db + g) * 64] = f32x4{dv[db][4 * g], dv[db][4 * g + 1], dv[db][4 * g + 2], dv[db][4 * g + 3]};
           }
       }
       __syncthreads();
       if (grp < s) {
-        const float* o = mb + (size_t)grp * (64 * 32 * DB) + lane;
+        const f32x4* o = mb + (size_t)grp * (64 * 8 * DB) + lane;
 #pragma unroll
         for (int db = 0; db < DB; ++db)
 #pragma unroll
-          for (int v = 0; v < 16; ++v) {
-            dk[db][v] += o[(16 * db + v) * 64];
-            dv[db][v] += o[(16 * DB + 16 * db + v) * 64];
+          for (int g = 0; g < 4; ++g) {
+            const f32x4 a = o[(4 * db + g) * 64], c = o[(4 * DB + 4 * db + g) * 64];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) { dk[db][4 * g + e] += a[e]; dv[db][4 * g + e] += c[e]; }
           }
       }
     }
