@@ -207,7 +207,6 @@ template <int D>
 hipError_t dq_d(const KP& p, hipStream_t st) {
   switch (wg_shape(p)) {
     case WG_4x2: dq_fast_launch<D, 4, 2>(p, st); break;
-    case WG_2x4: dq_fast_launch<D, 2, 4>(p, st); break;
     default: dq_fast_launch<D, 4, 1>(p, st); break;
   }
   return hipGetLastError();
@@ -222,6 +221,9 @@ hipError_t dq_d(const KP& p, hipStream_t st) {
     case 128: return fn<128>(__VA_ARGS__);        \
     default: return hipErrorInvalidValue;         \
   }
-hipError_t launch_fast_dq(const KP& p, hipStream_t st) { SS_FAST_DISPATCH_D(dq_d, p, st) }
+hipError_t launch_fast_dq(const KP& p, hipStream_t st) {
+  if (wg_shape(p) == WG_2x4) return launch_fast_dq_wave(p, st);
+  SS_FAST_DISPATCH_D(dq_d, p, st)
+}
 
 }  // namespace ssa

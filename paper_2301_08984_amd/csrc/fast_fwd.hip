@@ -265,7 +265,6 @@ template <int D, bool RECOMP>
 hipError_t fwd_r(const KP& p, hipStream_t st) {
   switch (wg_shape(p)) {
     case WG_4x2: fwd_fast_launch<D, RECOMP, 4, 2>(p, st); break;
-    case WG_2x4: fwd_fast_launch<D, RECOMP, 2, 4>(p, st); break;
     default: fwd_fast_launch<D, RECOMP, 4, 1>(p, st); break;
   }
   return hipGetLastError();
@@ -284,6 +283,10 @@ hipError_t fwd_d(const KP& p, bool recompute, hipStream_t st) {
     case 128: return fn<128>(__VA_ARGS__);        \
     default: return hipErrorInvalidValue;         \
   }
-hipError_t launch_fast_fwd(const KP& p, bool recompute, hipStream_t st) { SS_FAST_DISPATCH_D(fwd_d, p, recompute, st) }
+hipError_t launch_fast_fwd(const KP& p, bool recompute, hipStream_t st) {
+  // small shares: 32-query work-groups whose wavefronts split the keys
+  if (wg_shape(p) == WG_2x4) return launch_fast_fwd_wave(p, recompute, st);
+  SS_FAST_DISPATCH_D(fwd_d, p, recompute, st)
+}
 
 }  // namespace ssa

@@ -1,0 +1,533 @@
+// Forward / recompute and dQ kernels for small shares: query-stationary wavefronts that never
+// wait for each other inside the loop.
+#include "mfma_common.h"
+
+#include <type_traits>
+
+namespace ssa {
+namespace {
+
+// Block order of the wave kernels: the heaviest blocks first over the whole launch (block 0 of
+// every head and row, then block 1, ...), so that when there are more work-groups than compute
+// units the late, light ones fill in behind the early ones.
+__device__ inline BlockId heavy_first_block_id() {
+  const int units = gridDim.y * gridDim.z;
+  const int lin = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);
+  BlockId b;
+  b.x = lin / units;
+  b.y = (lin % units) % gridDim.y;
+  b.z = (lin % units) / gridDim.y;
+  return b;
+}
+
+// coalesced fetch of a 32-row sub-tile (rows clamped to S-1): lane l takes the 16-byte chunks
+// l, l+64, ... (chunk i = row i / (D/8), columns 8 * (i % (D/8)) ..)
+template <int D>
+__device__ inline void sub_load(u32x4 (&dst)[D / 16], const uint16_t* base, int64_t ss, int row0, int S, int lane) {
+  constexpr int CPR = D / 8;
+#pragma unroll
+  for (int c = 0; c < D / 16; ++c) {
+    const int idx = lane + c * 64, row = min(row0 + idx / CPR, S - 1), col = (idx % CPR) * 8;
+    dst[c] = *(const u32x4*)(base + (int64_t)row * ss + col);
+  }
+}
+template <int D, int LD>
+__device__ inline void sub_store(uint16_t* t, const u32x4 (&src)[D / 16], int lane) {
+  constexpr int CPR = D / 8;
+#pragma unroll
+  for (int c = 0; c < D / 16; ++c) {
+    const int idx = lane + c * 64, row = idx / CPR, col = (idx % CPR) * 8;
+    *(u32x4*)(t + row * LD + col) = src[c];
+  }
+}
+
+// ---------------------------------------------------------------------------
+// forward / recompute when the share has too few query blocks to fill the chip with
+// 128-query work-groups.  A work-group owns one 32-query block; its NG wavefronts all
+// hold the block's Q fragments and split the keys: wavefront g takes the 32-key
+// sub-tiles g, g+NG, ...  Every wavefront stages its own sub-tiles of K and V
+// (global -> registers -> its private double-buffered LDS slot -> operand reads), so
+// the loop has no barrier: the wavefronts drift apart and one's softmax arithmetic and
+// staging overlaps the others' matrix products.  Per step the scores of the next
+// sub-tile run on the matrix cores while the vector ALUs do the softmax of the current
+// one; then P V follows.  The NG partial results (O, m, l) are folded through LDS as a
+// fixed binary tree, so the result does not depend on timing.
+// ---------------------------------------------------------------------------
+template <int D, bool BIAS, bool CAUSAL, bool RECOMP, int NG>
+__global__ __launch_bounds__(64 * NG) void fwd_wave_kernel(KP p) {
+  constexpr int KS = D / 16, DB = D / 32, SUB = 32, CPT = D / 16;
+  constexpr int LDK = D + 8, LDV = D + 16;  // row pads chosen for conflict-free b128 / transpose reads
+  constexpr int BUF = SUB * LDK + SUB * LDV;
+  constexpr int SLOT = 2 * BUF;
+  constexpr int MSLOT = 64 * (4 * DB + 1);  // f32x4 units one wavefront hands over in the merge
+  constexpr int MERGE = (NG / 2) * MSLOT * 8;
+  constexpr int LDS_ELEMS = NG * SLOT > MERGE ? NG * SLOT : MERGE;
+  __shared__ __attribute__((aligned(16))) uint16_t smem[LDS_ELEMS];
+  const int lane = threadIdx.x & 63, grp = threadIdx.x >> 6, r = lane & 31, hl = lane >> 5;
+  uint16_t* slot = smem + grp * SLOT;
+  const BlockId blk = heavy_first_block_id();
+  const int h = p.h0 + blk.y, b = p.b0 + blk.z;
+  const int nsub = (p.S + SUB - 1) / SUB;
+  const int qb = CAUSAL ? nsub - 1 - blk.x : blk.x;  // late query blocks see the most keys under a causal mask
+  const int q0 = qb * SUB, q = q0 + r;
+  const int qc = min(q, p.S - 1);
+  const int64_t base = (int64_t)b * p.sb + (int64_t)h * p.sh;
+  const uint16_t* Qb = (const uint16_t*)p.Q + base;
+  const uint16_t* Kb = (const uint16_t*)p.K + base;
+  const uint16_t* Vb = (const uint16_t*)p.V + base;
+  const uint16_t* bias_row = BIAS ? (const uint16_t*)p.bias + ((int64_t)h * p.S + qc) * p.S : nullptr;
+  const float c1 = p.scale * LOG2E;
+
+  const int nj = CAUSAL ? min(nsub, qb + 1) : nsub;  // key sub-tiles with a visible key
+  const int j0 = grp;
+  const int n = j0 < nj ? (nj - 1 - j0) / NG + 1 : 0;
+  const int jlast = j0 + (n - 1) * NG;
+
+  u32x4 pk[CPT], pv[CPT];
+  uint2 bzn[4], bzc[4];  // bias slices of the sub-tile in flight / of the one about to be used
+  auto gload = [&](int j) {
+    sub_load<D>(pk, Kb, p.ss, j * SUB, p.S, lane);
+    sub_load<D>(pv, Vb, p.ss, j * SUB, p.S, lane);
+    if (BIAS) {
+#pragma unroll
+      for (int g = 0; g < 4; ++g) bzn[g] = *(const uint2*)(bias_row + min(j * SUB + 8 * g + 4 * hl, p.S - 4));
+    }
+  };
+  auto lstore = [&](int buf) {
+    sub_store<D, LDK>(slot + buf * BUF, pk, lane);
+    sub_store<D, LDV>(slot + buf * BUF + SUB * LDK, pv, lane);
+  };
+
+  // Q fragments: fetched coalesced, passed through the (still unused) second buffer
+  bf16x8 qf[KS];
+  {
+    u32x4 pq[CPT];
+    sub_load<D>(pq, Qb, p.ss, q0, p.S, lane);
+    if (n > 0) gload(j0);
+    sub_store<D, LDK>(slot + BUF, pq, lane);
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) qf[ks] = lds_nat<LDK>(slot + BUF, r, ks, hl);
+  }
+  f32x16 oacc[DB];
+#pragma unroll
+  for (int db = 0; db < DB; ++db)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) oacc[db][v] = 0.f;
+  float m = -1e30f, l = 0.f;
+
+  // S^T = K Q^T of the sub-tile staged in `buf`: lane = query, registers = keys
+  auto stage_s = [&](int buf, f32x16& sa) {
+    const uint16_t* sK = slot + buf * BUF;
+    bf16x8 fk[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) fk[ks] = lds_nat<LDK>(sK, r, ks, hl);
+#pragma unroll
+    for (int v = 0; v < 16; ++v) sa[v] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) sa = mfma(fk[ks], qf[ks], sa);
+  };
+  // online softmax of one 32-key block; leaves P as packed bf16 operands
+  auto softmax = [&](int k0, f32x16 sa, const uint2* bz, bf16x8 (&pf)[2], auto edge_tag) {
+    constexpr bool edge = decltype(edge_tag)::value;
+    if (BIAS) {
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const uint2 u = bz[g];
+        sa[4 * g + 0] = fmaf(sa[4 * g + 0], c1, __uint_as_float(u.x << 16) * LOG2E);
+        sa[4 * g + 1] = fmaf(sa[4 * g + 1], c1, __uint_as_float(u.x & 0xffff0000u) * LOG2E);
+        sa[4 * g + 2] = fmaf(sa[4 * g + 2], c1, __uint_as_float(u.y << 16) * LOG2E);
+        sa[4 * g + 3] = fmaf(sa[4 * g + 3], c1, __uint_as_float(u.y & 0xffff0000u) * LOG2E);
+      }
+    }
+    if (edge) {
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int key = k0 + key_of(v, hl);
+        const bool dead = key >= p.S || (CAUSAL && key > q);
+        sa[v] = dead ? -INFINITY : sa[v];
+      }
+    }
+    float rmax = -INFINITY;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) rmax = fmaxf(rmax, sa[v]);
+    if (!BIAS) rmax *= c1;  // scale > 0 on this path
+    rmax = half_max(rmax);
+    // the running maximum is raised only when exceeded by more than 2^8, so the O rescale is
+    // skipped on most sub-tiles; probabilities stay below 2^8, harmless in fp32/bf16 range
+    if (__builtin_amdgcn_ballot_w64(rmax > m + 8.f) != 0) {
+      const float mn = fmaxf(m, rmax);
+      const float alpha = fast_exp2(m - mn);
+      m = mn;
+      l *= alpha;
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) oacc[db][v] *= alpha;
+    }
+    float lsum = 0.f;
+    float pr[16];
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      pr[v] = BIAS ? fast_exp2(sa[v] - m) : fast_exp2(fmaf(sa[v], c1, -m));
+      lsum += pr[v];
+    }
+    l += lsum;
+    pf[0] = pack8(&pr[0]);
+    pf[1] = pack8(&pr[8]);
+  };
+  // O^T += V^T P^T
+  auto stage_pv = [&](int buf, const bf16x8 (&pf)[2]) {
+    const uint16_t* sV = slot + buf * BUF + SUB * LDK;
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      bf16x8 vf[DB];
+#pragma unroll
+      for (int db = 0; db < DB; ++db) vf[db] = lds_tr<LDV>(sV, 16 * t, 32 * db, lane);
+#pragma unroll
+      for (int db = 0; db < DB; ++db) oacc[db] = mfma(vf[db], pf[t], oacc[db]);
+    }
+  };
+  // one step: sub-tile j sits in LDS buffer `buf` with its scores in sc; the registers hold
+  // sub-tile j+NG (clamped to the wavefront's last one), which moves to the other buffer and has
+  // its scores computed into sn while the vector ALUs work on sc
+  auto step = [&](int j, int buf, const f32x16& sc, f32x16& sn, auto edge_tag) {
+    uint2 bz[4];
+    if (BIAS) {
+#pragma unroll
+      for (int g = 0; g < 4; ++g) { bz[g] = bzc[g]; bzc[g] = bzn[g]; }
+    }
+    lstore(buf ^ 1);
+    gload(min(j + 2 * NG, jlast));
+    stage_s(buf ^ 1, sn);
+    bf16x8 pf[2];
+    softmax(j * SUB, sc, bz, pf, edge_tag);
+    stage_pv(buf, pf);
+  };
+  auto is_edge = [&](int j) { return (j * SUB + SUB > p.S) || (CAUSAL && j * SUB + SUB - 1 > q0); };
+
+  if (n > 0) {
+    f32x16 sA, sB;
+    lstore(0);
+    if (BIAS) {
+#pragma unroll
+      for (int g = 0; g < 4; ++g) bzc[g] = bzn[g];
+    }
+    gload(min(j0 + NG, jlast));
+    stage_s(0, sA);
+    for (int i = 0; i < n; i += 2) {
+      const int j = j0 + i * NG;
+      if (is_edge(j)) step(j, 0, sA, sB, std::true_type{});
+      else step(j, 0, sA, sB, std::false_type{});
+      if (i + 1 >= n) break;
+      if (is_edge(j + NG)) step(j + NG, 1, sB, sA, std::true_type{});
+      else step(j + NG, 1, sB, sA, std::false_type{});
+    }
+  }
+
+  // fold the wavefronts' partial softmax results: binary tree over groups, fixed shape
+  if (NG > 1) {
+    f32x4* mb = (f32x4*)smem;
+#pragma unroll
+    for (int s = NG / 2; s >= 1; s >>= 1) {
+      __syncthreads();
+      if (grp >= s && grp < 2 * s) {
+        f32x4* my = mb + (size_t)(grp - s) * MSLOT + lane;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+          for (int g = 0; g < 4; ++g)
+            my[(4 * db + g) * 64] = f32x4{oacc[db][4 * g], oacc[db][4 * g + 1], oacc[db][4 * g + 2], oacc[db][4 * g + 3]};
+        my[4 * DB * 64] = f32x4{m, l, 0.f, 0.f};
+      }
+      __syncthreads();
+      if (grp < s) {
+        const f32x4* o = mb + (size_t)grp * MSLOT + lane;
+        const f32x4 ml = o[4 * DB * 64];
+        const float mn = fmaxf(m, ml[0]);
+        const float a0 = fast_exp2(m - mn), a1 = fast_exp2(ml[0] - mn);
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            const f32x4 x = o[(4 * db + g) * 64];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) oacc[db][4 * g + e] = oacc[db][4 * g + e] * a0 + x[e] * a1;
+          }
+        l = l * a0 + ml[1] * a1;
+        m = mn;
+      }
+    }
+    if (grp > 0) return;
+  }
+  if (q >= p.S) return;
+  fwd_epilogue<DB, RECOMP>(p, oacc, m, l, b, h, q, hl, base);
+}
+
+// ---------------------------------------------------------------------------
+// dQ for small shares, same organisation: a work-group owns one 32-query block, its NG
+// wavefronts hold the block's Q and dO fragments, LSE and Delta, and split the keys.
+// Per step S^T = K Q^T and dP^T = V dO^T of the next sub-tile run on the matrix cores
+// while the vector ALUs turn the current ones into dS; then dQ^T += K^T dS^T.
+// The NG partial sums are added through LDS as a fixed binary tree.
+// ---------------------------------------------------------------------------
+template <int D, bool BIAS, bool CAUSAL, int NG>
+__global__ __launch_bounds__(64 * NG) void dq_wave_kernel(KP p) {
+  constexpr int KS = D / 16, DB = D / 32, SUB = 32, CPT = D / 16;
+  constexpr int LDK = D + 16, LDV = D + 8;  // K is also read transposed
+  constexpr int BUF = SUB * LDK + SUB * LDV;
+  constexpr int SLOT = 2 * BUF;
+  constexpr int MSLOT = 64 * 4 * DB;
+  constexpr int MERGE = (NG / 2) * MSLOT * 8;
+  constexpr int LDS_ELEMS = NG * SLOT > MERGE ? NG * SLOT : MERGE;
+  __shared__ __attribute__((aligned(16))) uint16_t smem[LDS_ELEMS];
+  const int lane = threadIdx.x & 63, grp = threadIdx.x >> 6, r = lane & 31, hl = lane >> 5;
+  uint16_t* slot = smem + grp * SLOT;
+  const BlockId blk = heavy_first_block_id();
+  const int h = p.h0 + blk.y, b = p.b0 + blk.z;
+  const int nsub = (p.S + SUB - 1) / SUB;
+  const int qb = CAUSAL ? nsub - 1 - blk.x : blk.x;
+  const int q0 = qb * SUB, q = q0 + r;
+  const int qc = min(q, p.S - 1);
+  const int64_t base = (int64_t)b * p.sb + (int64_t)h * p.sh;
+  const uint16_t* Qb = (const uint16_t*)p.Q + base;
+  const uint16_t* Kb = (const uint16_t*)p.K + base;
+  const uint16_t* Vb = (const uint16_t*)p.V + base;
+  const uint16_t* dOb = (const uint16_t*)p.dO + (int64_t)b * p.do_sb + (int64_t)h * p.do_sh;
+  const uint16_t* bias_row = BIAS ? (const uint16_t*)p.bias + ((int64_t)h * p.S + qc) * p.S : nullptr;
+  const float c1 = p.scale * LOG2E;
+
+  const int nj = CAUSAL ? min(nsub, qb + 1) : nsub;
+  const int j0 = grp;
+  const int n = j0 < nj ? (nj - 1 - j0) / NG + 1 : 0;
+  const int jlast = j0 + (n - 1) * NG;
+
+  u32x4 pk[CPT], pv[CPT];
+  uint2 bzn[4], bzc[4];
+  auto gload = [&](int j) {
+    sub_load<D>(pk, Kb, p.ss, j * SUB, p.S, lane);
+    sub_load<D>(pv, Vb, p.ss, j * SUB, p.S, lane);
+    if (BIAS) {
+#pragma unroll
+      for (int g = 0; g < 4; ++g) bzn[g] = *(const uint2*)(bias_row + min(j * SUB + 8 * g + 4 * hl, p.S - 4));
+    }
+  };
+  auto lstore = [&](int buf) {
+    sub_store<D, LDK>(slot + buf * BUF, pk, lane);
+    sub_store<D, LDV>(slot + buf * BUF + SUB * LDK, pv, lane);
+  };
+
+  // Q and dO fragments: fetched coalesced, passed through the (still unused) second buffer
+  bf16x8 qf[KS], gf[KS];
+  {
+    u32x4 pq[CPT], pg[CPT];
+    sub_load<D>(pq, Qb, p.ss, q0, p.S, lane);
+    sub_load<D>(pg, dOb, p.do_ss, q0, p.S, lane);
+    if (n > 0) gload(j0);
+    sub_store<D, LDK>(slot + BUF, pq, lane);
+    sub_store<D, LDV>(slot + BUF + SUB * LDK, pg, lane);
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      qf[ks] = lds_nat<LDK>(slot + BUF, r, ks, hl);
+      gf[ks] = lds_nat<LDV>(slot + BUF + SUB * LDK, r, ks, hl);
+    }
+  }
+  const float nlse2 = -p.lse[(int64_t)b * p.lse_sb + (int64_t)h * p.lse_sh + qc] * LOG2E;
+  const float delta = p.delta[(int64_t)b * p.dl_sb + (int64_t)h * p.dl_sh + qc];
+  f32x16 acc[DB];
+#pragma unroll
+  for (int db = 0; db < DB; ++db)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[db][v] = 0.f;
+
+  auto stage_a = [&](int buf, f32x16& sa, f32x16& pa) {
+    const uint16_t* sK = slot + buf * BUF;
+    const uint16_t* sV = sK + SUB * LDK;
+    bf16x8 fk[KS], fv[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      fk[ks] = lds_nat<LDK>(sK, r, ks, hl);
+      fv[ks] = lds_nat<LDV>(sV, r, ks, hl);
+    }
+#pragma unroll
+    for (int v = 0; v < 16; ++v) { sa[v] = 0.f; pa[v] = 0.f; }
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      sa = mfma(fk[ks], qf[ks], sa);
+      pa = mfma(fv[ks], gf[ks], pa);
+    }
+  };
+  auto stage_v = [&](int k0, const f32x16& sa, const f32x16& pa, const uint2* bz, bf16x8 (&df)[2], auto edge_tag) {
+    constexpr bool edge = decltype(edge_tag)::value;
+    float ds[16];
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      float bl[4] = {nlse2, nlse2, nlse2, nlse2};
+      if (BIAS) {
+        bl[0] = fmaf(__uint_as_float(bz[g].x << 16), LOG2E, nlse2);
+        bl[1] = fmaf(__uint_as_float(bz[g].x & 0xffff0000u), LOG2E, nlse2);
+        bl[2] = fmaf(__uint_as_float(bz[g].y << 16), LOG2E, nlse2);
+        bl[3] = fmaf(__uint_as_float(bz[g].y & 0xffff0000u), LOG2E, nlse2);
+      }
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        float pe = fast_exp2(fmaf(sa[4 * g + e], c1, bl[e]));
+        if (edge) {
+          const int key = k0 + 8 * g + 4 * hl + e;
+          const bool dead = key >= p.S || (CAUSAL && key > q);
+          pe = dead ? 0.f : pe;
+        }
+        ds[4 * g + e] = pe * (pa[4 * g + e] - delta);
+      }
+    }
+    df[0] = pack8(&ds[0]);
+    df[1] = pack8(&ds[8]);
+  };
+  auto stage_b = [&](int buf, const bf16x8 (&df)[2]) {
+    const uint16_t* sK = slot + buf * BUF;
+#pragma unroll
+    for (int hb = 0; hb < 2; ++hb) {
+      bf16x8 kt_[DB];
+#pragma unroll
+      for (int db = 0; db < DB; ++db) kt_[db] = lds_tr<LDK>(sK, 16 * hb, 32 * db, lane);
+#pragma unroll
+      for (int db = 0; db < DB; ++db) acc[db] = mfma(kt_[db], df[hb], acc[db]);
+    }
+  };
+  auto step = [&](int j, int buf, const f32x16& sc, const f32x16& pc, f32x16& sn, f32x16& pn, auto edge_tag) {
+    uint2 bz[4];
+    if (BIAS) {
+#pragma unroll
+      for (int g = 0; g < 4; ++g) { bz[g] = bzc[g]; bzc[g] = bzn[g]; }
+    }
+    lstore(buf ^ 1);
+    gload(min(j + 2 * NG, jlast));
+    stage_a(buf ^ 1, sn, pn);
+    bf16x8 df[2];
+    stage_v(j * SUB, sc, pc, bz, df, edge_tag);
+    stage_b(buf, df);
+    __builtin_amdgcn_sched_group_barrier(0x200, 2 * CPT, 0);
+    __builtin_amdgcn_sched_group_barrier(0x020, 2 * CPT + (BIAS ? 4 : 0), 0);
+    __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+#pragma unroll
+    for (int t = 0; t < 2 * KS; ++t) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+      __builtin_amdgcn_sched_group_barrier(0x002, 6, 0);
+    }
+    __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+#pragma unroll
+    for (int t = 0; t < 2 * DB; ++t) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+    }
+  };
+  auto is_edge = [&](int j) { return (j * SUB + SUB > p.S) || (CAUSAL && j * SUB + SUB - 1 > q0); };
+
+  if (n > 0) {
+    f32x16 sA, pA, sB, pB;
+    lstore(0);
+    if (BIAS) {
+#pragma unroll
+      for (int g = 0; g < 4; ++g) bzc[g] = bzn[g];
+    }
+    gload(min(j0 + NG, jlast));
+    stage_a(0, sA, pA);
+    for (int i = 0; i < n; i += 2) {
+      const int j = j0 + i * NG;
+      if (is_edge(j)) step(j, 0, sA, pA, sB, pB, std::true_type{});
+      else step(j, 0, sA, pA, sB, pB, std::false_type{});
+      if (i + 1 >= n) break;
+      if (is_edge(j + NG)) step(j + NG, 1, sB, pB, sA, pA, std::true_type{});
+      else step(j + NG, 1, sB, pB, sA, pA, std::false_type{});
+    }
+  }
+
+  if (NG > 1) {
+    f32x4* mb = (f32x4*)smem;
+#pragma unroll
+    for (int s = NG / 2; s >= 1; s >>= 1) {
+      __syncthreads();
+      if (grp >= s && grp < 2 * s) {
+        f32x4* my = mb + (size_t)(grp - s) * MSLOT + lane;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+          for (int g = 0; g < 4; ++g)
+            my[(4 * db + g) * 64] = f32x4{acc[db][4 * g], acc[db][4 * g + 1], acc[db][4 * g + 2], acc[db][4 * g + 3]};
+      }
+      __syncthreads();
+      if (grp < s) {
+        const f32x4* o = mb + (size_t)grp * MSLOT + lane;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            const f32x4 x = o[(4 * db + g) * 64];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) acc[db][4 * g + e] += x[e];
+          }
+      }
+    }
+    if (grp > 0) return;
+  }
+  if (q >= p.S) return;
+  uint16_t* out = (uint16_t*)p.dQ + base + (int64_t)q * p.ss;
+#pragma unroll
+  for (int db = 0; db < DB; ++db)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const int d0 = 32 * db + 8 * g + 4 * hl;
+      uint2 o;
+      o.x = (uint32_t)f2bf(acc[db][4 * g] * p.scale) | ((uint32_t)f2bf(acc[db][4 * g + 1] * p.scale) << 16);
+      o.y = (uint32_t)f2bf(acc[db][4 * g + 2] * p.scale) | ((uint32_t)f2bf(acc[db][4 * g + 3] * p.scale) << 16);
+      *(uint2*)(out + d0) = o;
+    }
+}
+
+template <int D, bool RECOMP>
+hipError_t fwd_wave_r(const KP& p, hipStream_t st) {
+  constexpr int NG = 4;
+  const dim3 g((p.S + 31) / 32, p.h1 - p.h0, p.b1 - p.b0);
+  const bool bias = p.bias_kind == 1, causal = p.mask_kind == 1;
+  if (bias && causal) fwd_wave_kernel<D, true, true, RECOMP, NG><<<g, 64 * NG, 0, st>>>(p);
+  else if (bias) fwd_wave_kernel<D, true, false, RECOMP, NG><<<g, 64 * NG, 0, st>>>(p);
+  else if (causal) fwd_wave_kernel<D, false, true, RECOMP, NG><<<g, 64 * NG, 0, st>>>(p);
+  else fwd_wave_kernel<D, false, false, RECOMP, NG><<<g, 64 * NG, 0, st>>>(p);
+  return hipGetLastError();
+}
+template <int D>
+hipError_t fwd_wave_d(const KP& p, bool recompute, hipStream_t st) {
+  return recompute ? fwd_wave_r<D, true>(p, st) : fwd_wave_r<D, false>(p, st);
+}
+template <int D>
+hipError_t dq_wave_d(const KP& p, hipStream_t st) {
+  constexpr int NG = 4;
+  const dim3 g((p.S + 31) / 32, p.h1 - p.h0, p.b1 - p.b0);
+  const bool bias = p.bias_kind == 1, causal = p.mask_kind == 1;
+  if (bias && causal) dq_wave_kernel<D, true, true, NG><<<g, 64 * NG, 0, st>>>(p);
+  else if (bias) dq_wave_kernel<D, true, false, NG><<<g, 64 * NG, 0, st>>>(p);
+  else if (causal) dq_wave_kernel<D, false, true, NG><<<g, 64 * NG, 0, st>>>(p);
+  else dq_wave_kernel<D, false, false, NG><<<g, 64 * NG, 0, st>>>(p);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_fast_fwd_wave(const KP& p, bool recompute, hipStream_t st) {
+  switch (p.D) {
+    case 32: return fwd_wave_d<32>(p, recompute, st);
+    case 64: return fwd_wave_d<64>(p, recompute, st);
+    case 128: return fwd_wave_d<128>(p, recompute, st);
+    default: return hipErrorInvalidValue;
+  }
+}
+hipError_t launch_fast_dq_wave(const KP& p, hipStream_t st) {
+  switch (p.D) {
+    case 32: return dq_wave_d<32>(p, st);
+    case 64: return dq_wave_d<64>(p, st);
+    case 128: return dq_wave_d<128>(p, st);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+}  // namespace ssa

@@ -212,6 +212,8 @@ hipError_t launch_fast_fwd(const KP& p, bool recompute, hipStream_t st);
 hipError_t launch_fast_dq(const KP& p, hipStream_t st);
 hipError_t launch_fast_dkdv(const KP& p, hipStream_t st);
 hipError_t launch_fast_dkdv_wave(const KP& p, hipStream_t st);
+hipError_t launch_fast_fwd_wave(const KP& p, bool recompute, hipStream_t st);
+hipError_t launch_fast_dq_wave(const KP& p, hipStream_t st);
 hipError_t launch_fast_dbias(const KP& p, hipStream_t st);
 
 }  // namespace ssa
