@@ -20,17 +20,47 @@ __device__ inline BlockId heavy_first_block_id() {
   return b;
 }
 
-// coalesced fetch of a 32-row sub-tile (rows clamped to S-1): lane l takes the 16-byte chunks
-// l, l+64, ... (chunk i = row i / (D/8), columns 8 * (i % (D/8)) ..)
+// Buffer descriptor over one (row, head) slice of a [.., S, .., D] bf16 tensor whose rows are
+// `ss` elements apart: loads past the last valid row return zeros, so the staging loads need
+// neither clamps nor branches.  The slice must span less than 2 GiB (checked on the host).
+__device__ inline __amdgpu_buffer_rsrc_t slice_rsrc(const uint16_t* base, int64_t ss, int S, int D) {
+  return __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, (int)(((int64_t)(S - 1) * ss + D) * 2), 0x00020000);
+}
+// coalesced fetch of a 32-row sub-tile: lane l takes the 16-byte chunks l, l+64, ... (chunk i =
+// row i / (D/8), columns 8 * (i % (D/8)) ..).  `row0` is uniform over the wavefront, so every
+// chunk is addressed by a scalar offset plus the lane's constant byte offset
+// `loff` = ((l / (D/8)) * ss + 8 * (l % (D/8))) * 2: no vector arithmetic per load.
 template <int D>
-__device__ inline void sub_load(u32x4 (&dst)[D / 16], const uint16_t* base, int64_t ss, int row0, int S, int lane) {
-  constexpr int CPR = D / 8;
+__device__ inline void sub_load(u32x4 (&dst)[D / 16], __amdgpu_buffer_rsrc_t rs, int64_t ss, int row0, uint32_t loff) {
+  constexpr int RSTEP = 64 / (D / 8);
+  const uint32_t so = (uint32_t)row0 * (uint32_t)ss * 2u, step = (uint32_t)RSTEP * (uint32_t)ss * 2u;
 #pragma unroll
-  for (int c = 0; c < D / 16; ++c) {
-    const int idx = lane + c * 64, row = min(row0 + idx / CPR, S - 1), col = (idx % CPR) * 8;
-    dst[c] = *(const u32x4*)(base + (int64_t)row * ss + col);
+  for (int c = 0; c < D / 16; ++c) dst[c] = __builtin_amdgcn_raw_buffer_load_b128(rs, loff, so + c * step, 0);
+}
+// O accumulators *= alpha, for the rare step on which the running maximum is raised.  Written so that
+// the accumulators stay in the accumulation registers on the common path: as ordinary C++ the
+// compiler copies all of them to vector registers and back around the branch on every step.
+// The wait states cover a matrix operation that may still be writing the accumulators.
+template <int DB>
+__device__ inline void rescale_acc(f32x16 (&o)[DB], float alpha) {
+#pragma unroll
+  for (int db = 0; db < DB; ++db) {
+    float t[16], tmp;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) t[v] = o[db][v];
+#define SS_RS(i) "v_accvgpr_read_b32 %16, %" #i "\n\tv_mul_f32 %16, %16, %17\n\tv_accvgpr_write_b32 %" #i ", %16\n\t"
+    asm volatile("s_nop 15\n\ts_nop 15\n\t" SS_RS(0) SS_RS(1) SS_RS(2) SS_RS(3) SS_RS(4) SS_RS(5) SS_RS(6) SS_RS(7)
+                     SS_RS(8) SS_RS(9) SS_RS(10) SS_RS(11) SS_RS(12) SS_RS(13) SS_RS(14) SS_RS(15) "s_nop 7"
+                 : "+a"(t[0]), "+a"(t[1]), "+a"(t[2]), "+a"(t[3]), "+a"(t[4]), "+a"(t[5]), "+a"(t[6]), "+a"(t[7]),
+                   "+a"(t[8]), "+a"(t[9]), "+a"(t[10]), "+a"(t[11]), "+a"(t[12]), "+a"(t[13]), "+a"(t[14]),
+                   "+a"(t[15]), "=&v"(tmp)
+                 : "v"(alpha));
+#undef SS_RS
+#pragma unroll
+    for (int v = 0; v < 16; ++v) o[db][v] = t[v];
   }
 }
+
 template <int D, int LD>
 __device__ inline void sub_store(uint16_t* t, const u32x4 (&src)[D / 16], int lane) {
   constexpr int CPR = D / 8;
@@ -63,7 +93,8 @@ __global__ __launch_bounds__(64 * NG) void fwd_wave_kernel(KP p) {
   constexpr int MERGE = (NG / 2) * MSLOT * 8;
   constexpr int LDS_ELEMS = NG * SLOT > MERGE ? NG * SLOT : MERGE;
   __shared__ __attribute__((aligned(16))) uint16_t smem[LDS_ELEMS];
-  const int lane = threadIdx.x & 63, grp = threadIdx.x >> 6, r = lane & 31, hl = lane >> 5;
+  const int lane = threadIdx.x & 63, r = lane & 31, hl = lane >> 5;
+  const int grp = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // uniform: scalar registers
   uint16_t* slot = smem + grp * SLOT;
   const BlockId blk = heavy_first_block_id();
   const int h = p.h0 + blk.y, b = p.b0 + blk.z;
@@ -77,17 +108,19 @@ __global__ __launch_bounds__(64 * NG) void fwd_wave_kernel(KP p) {
   const uint16_t* Vb = (const uint16_t*)p.V + base;
   const uint16_t* bias_row = BIAS ? (const uint16_t*)p.bias + ((int64_t)h * p.S + qc) * p.S : nullptr;
   const float c1 = p.scale * LOG2E;
+  const uint32_t loff = ((uint32_t)(lane / (D / 8)) * (uint32_t)p.ss + 8u * (lane % (D / 8))) * 2u;
 
   const int nj = CAUSAL ? min(nsub, qb + 1) : nsub;  // key sub-tiles with a visible key
   const int j0 = grp;
   const int n = j0 < nj ? (nj - 1 - j0) / NG + 1 : 0;
   const int jlast = j0 + (n - 1) * NG;
 
+  const __amdgpu_buffer_rsrc_t rsK = slice_rsrc(Kb, p.ss, p.S, D), rsV = slice_rsrc(Vb, p.ss, p.S, D);
   u32x4 pk[CPT], pv[CPT];
   uint2 bzn[4], bzc[4];  // bias slices of the sub-tile in flight / of the one about to be used
   auto gload = [&](int j) {
-    sub_load<D>(pk, Kb, p.ss, j * SUB, p.S, lane);
-    sub_load<D>(pv, Vb, p.ss, j * SUB, p.S, lane);
+    sub_load<D>(pk, rsK, p.ss, j * SUB, loff);
+    sub_load<D>(pv, rsV, p.ss, j * SUB, loff);
     if (BIAS) {
 #pragma unroll
       for (int g = 0; g < 4; ++g) bzn[g] = *(const uint2*)(bias_row + min(j * SUB + 8 * g + 4 * hl, p.S - 4));
@@ -102,7 +135,7 @@ __global__ __launch_bounds__(64 * NG) void fwd_wave_kernel(KP p) {
   bf16x8 qf[KS];
   {
     u32x4 pq[CPT];
-    sub_load<D>(pq, Qb, p.ss, q0, p.S, lane);
+    sub_load<D>(pq, slice_rsrc(Qb, p.ss, p.S, D), p.ss, q0, loff);
     if (n > 0) gload(j0);
     sub_store<D, LDK>(slot + BUF, pq, lane);
 #pragma unroll
@@ -127,8 +160,7 @@ __global__ __launch_bounds__(64 * NG) void fwd_wave_kernel(KP p) {
     for (int ks = 0; ks < KS; ++ks) sa = mfma(fk[ks], qf[ks], sa);
   };
   // online softmax of one 32-key block; leaves P as packed bf16 operands
-  auto softmax = [&](int k0, f32x16 sa, const uint2* bz, bf16x8 (&pf)[2], auto edge_tag) {
-    constexpr bool edge = decltype(edge_tag)::value;
+  auto softmax = [&](int k0, f32x16 sa, const uint2* bz, bf16x8 (&pf)[2], bool edge) {
     if (BIAS) {
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
@@ -139,7 +171,7 @@ __global__ __launch_bounds__(64 * NG) void fwd_wave_kernel(KP p) {
         sa[4 * g + 3] = fmaf(sa[4 * g + 3], c1, __uint_as_float(u.y & 0xffff0000u) * LOG2E);
       }
     }
-    if (edge) {
+    if (edge) {  // uniform; touches the scores only, so the rest of the step is one code path
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
         const int key = k0 + key_of(v, hl);
@@ -159,10 +191,7 @@ __global__ __launch_bounds__(64 * NG) void fwd_wave_kernel(KP p) {
       const float alpha = fast_exp2(m - mn);
       m = mn;
       l *= alpha;
-#pragma unroll
-      for (int db = 0; db < DB; ++db)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) oacc[db][v] *= alpha;
+      rescale_acc<DB>(oacc, alpha);
     }
     float lsum = 0.f;
     float pr[16];
@@ -187,40 +216,33 @@ __global__ __launch_bounds__(64 * NG) void fwd_wave_kernel(KP p) {
       for (int db = 0; db < DB; ++db) oacc[db] = mfma(vf[db], pf[t], oacc[db]);
     }
   };
-  // one step: sub-tile j sits in LDS buffer `buf` with its scores in sc; the registers hold
-  // sub-tile j+NG (clamped to the wavefront's last one), which moves to the other buffer and has
-  // its scores computed into sn while the vector ALUs work on sc
-  auto step = [&](int j, int buf, const f32x16& sc, f32x16& sn, auto edge_tag) {
-    uint2 bz[4];
-    if (BIAS) {
-#pragma unroll
-      for (int g = 0; g < 4; ++g) { bz[g] = bzc[g]; bzc[g] = bzn[g]; }
-    }
-    lstore(buf ^ 1);
-    gload(min(j + 2 * NG, jlast));
-    stage_s(buf ^ 1, sn);
-    bf16x8 pf[2];
-    softmax(j * SUB, sc, bz, pf, edge_tag);
-    stage_pv(buf, pf);
-  };
-  auto is_edge = [&](int j) { return (j * SUB + SUB > p.S) || (CAUSAL && j * SUB + SUB - 1 > q0); };
 
   if (n > 0) {
-    f32x16 sA, sB;
+    f32x16 sc, sn;
     lstore(0);
     if (BIAS) {
 #pragma unroll
       for (int g = 0; g < 4; ++g) bzc[g] = bzn[g];
     }
     gload(min(j0 + NG, jlast));
-    stage_s(0, sA);
-    for (int i = 0; i < n; i += 2) {
-      const int j = j0 + i * NG;
-      if (is_edge(j)) step(j, 0, sA, sB, std::true_type{});
-      else step(j, 0, sA, sB, std::false_type{});
-      if (i + 1 >= n) break;
-      if (is_edge(j + NG)) step(j + NG, 1, sB, sA, std::true_type{});
-      else step(j + NG, 1, sB, sA, std::false_type{});
+    stage_s(0, sc);
+    // one step: sub-tile j sits in LDS buffer `buf` with its scores in sc; the registers hold sub-tile
+    // j+NG (clamped to the wavefront's last one), which moves to the other buffer and has its scores
+    // computed into sn while the vector ALUs work on sc
+    for (int i = 0; i < n; ++i) {
+      const int j = j0 + i * NG, buf = i & 1;
+      uint2 bz[4];
+      if (BIAS) {
+#pragma unroll
+        for (int g = 0; g < 4; ++g) { bz[g] = bzc[g]; bzc[g] = bzn[g]; }
+      }
+      lstore(buf ^ 1);
+      gload(min(j + 2 * NG, jlast));
+      stage_s(buf ^ 1, sn);
+      bf16x8 pf[2];
+      softmax(j * SUB, sc, bz, pf, (j * SUB + SUB > p.S) || (CAUSAL && j * SUB + SUB - 1 > q0));
+      stage_pv(buf, pf);
+      sc = sn;
     }
   }
 
@@ -280,7 +302,8 @@ __global__ __launch_bounds__(64 * NG) void dq_wave_kernel(KP p) {
   constexpr int MERGE = (NG / 2) * MSLOT * 8;
   constexpr int LDS_ELEMS = NG * SLOT > MERGE ? NG * SLOT : MERGE;
   __shared__ __attribute__((aligned(16))) uint16_t smem[LDS_ELEMS];
-  const int lane = threadIdx.x & 63, grp = threadIdx.x >> 6, r = lane & 31, hl = lane >> 5;
+  const int lane = threadIdx.x & 63, r = lane & 31, hl = lane >> 5;
+  const int grp = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // uniform: scalar registers
   uint16_t* slot = smem + grp * SLOT;
   const BlockId blk = heavy_first_block_id();
   const int h = p.h0 + blk.y, b = p.b0 + blk.z;
@@ -295,17 +318,20 @@ __global__ __launch_bounds__(64 * NG) void dq_wave_kernel(KP p) {
   const uint16_t* dOb = (const uint16_t*)p.dO + (int64_t)b * p.do_sb + (int64_t)h * p.do_sh;
   const uint16_t* bias_row = BIAS ? (const uint16_t*)p.bias + ((int64_t)h * p.S + qc) * p.S : nullptr;
   const float c1 = p.scale * LOG2E;
+  const uint32_t loff = ((uint32_t)(lane / (D / 8)) * (uint32_t)p.ss + 8u * (lane % (D / 8))) * 2u;
+  const uint32_t loff_g = ((uint32_t)(lane / (D / 8)) * (uint32_t)p.do_ss + 8u * (lane % (D / 8))) * 2u;
 
   const int nj = CAUSAL ? min(nsub, qb + 1) : nsub;
   const int j0 = grp;
   const int n = j0 < nj ? (nj - 1 - j0) / NG + 1 : 0;
   const int jlast = j0 + (n - 1) * NG;
 
+  const __amdgpu_buffer_rsrc_t rsK = slice_rsrc(Kb, p.ss, p.S, D), rsV = slice_rsrc(Vb, p.ss, p.S, D);
   u32x4 pk[CPT], pv[CPT];
   uint2 bzn[4], bzc[4];
   auto gload = [&](int j) {
-    sub_load<D>(pk, Kb, p.ss, j * SUB, p.S, lane);
-    sub_load<D>(pv, Vb, p.ss, j * SUB, p.S, lane);
+    sub_load<D>(pk, rsK, p.ss, j * SUB, loff);
+    sub_load<D>(pv, rsV, p.ss, j * SUB, loff);
     if (BIAS) {
 #pragma unroll
       for (int g = 0; g < 4; ++g) bzn[g] = *(const uint2*)(bias_row + min(j * SUB + 8 * g + 4 * hl, p.S - 4));
@@ -320,8 +346,8 @@ __global__ __launch_bounds__(64 * NG) void dq_wave_kernel(KP p) {
   bf16x8 qf[KS], gf[KS];
   {
     u32x4 pq[CPT], pg[CPT];
-    sub_load<D>(pq, Qb, p.ss, q0, p.S, lane);
-    sub_load<D>(pg, dOb, p.do_ss, q0, p.S, lane);
+    sub_load<D>(pq, slice_rsrc(Qb, p.ss, p.S, D), p.ss, q0, loff);
+    sub_load<D>(pg, slice_rsrc(dOb, p.do_ss, p.S, D), p.do_ss, q0, loff_g);
     if (n > 0) gload(j0);
     sub_store<D, LDK>(slot + BUF, pq, lane);
     sub_store<D, LDV>(slot + BUF + SUB * LDK, pg, lane);
