@@ -382,9 +382,8 @@ __global__ __launch_bounds__(64 * NG) void dq_wave_kernel(KP p) {
       pa = mfma(fv[ks], gf[ks], pa);
     }
   };
-  auto stage_v = [&](int k0, const f32x16& sa, const f32x16& pa, const uint2* bz, bf16x8 (&df)[2], auto edge_tag) {
-    constexpr bool edge = decltype(edge_tag)::value;
-    float ds[16];
+  auto stage_v = [&](int k0, const f32x16& sa, const f32x16& pa, const uint2* bz, bf16x8 (&df)[2], bool edge) {
+    float pe[16];
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
       float bl[4] = {nlse2, nlse2, nlse2, nlse2};
@@ -395,16 +394,19 @@ __global__ __launch_bounds__(64 * NG) void dq_wave_kernel(KP p) {
         bl[3] = fmaf(__uint_as_float(bz[g].y & 0xffff0000u), LOG2E, nlse2);
       }
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        float pe = fast_exp2(fmaf(sa[4 * g + e], c1, bl[e]));
-        if (edge) {
-          const int key = k0 + 8 * g + 4 * hl + e;
-          const bool dead = key >= p.S || (CAUSAL && key > q);
-          pe = dead ? 0.f : pe;
-        }
-        ds[4 * g + e] = pe * (pa[4 * g + e] - delta);
+      for (int e = 0; e < 4; ++e) pe[4 * g + e] = fast_exp2(fmaf(sa[4 * g + e], c1, bl[e]));
+    }
+    if (edge) {  // uniform; touches P only, so the rest of the step is one code path
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int key = k0 + key_of(v, hl);
+        const bool dead = key >= p.S || (CAUSAL && key > q);
+        pe[v] = dead ? 0.f : pe[v];
       }
     }
+    float ds[16];
+#pragma unroll
+    for (int v = 0; v < 16; ++v) ds[v] = pe[v] * (pa[v] - delta);
     df[0] = pack8(&ds[0]);
     df[1] = pack8(&ds[8]);
   };
@@ -419,52 +421,34 @@ __global__ __launch_bounds__(64 * NG) void dq_wave_kernel(KP p) {
       for (int db = 0; db < DB; ++db) acc[db] = mfma(kt_[db], df[hb], acc[db]);
     }
   };
-  auto step = [&](int j, int buf, const f32x16& sc, const f32x16& pc, f32x16& sn, f32x16& pn, auto edge_tag) {
-    uint2 bz[4];
-    if (BIAS) {
-#pragma unroll
-      for (int g = 0; g < 4; ++g) { bz[g] = bzc[g]; bzc[g] = bzn[g]; }
-    }
-    lstore(buf ^ 1);
-    gload(min(j + 2 * NG, jlast));
-    stage_a(buf ^ 1, sn, pn);
-    bf16x8 df[2];
-    stage_v(j * SUB, sc, pc, bz, df, edge_tag);
-    stage_b(buf, df);
-    __builtin_amdgcn_sched_group_barrier(0x200, 2 * CPT, 0);
-    __builtin_amdgcn_sched_group_barrier(0x020, 2 * CPT + (BIAS ? 4 : 0), 0);
-    __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
-#pragma unroll
-    for (int t = 0; t < 2 * KS; ++t) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-      __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
-      __builtin_amdgcn_sched_group_barrier(0x002, 6, 0);
-    }
-    __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
-#pragma unroll
-    for (int t = 0; t < 2 * DB; ++t) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-      __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
-    }
-  };
-  auto is_edge = [&](int j) { return (j * SUB + SUB > p.S) || (CAUSAL && j * SUB + SUB - 1 > q0); };
 
   if (n > 0) {
-    f32x16 sA, pA, sB, pB;
+    f32x16 sc, pc, sn, pn;
     lstore(0);
     if (BIAS) {
 #pragma unroll
       for (int g = 0; g < 4; ++g) bzc[g] = bzn[g];
     }
     gload(min(j0 + NG, jlast));
-    stage_a(0, sA, pA);
-    for (int i = 0; i < n; i += 2) {
-      const int j = j0 + i * NG;
-      if (is_edge(j)) step(j, 0, sA, pA, sB, pB, std::true_type{});
-      else step(j, 0, sA, pA, sB, pB, std::false_type{});
-      if (i + 1 >= n) break;
-      if (is_edge(j + NG)) step(j + NG, 1, sB, pB, sA, pA, std::true_type{});
-      else step(j + NG, 1, sB, pB, sA, pA, std::false_type{});
+    stage_a(0, sc, pc);
+    // one step: sub-tile j sits in LDS buffer `buf` with its products in (sc, pc); the registers hold
+    // sub-tile j+NG (clamped to the wavefront's last one), which moves to the other buffer and is
+    // multiplied into (sn, pn) while the vector ALUs work on (sc, pc)
+    for (int i = 0; i < n; ++i) {
+      const int j = j0 + i * NG, buf = i & 1;
+      uint2 bz[4];
+      if (BIAS) {
+#pragma unroll
+        for (int g = 0; g < 4; ++g) { bz[g] = bzc[g]; bzc[g] = bzn[g]; }
+      }
+      lstore(buf ^ 1);
+      gload(min(j + 2 * NG, jlast));
+      stage_a(buf ^ 1, sn, pn);
+      bf16x8 df[2];
+      stage_v(j * SUB, sc, pc, bz, df, (j * SUB + SUB > p.S) || (CAUSAL && j * SUB + SUB - 1 > q0));
+      stage_b(buf, df);
+      sc = sn;
+      pc = pn;
     }
   }
 
