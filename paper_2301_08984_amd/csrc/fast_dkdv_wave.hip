@@ -28,7 +28,8 @@ __global__ __launch_bounds__(64 * QG) void dkdv_wave_kernel(KP p) {
   constexpr int MERGE = (QG / 2) * 64 * 32 * DB * 2;
   constexpr int LDS_ELEMS = QG * SLOT > MERGE ? QG * SLOT : MERGE;
   __shared__ __attribute__((aligned(16))) uint16_t smem[LDS_ELEMS];
-  const int lane = threadIdx.x & 63, grp = threadIdx.x >> 6, r = lane & 31, hl = lane >> 5;
+  const int lane = threadIdx.x & 63, r = lane & 31, hl = lane >> 5;
+  const int grp = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // uniform: scalar registers
   uint16_t* slot = smem + grp * SLOT;
   float* sstat = (float*)(slot + 4 * MAT);
   // heaviest key blocks first over the whole launch (block 0 of every head, then block 1, ...): when
@@ -71,15 +72,24 @@ __global__ __launch_bounds__(64 * QG) void dkdv_wave_kernel(KP p) {
   const int n = j0 < nsub ? (nsub - 1 - j0) / QG + 1 : 0;
   const int jlast = j0 + (n - 1) * QG;
 
+  // bounds-checked staging loads: a scalar offset per chunk plus the lane's constant byte offset, zeros
+  // past the last row (the slices span less than 2 GiB: checked on the host)
+  const __amdgpu_buffer_rsrc_t rsQ = __builtin_amdgcn_make_buffer_rsrc(
+      (void*)Qb, 0, (int)(((int64_t)(p.S - 1) * p.ss + D) * 2), 0x00020000);
+  const __amdgpu_buffer_rsrc_t rsG = __builtin_amdgcn_make_buffer_rsrc(
+      (void*)dOb, 0, (int)(((int64_t)(p.S - 1) * p.do_ss + D) * 2), 0x00020000);
+  const uint32_t loff_q = ((uint32_t)(lane / CPR) * (uint32_t)p.ss + 8u * (lane % CPR)) * 2u;
+  const uint32_t loff_g = ((uint32_t)(lane / CPR) * (uint32_t)p.do_ss + 8u * (lane % CPR)) * 2u;
   u32x4 pq[CPT], pg[CPT];
   float pstat = 0.f;
   uint2 bzn[4], bzc[4];  // bias slices of the sub-tile in the registers / of the one about to be used
   auto gload = [&](int j) {
+    const uint32_t so_q = (uint32_t)(j * SUB) * (uint32_t)p.ss * 2u, st_q = (uint32_t)(64 / CPR) * (uint32_t)p.ss * 2u;
+    const uint32_t so_g = (uint32_t)(j * SUB) * (uint32_t)p.do_ss * 2u, st_g = (uint32_t)(64 / CPR) * (uint32_t)p.do_ss * 2u;
 #pragma unroll
     for (int c = 0; c < CPT; ++c) {
-      const int idx = lane + c * 64, row = min(j * SUB + idx / CPR, p.S - 1), col = (idx % CPR) * 8;
-      pq[c] = *(const u32x4*)(Qb + (int64_t)row * p.ss + col);
-      pg[c] = *(const u32x4*)(dOb + (int64_t)row * p.do_ss + col);
+      pq[c] = __builtin_amdgcn_raw_buffer_load_b128(rsQ, loff_q, so_q + c * st_q, 0);
+      pg[c] = __builtin_amdgcn_raw_buffer_load_b128(rsG, loff_g, so_g + c * st_g, 0);
     }
     const int i = min(j * SUB + r, p.S - 1);
     pstat = hl == 0 ? lse_b[i] : dl_b[i];
@@ -120,15 +130,13 @@ __global__ __launch_bounds__(64 * QG) void dkdv_wave_kernel(KP p) {
   };
   // P and dS as packed bf16 operands
   auto stage_v = [&](int buf, int i0, const f32x16& sa, const f32x16& pa, const uint2* bz, bf16x8 (&pf)[2],
-                     bf16x8 (&df)[2], auto edge_tag) {
-    constexpr bool edge = decltype(edge_tag)::value;
+                     bf16x8 (&df)[2], bool edge) {
     const float* tl = sstat + buf * 2 * SUB;
     const float* td = tl + SUB;
     float pr[16], ds[16];
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
       const f32x4 l4 = *(const f32x4*)(tl + 8 * g + 4 * hl);
-      const f32x4 d4 = *(const f32x4*)(td + 8 * g + 4 * hl);
       float bl[4] = {0.f, 0.f, 0.f, 0.f};
       if (BIAS) {
         const uint2 u = bz[g];
@@ -136,16 +144,21 @@ __global__ __launch_bounds__(64 * QG) void dkdv_wave_kernel(KP p) {
         bl[2] = __uint_as_float(u.y << 16) * LOG2E; bl[3] = __uint_as_float(u.y & 0xffff0000u) * LOG2E;
       }
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        float pe = fast_exp2(fmaf(sa[4 * g + e], c1, BIAS ? bl[e] + l4[e] : l4[e]));
-        if (edge) {
-          const int i = i0 + 8 * g + 4 * hl + e;
-          const bool dead = i >= p.S || key >= p.S || (CAUSAL && key > i);
-          pe = dead ? 0.f : pe;
-        }
-        pr[4 * g + e] = pe;
-        ds[4 * g + e] = pe * (pa[4 * g + e] - d4[e]);
+      for (int e = 0; e < 4; ++e) pr[4 * g + e] = fast_exp2(fmaf(sa[4 * g + e], c1, BIAS ? bl[e] + l4[e] : l4[e]));
+    }
+    if (edge) {  // uniform; touches P only, so the rest of the step is one code path
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int i = i0 + key_of(v, hl);
+        const bool dead = i >= p.S || key >= p.S || (CAUSAL && key > i);
+        pr[v] = dead ? 0.f : pr[v];
       }
+    }
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const f32x4 d4 = *(const f32x4*)(td + 8 * g + 4 * hl);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) ds[4 * g + e] = pr[4 * g + e] * (pa[4 * g + e] - d4[e]);
     }
     pf[0] = pack8(&pr[0]); pf[1] = pack8(&pr[8]);
     df[0] = pack8(&ds[0]); df[1] = pack8(&ds[8]);
@@ -169,42 +182,9 @@ __global__ __launch_bounds__(64 * QG) void dkdv_wave_kernel(KP p) {
       }
     }
   };
-  // one step: sub-tile j sits in LDS buffer `buf` with its scores in (sc, pc); the registers hold
-  // sub-tile j+QG (clamped to the wavefront's last one), which moves to the other buffer and has
-  // its scores computed into (sn, pn) while the vector ALUs work on (sc, pc)
-  auto step = [&](int j, int buf, const f32x16& sc, const f32x16& pc, f32x16& sn, f32x16& pn, auto edge_tag) {
-    uint2 bz[4];
-    if (BIAS) {
-#pragma unroll
-      for (int g = 0; g < 4; ++g) { bz[g] = bzc[g]; bzc[g] = bzn[g]; }
-    }
-    lstore(buf ^ 1);
-    gload(min(j + 2 * QG, jlast));
-    bf16x8 pf[2], df[2];
-    stage_a(buf ^ 1, sn, pn);
-    stage_v(buf, j * SUB, sc, pc, bz, pf, df, edge_tag);
-    stage_b(buf, pf, df);
-    // LDS stores, then next scores (16 matrix ops) under the vector-ALU work, then the gradient products
-    __builtin_amdgcn_sched_group_barrier(0x200, 2 * CPT + 1, 0);
-    __builtin_amdgcn_sched_group_barrier(0x020, 2 * CPT + 2, 0);
-    __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
-#pragma unroll
-    for (int q = 0; q < 2 * KS; ++q) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-      __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
-      __builtin_amdgcn_sched_group_barrier(0x002, 8, 0);
-    }
-    __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
-#pragma unroll
-    for (int q = 0; q < 4 * DB; ++q) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-      __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
-    }
-  };
-  auto is_edge = [&](int j) { return (j * SUB + SUB > p.S) || (k0 + 32 > p.S) || (CAUSAL && j * SUB < k0 + 31); };
 
   if (n > 0) {
-    f32x16 sA, pA, sB, pB;
+    f32x16 sc, pc, sn, pn;
     gload(j0);
     lstore(0);
     if (BIAS) {
@@ -212,14 +192,26 @@ __global__ __launch_bounds__(64 * QG) void dkdv_wave_kernel(KP p) {
       for (int g = 0; g < 4; ++g) bzc[g] = bzn[g];
     }
     gload(min(j0 + QG, jlast));
-    stage_a(0, sA, pA);
-    for (int i = 0; i < n; i += 2) {
-      const int j = j0 + i * QG;
-      if (is_edge(j)) step(j, 0, sA, pA, sB, pB, std::true_type{});
-      else step(j, 0, sA, pA, sB, pB, std::false_type{});
-      if (i + 1 >= n) break;
-      if (is_edge(j + QG)) step(j + QG, 1, sB, pB, sA, pA, std::true_type{});
-      else step(j + QG, 1, sB, pB, sA, pA, std::false_type{});
+    stage_a(0, sc, pc);
+    // one step: sub-tile j sits in LDS buffer `buf` with its scores in (sc, pc); the registers hold
+    // sub-tile j+QG (clamped to the wavefront's last one), which moves to the other buffer and has
+    // its scores computed into (sn, pn) while the vector ALUs work on (sc, pc)
+    for (int i = 0; i < n; ++i) {
+      const int j = j0 + i * QG, buf = i & 1;
+      uint2 bz[4];
+      if (BIAS) {
+#pragma unroll
+        for (int g = 0; g < 4; ++g) { bz[g] = bzc[g]; bzc[g] = bzn[g]; }
+      }
+      lstore(buf ^ 1);
+      gload(min(j + 2 * QG, jlast));
+      bf16x8 pf[2], df[2];
+      stage_a(buf ^ 1, sn, pn);
+      stage_v(buf, j * SUB, sc, pc, bz, pf, df,
+              (j * SUB + SUB > p.S) || (k0 + 32 > p.S) || (CAUSAL && j * SUB < k0 + 31));
+      stage_b(buf, pf, df);
+      sc = sn;
+      pc = pn;
     }
   }
 
