@@ -188,7 +188,8 @@ inline bool fast_ok(const KP& p) {
 // Work-group shape of the forward / dQ kernels: query wavefronts x key-tile groups.  Large shares
 // use 4x1 (many independent work-groups per compute unit); when the whole share offers fewer than
 // two 128-query work-groups per compute unit the key tiles are split over groups inside the
-// work-group (4x2), and below one per compute unit the work-group also covers fewer queries (2x4).
+// work-group (4x2); below one per compute unit (2x4) separate kernels take over whose work-groups
+// own 32 queries (forward, dQ) or 32 keys (dK/dV) and whose four wavefronts split the other axis.
 // Decided from the share, never from the chunk.
 // Rows per group of the tiled bias-gradient kernel: 0 = one group (the sum continues in the output);
 // otherwise the share's rows are cut into groups so that about two work-groups per compute unit exist.
@@ -202,7 +203,11 @@ enum WgShape { WG_4x1, WG_4x2, WG_2x4 };
 inline WgShape wg_shape(const KP& p) {
   const int64_t wgs = (int64_t)((p.S + 127) / 128) * p.share_units;
   if (wgs >= 512 || p.S < 512) return WG_4x1;
-  return wgs >= 256 ? WG_4x2 : WG_2x4;
+  if (wgs >= 256) return WG_4x2;
+  // the kernels of the smallest shape address one (row, head) slice with 32-bit buffer offsets
+  const int64_t row_stride = p.ss > (int64_t)p.H * p.D ? p.ss : (int64_t)p.H * p.D;
+  if (((int64_t)(p.S - 1) * row_stride + p.D) * 2 >= (1ll << 31)) return WG_4x2;
+  return WG_2x4;
 }
 
 }  // namespace
