@@ -129,8 +129,8 @@ __global__ __launch_bounds__(64 * QG) void dkdv_wave_kernel(KP p) {
     }
   };
   // P and dS as packed bf16 operands
-  auto stage_v = [&](int buf, int i0, const f32x16& sa, const f32x16& pa, const uint2* bz, bf16x8 (&pf)[2],
-                     bf16x8 (&df)[2], bool edge) {
+  auto stage_v = [&](int buf, const f32x16& sa, const f32x16& pa, const uint2* bz, bf16x8 (&pf)[2],
+                     bf16x8 (&df)[2]) {
     const float* tl = sstat + buf * 2 * SUB;
     const float* td = tl + SUB;
     float pr[16], ds[16];
@@ -145,14 +145,6 @@ __global__ __launch_bounds__(64 * QG) void dkdv_wave_kernel(KP p) {
       }
 #pragma unroll
       for (int e = 0; e < 4; ++e) pr[4 * g + e] = fast_exp2(fmaf(sa[4 * g + e], c1, BIAS ? bl[e] + l4[e] : l4[e]));
-    }
-    if (edge) {  // uniform; touches P only, so the rest of the step is one code path
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int i = i0 + key_of(v, hl);
-        const bool dead = i >= p.S || key >= p.S || (CAUSAL && key > i);
-        pr[v] = dead ? 0.f : pr[v];
-      }
     }
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
@@ -203,12 +195,21 @@ __global__ __launch_bounds__(64 * QG) void dkdv_wave_kernel(KP p) {
 #pragma unroll
         for (int g = 0; g < 4; ++g) { bz[g] = bzc[g]; bzc[g] = bzn[g]; }
       }
+      if ((j * SUB + SUB > p.S) || (k0 + 32 > p.S) || (CAUSAL && j * SUB < k0 + 31)) {
+        // uniform; masked scores become -inf (P = 0) before anything else, so that the rest of the
+        // step is one straight-line block
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int i = j * SUB + key_of(v, hl);
+          const bool dead = i >= p.S || key >= p.S || (CAUSAL && key > i);
+          sc[v] = dead ? -INFINITY : sc[v];
+        }
+      }
       lstore(buf ^ 1);
       gload(min(j + 2 * QG, jlast));
       bf16x8 pf[2], df[2];
       stage_a(buf ^ 1, sn, pn);
-      stage_v(buf, j * SUB, sc, pc, bz, pf, df,
-              (j * SUB + SUB > p.S) || (k0 + 32 > p.S) || (CAUSAL && j * SUB < k0 + 31));
+      stage_v(buf, sc, pc, bz, pf, df);
       stage_b(buf, pf, df);
       sc = sn;
       pc = pn;

@@ -159,8 +159,8 @@ __global__ __launch_bounds__(64 * NG) void fwd_wave_kernel(KP p) {
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) sa = mfma(fk[ks], qf[ks], sa);
   };
-  // online softmax of one 32-key block; leaves P as packed bf16 operands
-  auto softmax = [&](int k0, f32x16 sa, const uint2* bz, bf16x8 (&pf)[2], bool edge) {
+  // online softmax of one 32-key block, first half: bias, mask, row maximum, running maximum
+  auto softmax_max = [&](int k0, f32x16& sa, const uint2* bz, bool edge) {
     if (BIAS) {
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
@@ -171,7 +171,7 @@ __global__ __launch_bounds__(64 * NG) void fwd_wave_kernel(KP p) {
         sa[4 * g + 3] = fmaf(sa[4 * g + 3], c1, __uint_as_float(u.y & 0xffff0000u) * LOG2E);
       }
     }
-    if (edge) {  // uniform; touches the scores only, so the rest of the step is one code path
+    if (edge) {  // uniform; touches the scores only
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
         const int key = k0 + key_of(v, hl);
@@ -193,6 +193,9 @@ __global__ __launch_bounds__(64 * NG) void fwd_wave_kernel(KP p) {
       l *= alpha;
       rescale_acc<DB>(oacc, alpha);
     }
+  };
+  // second half: P = exp2(s - m) as packed bf16 operands, row sum
+  auto softmax_exp = [&](const f32x16& sa, bf16x8 (&pf)[2]) {
     float lsum = 0.f;
     float pr[16];
 #pragma unroll
@@ -236,11 +239,14 @@ __global__ __launch_bounds__(64 * NG) void fwd_wave_kernel(KP p) {
 #pragma unroll
         for (int g = 0; g < 4; ++g) { bz[g] = bzc[g]; bzc[g] = bzn[g]; }
       }
+      softmax_max(j * SUB, sc, bz, (j * SUB + SUB > p.S) || (CAUSAL && j * SUB + SUB - 1 > q0));
+      // from here on the step is one straight-line block: the next scores run on the matrix cores
+      // under the exponentials of the current ones
       lstore(buf ^ 1);
       gload(min(j + 2 * NG, jlast));
       stage_s(buf ^ 1, sn);
       bf16x8 pf[2];
-      softmax(j * SUB, sc, bz, pf, (j * SUB + SUB > p.S) || (CAUSAL && j * SUB + SUB - 1 > q0));
+      softmax_exp(sc, pf);
       stage_pv(buf, pf);
       sc = sn;
     }
@@ -382,7 +388,7 @@ __global__ __launch_bounds__(64 * NG) void dq_wave_kernel(KP p) {
       pa = mfma(fv[ks], gf[ks], pa);
     }
   };
-  auto stage_v = [&](int k0, const f32x16& sa, const f32x16& pa, const uint2* bz, bf16x8 (&df)[2], bool edge) {
+  auto stage_v = [&](const f32x16& sa, const f32x16& pa, const uint2* bz, bf16x8 (&df)[2]) {
     float pe[16];
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
@@ -395,14 +401,6 @@ __global__ __launch_bounds__(64 * NG) void dq_wave_kernel(KP p) {
       }
 #pragma unroll
       for (int e = 0; e < 4; ++e) pe[4 * g + e] = fast_exp2(fmaf(sa[4 * g + e], c1, bl[e]));
-    }
-    if (edge) {  // uniform; touches P only, so the rest of the step is one code path
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int key = k0 + key_of(v, hl);
-        const bool dead = key >= p.S || (CAUSAL && key > q);
-        pe[v] = dead ? 0.f : pe[v];
-      }
     }
     float ds[16];
 #pragma unroll
@@ -441,11 +439,21 @@ __global__ __launch_bounds__(64 * NG) void dq_wave_kernel(KP p) {
 #pragma unroll
         for (int g = 0; g < 4; ++g) { bz[g] = bzc[g]; bzc[g] = bzn[g]; }
       }
+      if ((j * SUB + SUB > p.S) || (CAUSAL && j * SUB + SUB - 1 > q0)) {
+        // uniform; masked scores become -inf (P = 0) before anything else, so that the rest of the
+        // step is one straight-line block
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int key = j * SUB + key_of(v, hl);
+          const bool dead = key >= p.S || (CAUSAL && key > q);
+          sc[v] = dead ? -INFINITY : sc[v];
+        }
+      }
       lstore(buf ^ 1);
       gload(min(j + 2 * NG, jlast));
       stage_a(buf ^ 1, sn, pn);
       bf16x8 df[2];
-      stage_v(j * SUB, sc, pc, bz, df, (j * SUB + SUB > p.S) || (CAUSAL && j * SUB + SUB - 1 > q0));
+      stage_v(sc, pc, bz, df);
       stage_b(buf, df);
       sc = sn;
       pc = pn;
