@@ -76,26 +76,27 @@ __device__ inline void sub_store(uint16_t* t, const u32x4 (&src)[D / 16], int la
 // 128-query work-groups.  A work-group owns one 32-query block; its NG wavefronts all
 // hold the block's Q fragments and split the keys: wavefront g takes the 32-key
 // sub-tiles g, g+NG, ...  Every wavefront stages its own sub-tiles of K and V
-// (global -> registers -> its private double-buffered LDS slot -> operand reads), so
-// the loop has no barrier: the wavefronts drift apart and one's softmax arithmetic and
-// staging overlaps the others' matrix products.  Per step the scores of the next
-// sub-tile run on the matrix cores while the vector ALUs do the softmax of the current
-// one; then P V follows.  The NG partial results (O, m, l) are folded through LDS as a
+// (global -> registers -> its private LDS slot -> operand reads), so the loop has no
+// barrier: the wavefronts drift apart and one's softmax arithmetic and staging overlaps
+// the others' matrix products (two wavefronts share each SIMD).  The slot holds one K
+// and one V sub-tile: K of sub-tile j+1 is consumed (scores, one step ahead) before V
+// of sub-tile j, so K runs two sub-tiles ahead in registers and one ahead in LDS, V one
+// ahead in registers.  The NG partial results (O, m, l) are folded through LDS as a
 // fixed binary tree, so the result does not depend on timing.
 // ---------------------------------------------------------------------------
 template <int D, bool BIAS, bool CAUSAL, bool RECOMP, int NG>
 __global__ __launch_bounds__(64 * NG) void fwd_wave_kernel(KP p) {
   constexpr int KS = D / 16, DB = D / 32, SUB = 32, CPT = D / 16;
   constexpr int LDK = D + 8, LDV = D + 16;  // row pads chosen for conflict-free b128 / transpose reads
-  constexpr int BUF = SUB * LDK + SUB * LDV;
-  constexpr int SLOT = 2 * BUF;
+  constexpr int SLOT = SUB * LDK + SUB * LDV;
   constexpr int MSLOT = 64 * (4 * DB + 1);  // f32x4 units one wavefront hands over in the merge
   constexpr int MERGE = (NG / 2) * MSLOT * 8;
   constexpr int LDS_ELEMS = NG * SLOT > MERGE ? NG * SLOT : MERGE;
   __shared__ __attribute__((aligned(16))) uint16_t smem[LDS_ELEMS];
   const int lane = threadIdx.x & 63, r = lane & 31, hl = lane >> 5;
   const int grp = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // uniform: scalar registers
-  uint16_t* slot = smem + grp * SLOT;
+  uint16_t* sK = smem + grp * SLOT;
+  uint16_t* sV = sK + SUB * LDK;
   const BlockId blk = heavy_first_block_id();
   const int h = p.h0 + blk.y, b = p.b0 + blk.z;
   const int nsub = (p.S + SUB - 1) / SUB;
@@ -114,32 +115,29 @@ __global__ __launch_bounds__(64 * NG) void fwd_wave_kernel(KP p) {
   const int j0 = grp;
   const int n = j0 < nj ? (nj - 1 - j0) / NG + 1 : 0;
   const int jlast = j0 + (n - 1) * NG;
+  auto jc = [&](int j) { return min(j, jlast); };  // past the wavefront's last sub-tile: fetch it again
 
   const __amdgpu_buffer_rsrc_t rsK = slice_rsrc(Kb, p.ss, p.S, D), rsV = slice_rsrc(Vb, p.ss, p.S, D);
   u32x4 pk[CPT], pv[CPT];
-  uint2 bzn[4], bzc[4];  // bias slices of the sub-tile in flight / of the one about to be used
-  auto gload = [&](int j) {
-    sub_load<D>(pk, rsK, p.ss, j * SUB, loff);
-    sub_load<D>(pv, rsV, p.ss, j * SUB, loff);
-    if (BIAS) {
+  uint2 bzn[4], bzc[4];  // bias slices of the next sub-tile / of the one about to be used
+  auto bload = [&](int j) {
 #pragma unroll
-      for (int g = 0; g < 4; ++g) bzn[g] = *(const uint2*)(bias_row + min(j * SUB + 8 * g + 4 * hl, p.S - 4));
-    }
-  };
-  auto lstore = [&](int buf) {
-    sub_store<D, LDK>(slot + buf * BUF, pk, lane);
-    sub_store<D, LDV>(slot + buf * BUF + SUB * LDK, pv, lane);
+    for (int g = 0; g < 4; ++g) bzn[g] = *(const uint2*)(bias_row + min(j * SUB + 8 * g + 4 * hl, p.S - 4));
   };
 
-  // Q fragments: fetched coalesced, passed through the (still unused) second buffer
+  // Q fragments: fetched coalesced, passed through the (still unused) K buffer
   bf16x8 qf[KS];
   {
     u32x4 pq[CPT];
     sub_load<D>(pq, slice_rsrc(Qb, p.ss, p.S, D), p.ss, q0, loff);
-    if (n > 0) gload(j0);
-    sub_store<D, LDK>(slot + BUF, pq, lane);
+    if (n > 0) {
+      sub_load<D>(pk, rsK, p.ss, j0 * SUB, loff);
+      sub_load<D>(pv, rsV, p.ss, j0 * SUB, loff);
+      if (BIAS) bload(j0);
+    }
+    sub_store<D, LDK>(sK, pq, lane);
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) qf[ks] = lds_nat<LDK>(slot + BUF, r, ks, hl);
+    for (int ks = 0; ks < KS; ++ks) qf[ks] = lds_nat<LDK>(sK, r, ks, hl);
   }
   f32x16 oacc[DB];
 #pragma unroll
@@ -148,9 +146,8 @@ __global__ __launch_bounds__(64 * NG) void fwd_wave_kernel(KP p) {
     for (int v = 0; v < 16; ++v) oacc[db][v] = 0.f;
   float m = -1e30f, l = 0.f;
 
-  // S^T = K Q^T of the sub-tile staged in `buf`: lane = query, registers = keys
-  auto stage_s = [&](int buf, f32x16& sa) {
-    const uint16_t* sK = slot + buf * BUF;
+  // S^T = K Q^T of the sub-tile in the K buffer: lane = query, registers = keys
+  auto stage_s = [&](f32x16& sa) {
     bf16x8 fk[KS];
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) fk[ks] = lds_nat<LDK>(sK, r, ks, hl);
@@ -207,9 +204,8 @@ __global__ __launch_bounds__(64 * NG) void fwd_wave_kernel(KP p) {
     pf[0] = pack8(&pr[0]);
     pf[1] = pack8(&pr[8]);
   };
-  // O^T += V^T P^T
-  auto stage_pv = [&](int buf, const bf16x8 (&pf)[2]) {
-    const uint16_t* sV = slot + buf * BUF + SUB * LDK;
+  // O^T += V^T P^T with the sub-tile in the V buffer
+  auto stage_pv = [&](const bf16x8 (&pf)[2]) {
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
       bf16x8 vf[DB];
@@ -222,32 +218,37 @@ __global__ __launch_bounds__(64 * NG) void fwd_wave_kernel(KP p) {
 
   if (n > 0) {
     f32x16 sc, sn;
-    lstore(0);
+    // K(j0) -> LDS -> scores; then K(j0+NG) -> LDS with K(j0+2NG) in flight, V(j0) -> LDS with V(j0+NG) in flight
+    sub_store<D, LDK>(sK, pk, lane);
+    sub_load<D>(pk, rsK, p.ss, jc(j0 + NG) * SUB, loff);
+    stage_s(sc);
+    sub_store<D, LDK>(sK, pk, lane);
+    sub_load<D>(pk, rsK, p.ss, jc(j0 + 2 * NG) * SUB, loff);
+    sub_store<D, LDV>(sV, pv, lane);
+    sub_load<D>(pv, rsV, p.ss, jc(j0 + NG) * SUB, loff);
     if (BIAS) {
 #pragma unroll
       for (int g = 0; g < 4; ++g) bzc[g] = bzn[g];
     }
-    gload(min(j0 + NG, jlast));
-    stage_s(0, sc);
-    // one step: sub-tile j sits in LDS buffer `buf` with its scores in sc; the registers hold sub-tile
-    // j+NG (clamped to the wavefront's last one), which moves to the other buffer and has its scores
-    // computed into sn while the vector ALUs work on sc
+    // step i: scores of sub-tile j are in sc, V(j) and K(j+NG) are in LDS, K(j+2NG) and V(j+NG) in registers
     for (int i = 0; i < n; ++i) {
-      const int j = j0 + i * NG, buf = i & 1;
-      uint2 bz[4];
-      if (BIAS) {
-#pragma unroll
-        for (int g = 0; g < 4; ++g) { bz[g] = bzc[g]; bzc[g] = bzn[g]; }
-      }
-      softmax_max(j * SUB, sc, bz, (j * SUB + SUB > p.S) || (CAUSAL && j * SUB + SUB - 1 > q0));
+      const int j = j0 + i * NG;
+      softmax_max(j * SUB, sc, bzc, (j * SUB + SUB > p.S) || (CAUSAL && j * SUB + SUB - 1 > q0));
       // from here on the step is one straight-line block: the next scores run on the matrix cores
       // under the exponentials of the current ones
-      lstore(buf ^ 1);
-      gload(min(j + 2 * NG, jlast));
-      stage_s(buf ^ 1, sn);
+      if (BIAS) bload(jc(j + NG));
+      stage_s(sn);
+      sub_store<D, LDK>(sK, pk, lane);
+      sub_load<D>(pk, rsK, p.ss, jc(j + 3 * NG) * SUB, loff);
       bf16x8 pf[2];
       softmax_exp(sc, pf);
-      stage_pv(buf, pf);
+      stage_pv(pf);
+      sub_store<D, LDV>(sV, pv, lane);
+      sub_load<D>(pv, rsV, p.ss, jc(j + 2 * NG) * SUB, loff);
+      if (BIAS) {
+#pragma unroll
+        for (int g = 0; g < 4; ++g) bzc[g] = bzn[g];
+      }
       sc = sn;
     }
   }

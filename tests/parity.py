@@ -64,8 +64,8 @@ def run_case(cfg, lo=None, hi=None, k=1, flags=0, use_lse=False, inputs=None, sc
     return dc, inp
 
 
-def check_against_oracle(cfg, lo=None, hi=None, k=1, flags=0, use_lse=False, scale=None, tol=None):
-    dc, inp = run_case(cfg, lo, hi, k, flags, use_lse, scale=scale)
+def check_against_oracle(cfg, lo=None, hi=None, k=1, flags=0, use_lse=False, scale=None, tol=None, inputs=None):
+    dc, inp = run_case(cfg, lo, hi, k, flags, use_lse, inputs=inputs, scale=scale)
     ext = dc.H if cfg["axis"] == "head" else dc.B
     lo = 0 if lo is None else lo
     hi = ext if hi is None else hi

@@ -90,6 +90,24 @@ def test_results_identical_across_k(name):
                 assert np.array_equal(outs[n], ref[n], equal_nan=True), (name, k, n)
 
 
+@pytest.mark.parametrize("name", ["gpt_like", "long_seq_few_heads", "bias_causal_d64", "long_seq_bias_d64",
+                                  "long_seq_bias_causal_d32", "long_seq_mid_share", "tri_like"])
+def test_rising_scores_raise_the_running_maximum(name):
+    """Keys grow by powers of two along the sequence, so the row maximum jumps by far more than the
+    lazy-rescale threshold several times per row: the accumulated output has to be rescaled while
+    it is non-zero, on every kernel variant that keeps a running maximum."""
+    from paper_2301_08984_amd.workloads import make_inputs
+    cfg = SMALL[name]
+    inp = make_inputs(**cfg)
+    S = cfg["S"]
+    grow = (2.0 ** (np.arange(S) * 4 // S)).astype(inp["K"].dtype)  # x1, x2, x4, x8 by quarters: exact in bf16
+    inp["K"] = inp["K"] * grow[None, :, None, None]
+    n = cfg["H"] if cfg["axis"] == "head" else cfg["B"]
+    for k in (1, min(n, 2)):
+        print(f"case {name} rising scores k={k}", flush=True)
+        check_against_oracle(cfg, k=k, inputs=inp)
+
+
 def test_other_scale_and_strided_layout():
     """scale is an argument; activations may sit in a wider buffer (stride_h > D)."""
     import torch
