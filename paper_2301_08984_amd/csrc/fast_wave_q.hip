@@ -85,7 +85,7 @@ __device__ inline void sub_store(uint16_t* t, const u32x4 (&src)[D / 16], int la
 // fixed binary tree, so the result does not depend on timing.
 // ---------------------------------------------------------------------------
 template <int D, bool BIAS, bool CAUSAL, bool RECOMP, int NG>
-__global__ __launch_bounds__(64 * NG) void fwd_wave_kernel(KP p) {
+__global__ __launch_bounds__(64 * NG) __attribute__((amdgpu_waves_per_eu(2, 2))) void fwd_wave_kernel(KP p) {
   constexpr int KS = D / 16, DB = D / 32, SUB = 32, CPT = D / 16;
   constexpr int LDK = D + 8, LDV = D + 16;  // row pads chosen for conflict-free b128 / transpose reads
   constexpr int SLOT = SUB * LDK + SUB * LDV;
