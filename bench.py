@@ -26,7 +26,7 @@ PEAK_HBM = 8.0e12        # B/s
 BOUND = {"gpt3_shard": "mfma", "swin_window": "hbm", "af2_msa_row": "hbm", "af2_triangle": "hbm",
          "tiny_mha": "hbm"}
 # contractions (each 2*D flop per visible score element) a kernel performs
-CONTRACTIONS = {"fwd": 2, "recompute": 2, "dq": 3, "dkdv": 4, "dbias": 2, "table_reduce": 0}
+CONTRACTIONS = {"fwd": 2, "recompute": 2, "dq": 3, "dkdv": 4, "dbias": 2, "table_reduce": 0, "dq_dkdv": 7}
 
 
 def visible_fraction(w):
@@ -60,6 +60,7 @@ def kernel_bytes(w, name, units, axis_extent):
         "recompute": (4 + g) * T + 2 * g * T + nb + 2 * stat,
         "dq": 5 * T + nb + 2 * stat,
         "dkdv": 6 * T + nb + 2 * stat,
+        "dq_dkdv": 7 * T + nb + 2 * stat,
         "dbias": 4 * T + nb + 2 * stat + (w["H"] * w["S"] ** 2 * 4 if w["bias"] else 0),
         "table_reduce": w["H"] * w["S"] ** 2 * 4,
     }

@@ -331,8 +331,12 @@ int ss_attn_bwd(const ss_attn_desc* d, const void* Q, const void* K, const void*
     }
     if (mfma) {
       SS_LAUNCH(SS_K_RECOMPUTE, ssa::launch_mfma_fwd(p, true, st), "recompute");
-      SS_LAUNCH(SS_K_DQ, ssa::launch_mfma_dq(p, st), "dQ");
-      SS_LAUNCH(SS_K_DKDV, ssa::launch_mfma_dkdv(p, st), "dK/dV");
+      if (ssa::mfma_fuses_dq_dkdv(p)) {
+        SS_LAUNCH(SS_K_DQ_DKDV, ssa::launch_mfma_dq_dkdv(p, st), "dQ + dK/dV");
+      } else {
+        SS_LAUNCH(SS_K_DQ, ssa::launch_mfma_dq(p, st), "dQ");
+        SS_LAUNCH(SS_K_DKDV, ssa::launch_mfma_dkdv(p, st), "dK/dV");
+      }
       if (want_dbias) {
         if (w.gw > 0) {  // grouped sum: partials in the workspace, reduced after the last chunk that adds to them
           p.sm_partial = (float*)(ws + w.partial);

@@ -490,11 +490,7 @@ hipError_t dbias_d(const KP& p, hipStream_t st) {
     case 128: return fn<128>(__VA_ARGS__);        \
     default: return hipErrorInvalidValue;         \
   }
-hipError_t launch_fast_dkdv(const KP& p, hipStream_t st) {
-  // small shares: 32-key work-groups whose wavefronts split the queries
-  if (wg_shape(p) == WG_2x4) return launch_fast_dkdv_wave(p, st);
-  SS_FAST_DISPATCH_D(dkdv_d, p, st)
-}
+hipError_t launch_fast_dkdv(const KP& p, hipStream_t st) { SS_FAST_DISPATCH_D(dkdv_d, p, st) }
 hipError_t launch_fast_dbias(const KP& p, hipStream_t st) { SS_FAST_DISPATCH_D(dbias_d, p, st) }
 
 hipError_t launch_bias_transpose(const void* bias, void* biasT, int S, int h0, int h1, hipStream_t st) {

@@ -221,9 +221,6 @@ hipError_t dq_d(const KP& p, hipStream_t st) {
     case 128: return fn<128>(__VA_ARGS__);        \
     default: return hipErrorInvalidValue;         \
   }
-hipError_t launch_fast_dq(const KP& p, hipStream_t st) {
-  if (wg_shape(p) == WG_2x4) return launch_fast_dq_wave(p, st);
-  SS_FAST_DISPATCH_D(dq_d, p, st)
-}
+hipError_t launch_fast_dq(const KP& p, hipStream_t st) { SS_FAST_DISPATCH_D(dq_d, p, st) }
 
 }  // namespace ssa

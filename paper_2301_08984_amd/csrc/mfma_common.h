@@ -216,9 +216,8 @@ inline WgShape wg_shape(const KP& p) {
 hipError_t launch_fast_fwd(const KP& p, bool recompute, hipStream_t st);
 hipError_t launch_fast_dq(const KP& p, hipStream_t st);
 hipError_t launch_fast_dkdv(const KP& p, hipStream_t st);
-hipError_t launch_fast_dkdv_wave(const KP& p, hipStream_t st);
 hipError_t launch_fast_fwd_wave(const KP& p, bool recompute, hipStream_t st);
-hipError_t launch_fast_dq_wave(const KP& p, hipStream_t st);
+hipError_t launch_fast_bwd_wave(const KP& p, hipStream_t st);
 hipError_t launch_fast_dbias(const KP& p, hipStream_t st);
 
 }  // namespace ssa
