@@ -13,7 +13,7 @@ namespace {
 // ---------------------------------------------------------------------------
 template <int D, int NG>
 constexpr int dq_wave_lds_elems() {
-  constexpr int SLOT = 2 * (32 * (D + 16) + 32 * (D + 8)), MERGE = (NG / 2) * 64 * 4 * (D / 32) * 8;
+  constexpr int SLOT = 2 * (32 * (D + 16) + 32 * (D + 8)), MERGE = NG * 64 * 4 * (D / 32) * 8;
   return NG * SLOT > MERGE ? NG * SLOT : MERGE;
 }
 template <int D, bool BIAS, bool CAUSAL, int NG>
@@ -23,7 +23,7 @@ __device__ __forceinline__ void dq_wave_block(const KP& p, uint16_t* smem, int r
   constexpr int BUF = SUB * LDK + SUB * LDV;
   constexpr int SLOT = 2 * BUF;
   constexpr int MSLOT = 64 * 4 * DB;
-  static_assert(NG * SLOT <= dq_wave_lds_elems<D, NG>() && (NG / 2) * MSLOT * 8 <= dq_wave_lds_elems<D, NG>(), "LDS size");
+  static_assert(NG * SLOT <= dq_wave_lds_elems<D, NG>() && NG * 64 * 4 * DB * 8 <= dq_wave_lds_elems<D, NG>(), "LDS size");
   const int lane = threadIdx.x & 63, r = lane & 31, hl = lane >> 5;
   const int grp = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // uniform: scalar registers
   uint16_t* slot = smem + grp * SLOT;
@@ -175,46 +175,47 @@ __device__ __forceinline__ void dq_wave_block(const KP& p, uint16_t* smem, int r
     }
   }
 
+  auto store_q = [&](int db, int g, const f32x4& x) {
+    const int d0 = 32 * db + 8 * g + 4 * hl;
+    uint2 o;
+    o.x = (uint32_t)f2bf(x[0] * p.scale) | ((uint32_t)f2bf(x[1] * p.scale) << 16);
+    o.y = (uint32_t)f2bf(x[2] * p.scale) | ((uint32_t)f2bf(x[3] * p.scale) << 16);
+    *(uint2*)((uint16_t*)p.dQ + base + (int64_t)q * p.ss + d0) = o;
+  };
   if (NG > 1) {
+    // every wavefront hands over its partial sums through LDS; wavefront w then folds and stores
+    // the 32-column output blocks w, w+NG, ...: a fixed binary tree over the wavefronts
+    constexpr int WSLOT = 64 * 4 * DB;  // f32x4 units per wavefront
     f32x4* mb = (f32x4*)smem;
+    __syncthreads();
+    f32x4* my = mb + (size_t)grp * WSLOT + lane;
 #pragma unroll
-    for (int s = NG / 2; s >= 1; s >>= 1) {
-      __syncthreads();
-      if (grp >= s && grp < 2 * s) {
-        f32x4* my = mb + (size_t)(grp - s) * MSLOT + lane;
+    for (int db = 0; db < DB; ++db)
 #pragma unroll
-        for (int db = 0; db < DB; ++db)
+      for (int g = 0; g < 4; ++g)
+        my[(4 * db + g) * 64] = f32x4{acc[db][4 * g], acc[db][4 * g + 1], acc[db][4 * g + 2], acc[db][4 * g + 3]};
+    __syncthreads();
+    if (q >= p.S) return;
+    for (int db = grp; db < DB; db += NG)
 #pragma unroll
-          for (int g = 0; g < 4; ++g)
-            my[(4 * db + g) * 64] = f32x4{acc[db][4 * g], acc[db][4 * g + 1], acc[db][4 * g + 2], acc[db][4 * g + 3]};
+      for (int g = 0; g < 4; ++g) {
+        f32x4 x[NG];
+#pragma unroll
+        for (int w = 0; w < NG; ++w) x[w] = mb[(size_t)w * WSLOT + (4 * db + g) * 64 + lane];
+#pragma unroll
+        for (int st = NG / 2; st >= 1; st >>= 1)
+#pragma unroll
+          for (int w = 0; w < st; ++w) x[w] += x[w + st];
+        store_q(db, g, x[0]);
       }
-      __syncthreads();
-      if (grp < s) {
-        const f32x4* o = mb + (size_t)grp * MSLOT + lane;
-#pragma unroll
-        for (int db = 0; db < DB; ++db)
-#pragma unroll
-          for (int g = 0; g < 4; ++g) {
-            const f32x4 x = o[(4 * db + g) * 64];
-#pragma unroll
-            for (int e = 0; e < 4; ++e) acc[db][4 * g + e] += x[e];
-          }
-      }
-    }
-    if (grp > 0) return;
+    return;
   }
   if (q >= p.S) return;
-  uint16_t* out = (uint16_t*)p.dQ + base + (int64_t)q * p.ss;
 #pragma unroll
   for (int db = 0; db < DB; ++db)
 #pragma unroll
-    for (int g = 0; g < 4; ++g) {
-      const int d0 = 32 * db + 8 * g + 4 * hl;
-      uint2 o;
-      o.x = (uint32_t)f2bf(acc[db][4 * g] * p.scale) | ((uint32_t)f2bf(acc[db][4 * g + 1] * p.scale) << 16);
-      o.y = (uint32_t)f2bf(acc[db][4 * g + 2] * p.scale) | ((uint32_t)f2bf(acc[db][4 * g + 3] * p.scale) << 16);
-      *(uint2*)(out + d0) = o;
-    }
+    for (int g = 0; g < 4; ++g)
+      store_q(db, g, f32x4{acc[db][4 * g], acc[db][4 * g + 1], acc[db][4 * g + 2], acc[db][4 * g + 3]});
 }
 
 // ---------------------------------------------------------------------------
@@ -232,7 +233,7 @@ __device__ __forceinline__ void dq_wave_block(const KP& p, uint16_t* smem, int r
 // ---------------------------------------------------------------------------
 template <int D, int QG>
 constexpr int dkdv_wave_lds_elems() {
-  constexpr int SLOT = 4 * 32 * (D + 16) + 2 * 2 * 2 * 32, MERGE = (QG / 2) * 64 * 32 * (D / 32) * 2;
+  constexpr int SLOT = 4 * 32 * (D + 16) + 2 * 2 * 2 * 32, MERGE = QG * 64 * 8 * (D / 32) * 8;
   return QG * SLOT > MERGE ? QG * SLOT : MERGE;
 }
 template <int D, bool BIAS, bool CAUSAL, int QG>
@@ -241,7 +242,7 @@ __device__ __forceinline__ void dkdv_wave_block(const KP& p, uint16_t* smem, int
   constexpr int CPR = D / 8, CPT = SUB * CPR / 64;
   constexpr int MAT = SUB * LD;                  // uint16 elements of one staged matrix
   constexpr int SLOT = 4 * MAT + 2 * 2 * 2 * SUB;  // two buffers of (Q, dO) + two of (lse, delta) as floats
-  constexpr int MERGE = (QG / 2) * 64 * 32 * DB * 2;
+  constexpr int MERGE = QG * 64 * 8 * DB * 8;  // uint16 units of the hand-over area
   static_assert(QG * SLOT <= dkdv_wave_lds_elems<D, QG>() && MERGE <= dkdv_wave_lds_elems<D, QG>(), "LDS size");
   const int lane = threadIdx.x & 63, r = lane & 31, hl = lane >> 5;
   const int grp = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // uniform: scalar registers
@@ -421,53 +422,57 @@ __device__ __forceinline__ void dkdv_wave_block(const KP& p, uint16_t* smem, int
     }
   }
 
-  // fold the wavefronts' partial sums: binary tree over groups, fixed shape
+  auto store_kv = [&](int db, int g, const f32x4& k4, const f32x4& v4) {
+    const int d0 = 32 * db + 8 * g + 4 * hl;
+    uint2 a, c;
+    a.x = (uint32_t)f2bf(k4[0] * p.scale) | ((uint32_t)f2bf(k4[1] * p.scale) << 16);
+    a.y = (uint32_t)f2bf(k4[2] * p.scale) | ((uint32_t)f2bf(k4[3] * p.scale) << 16);
+    c.x = (uint32_t)f2bf(v4[0]) | ((uint32_t)f2bf(v4[1]) << 16);
+    c.y = (uint32_t)f2bf(v4[2]) | ((uint32_t)f2bf(v4[3]) << 16);
+    *(uint2*)((uint16_t*)p.dK + base + (int64_t)key * p.ss + d0) = a;
+    *(uint2*)((uint16_t*)p.dV + base + (int64_t)key * p.ss + d0) = c;
+  };
   if (QG > 1) {
+    // every wavefront hands over its partial sums through LDS; wavefront w then folds and stores
+    // the 32-column output blocks w, w+QG, ...  The fold is a fixed binary tree over the
+    // wavefronts ((g0+g2)+(g1+g3) for QG = 4), so the result does not depend on timing.
+    constexpr int WSLOT = 64 * 8 * DB;  // f32x4 units per wavefront
     f32x4* mb = (f32x4*)smem;
+    __syncthreads();
+    f32x4* my = mb + (size_t)grp * WSLOT + lane;
 #pragma unroll
-    for (int s = QG / 2; s >= 1; s >>= 1) {
-      __syncthreads();
-      if (grp >= s && grp < 2 * s) {
-        f32x4* my = mb + (size_t)(grp - s) * (64 * 8 * DB) + lane;
+    for (int db = 0; db < DB; ++db)
 #pragma unroll
-        for (int db = 0; db < DB; ++db)
-#pragma unroll
-          for (int g = 0; g < 4; ++g) {
-            my[(4 * db + g) * 64] = f32x4{dk[db][4 * g], dk[db][4 * g + 1], dk[db][4 * g + 2], dk[db][4 * g + 3]};
-            my[(4 * DB + 4 * db + g) * 64] = f32x4{dv[db][4 * g], dv[db][4 * g + 1], dv[db][4 * g + 2], dv[db][4 * g + 3]};
-          }
+      for (int g = 0; g < 4; ++g) {
+        my[(8 * db + g) * 64] = f32x4{dk[db][4 * g], dk[db][4 * g + 1], dk[db][4 * g + 2], dk[db][4 * g + 3]};
+        my[(8 * db + 4 + g) * 64] = f32x4{dv[db][4 * g], dv[db][4 * g + 1], dv[db][4 * g + 2], dv[db][4 * g + 3]};
       }
-      __syncthreads();
-      if (grp < s) {
-        const f32x4* o = mb + (size_t)grp * (64 * 8 * DB) + lane;
+    __syncthreads();
+    if (key >= p.S) return;
+    for (int db = grp; db < DB; db += QG)
 #pragma unroll
-        for (int db = 0; db < DB; ++db)
+      for (int g = 0; g < 4; ++g) {
+        f32x4 xk[QG], xv[QG];
 #pragma unroll
-          for (int g = 0; g < 4; ++g) {
-            const f32x4 a = o[(4 * db + g) * 64], c = o[(4 * DB + 4 * db + g) * 64];
+        for (int w = 0; w < QG; ++w) {
+          xk[w] = mb[(size_t)w * WSLOT + (8 * db + g) * 64 + lane];
+          xv[w] = mb[(size_t)w * WSLOT + (8 * db + 4 + g) * 64 + lane];
+        }
 #pragma unroll
-            for (int e = 0; e < 4; ++e) { dk[db][4 * g + e] += a[e]; dv[db][4 * g + e] += c[e]; }
-          }
+        for (int st = QG / 2; st >= 1; st >>= 1)
+#pragma unroll
+          for (int w = 0; w < st; ++w) { xk[w] += xk[w + st]; xv[w] += xv[w + st]; }
+        store_kv(db, g, xk[0], xv[0]);
       }
-    }
-    if (grp > 0) return;
+    return;
   }
   if (key >= p.S) return;
-  uint16_t* oK = (uint16_t*)p.dK + base + (int64_t)key * p.ss;
-  uint16_t* oV = (uint16_t*)p.dV + base + (int64_t)key * p.ss;
 #pragma unroll
   for (int db = 0; db < DB; ++db)
 #pragma unroll
-    for (int g = 0; g < 4; ++g) {
-      const int d0 = 32 * db + 8 * g + 4 * hl;
-      uint2 a, c;
-      a.x = (uint32_t)f2bf(dk[db][4 * g] * p.scale) | ((uint32_t)f2bf(dk[db][4 * g + 1] * p.scale) << 16);
-      a.y = (uint32_t)f2bf(dk[db][4 * g + 2] * p.scale) | ((uint32_t)f2bf(dk[db][4 * g + 3] * p.scale) << 16);
-      c.x = (uint32_t)f2bf(dv[db][4 * g]) | ((uint32_t)f2bf(dv[db][4 * g + 1]) << 16);
-      c.y = (uint32_t)f2bf(dv[db][4 * g + 2]) | ((uint32_t)f2bf(dv[db][4 * g + 3]) << 16);
-      *(uint2*)(oK + d0) = a;
-      *(uint2*)(oV + d0) = c;
-    }
+    for (int g = 0; g < 4; ++g)
+      store_kv(db, g, f32x4{dk[db][4 * g], dk[db][4 * g + 1], dk[db][4 * g + 2], dk[db][4 * g + 3]},
+               f32x4{dv[db][4 * g], dv[db][4 * g + 1], dv[db][4 * g + 2], dv[db][4 * g + 3]});
 }
 
 // ---------------------------------------------------------------------------
