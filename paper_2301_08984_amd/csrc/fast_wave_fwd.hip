@@ -24,7 +24,7 @@ __global__ __launch_bounds__(64 * NG) __attribute__((amdgpu_waves_per_eu(2, 2)))
   constexpr int LDK = D + 8, LDV = D + 16;  // row pads chosen for conflict-free b128 / transpose reads
   constexpr int SLOT = SUB * LDK + SUB * LDV;
   constexpr int MSLOT = 64 * (4 * DB + 1);  // f32x4 units one wavefront hands over in the merge
-  constexpr int MERGE = (NG / 2) * MSLOT * 8;
+  constexpr int MERGE = NG * MSLOT * 8 + 2 * 32 * (DB < NG ? DB : NG);  // hand-over area + partial Delta, uint16 units
   constexpr int LDS_ELEMS = NG * SLOT > MERGE ? NG * SLOT : MERGE;
   __shared__ __attribute__((aligned(16))) uint16_t smem[LDS_ELEMS];
   const int lane = threadIdx.x & 63, r = lane & 31, hl = lane >> 5;
@@ -187,40 +187,82 @@ __global__ __launch_bounds__(64 * NG) __attribute__((amdgpu_waves_per_eu(2, 2)))
     }
   }
 
-  // fold the wavefronts' partial softmax results: binary tree over groups, fixed shape
   if (NG > 1) {
+    // every wavefront hands over its partial (O, m, l) through LDS; each then folds the statistics
+    // with the same fixed binary tree ((g0+g2)+(g1+g3) for NG = 4), which also yields the weights
+    // of every tree node, and wavefront w folds, normalises and stores the 32-column output blocks
+    // w, w+NG, ...
     f32x4* mb = (f32x4*)smem;
+    float* dpart = (float*)(mb + NG * MSLOT);  // [DB][32] partial Delta per output block (recompute)
+    __syncthreads();
+    f32x4* my = mb + (size_t)grp * MSLOT + lane;
 #pragma unroll
-    for (int s = NG / 2; s >= 1; s >>= 1) {
-      __syncthreads();
-      if (grp >= s && grp < 2 * s) {
-        f32x4* my = mb + (size_t)(grp - s) * MSLOT + lane;
+    for (int db = 0; db < DB; ++db)
 #pragma unroll
-        for (int db = 0; db < DB; ++db)
+      for (int g = 0; g < 4; ++g)
+        my[(4 * db + g) * 64] = f32x4{oacc[db][4 * g], oacc[db][4 * g + 1], oacc[db][4 * g + 2], oacc[db][4 * g + 3]};
+    my[4 * DB * 64] = f32x4{m, l, 0.f, 0.f};
+    __syncthreads();
+    float mm[NG], ll[NG];
 #pragma unroll
-          for (int g = 0; g < 4; ++g)
-            my[(4 * db + g) * 64] = f32x4{oacc[db][4 * g], oacc[db][4 * g + 1], oacc[db][4 * g + 2], oacc[db][4 * g + 3]};
-        my[4 * DB * 64] = f32x4{m, l, 0.f, 0.f};
-      }
-      __syncthreads();
-      if (grp < s) {
-        const f32x4* o = mb + (size_t)grp * MSLOT + lane;
-        const f32x4 ml = o[4 * DB * 64];
-        const float mn = fmaxf(m, ml[0]);
-        const float a0 = fast_exp2(m - mn), a1 = fast_exp2(ml[0] - mn);
-#pragma unroll
-        for (int db = 0; db < DB; ++db)
-#pragma unroll
-          for (int g = 0; g < 4; ++g) {
-            const f32x4 x = o[(4 * db + g) * 64];
-#pragma unroll
-            for (int e = 0; e < 4; ++e) oacc[db][4 * g + e] = oacc[db][4 * g + e] * a0 + x[e] * a1;
-          }
-        l = l * a0 + ml[1] * a1;
-        m = mn;
-      }
+    for (int w = 0; w < NG; ++w) {
+      const f32x4 ml = mb[(size_t)w * MSLOT + 4 * DB * 64 + lane];
+      mm[w] = ml[0];
+      ll[w] = ml[1];
     }
-    if (grp > 0) return;
+    float a0s[NG], a1s[NG];  // tree weights, entry st + w: node w and its partner w + st at level st
+#pragma unroll
+    for (int st = NG / 2; st >= 1; st >>= 1)
+#pragma unroll
+      for (int w = 0; w < st; ++w) {
+        const float mn = fmaxf(mm[w], mm[w + st]);
+        const float a0 = fast_exp2(mm[w] - mn), a1 = fast_exp2(mm[w + st] - mn);
+        a0s[st + w] = a0;
+        a1s[st + w] = a1;
+        ll[w] = ll[w] * a0 + ll[w + st] * a1;
+        mm[w] = mn;
+      }
+    m = mm[0];
+    l = half_sum(ll[0]);
+    const float inv = 1.f / l;
+    float part = 0.f;
+    bool mine = false;
+    for (int db = grp; db < DB; db += NG) {
+      mine = true;
+      f32x16 o;
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        f32x4 x[NG];
+#pragma unroll
+        for (int w = 0; w < NG; ++w) x[w] = mb[(size_t)w * MSLOT + (4 * db + g) * 64 + lane];
+#pragma unroll
+        for (int st = NG / 2; st >= 1; st >>= 1)
+#pragma unroll
+          for (int w = 0; w < st; ++w)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) x[w][e] = x[w][e] * a0s[st + w] + x[w + st][e] * a1s[st + w];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o[4 * g + e] = x[0][e];
+      }
+      if (q < p.S) part += fwd_epilogue_block<RECOMP>(p, o, db, inv, b, h, q, hl, base);
+    }
+    const float lse = (m + log2f(l)) * LN2;
+    if (!RECOMP) {
+      if (grp == 0 && hl == 0 && q < p.S && p.lse_out) p.lse_out[(int64_t)b * p.lse_sb + (int64_t)h * p.lse_sh + q] = lse;
+      return;
+    }
+    // recompute: Delta = sum over the output blocks of the partial row sums, in block order
+    part = half_sum(part);
+    if (mine && hl == 0) dpart[grp * 32 + r] = part;  // DB <= NG: wavefront w owns block w
+    __syncthreads();
+    if (grp == 0 && hl == 0 && q < p.S) {
+      float dl = 0.f;
+#pragma unroll
+      for (int db = 0; db < (DB < NG ? DB : NG); ++db) dl += dpart[db * 32 + r];
+      p.delta[(int64_t)b * p.dl_sb + (int64_t)h * p.dl_sh + q] = dl;
+      if (p.lse_out) p.lse_out[(int64_t)b * p.lse_sb + (int64_t)h * p.lse_sh + q] = lse;
+    }
+    return;
   }
   if (q >= p.S) return;
   fwd_epilogue<DB, RECOMP>(p, oacc, m, l, b, h, q, hl, base);
