@@ -23,7 +23,7 @@ sys.path.insert(0, ROOT)
 PEAK_MFMA_BF16 = 2.5e15  # dense bf16 FLOP/s, MI355X
 PEAK_HBM = 8.0e12        # B/s
 # which published roofline bounds the dominant kernel of each workload
-BOUND = {"gpt3_shard": "mfma", "swin_window": "hbm", "af2_msa_row": "hbm", "af2_triangle": "hbm",
+BOUND = {"gpt3_shard": "mfma", "gpt3_long": "mfma", "swin_window": "hbm", "af2_msa_row": "hbm", "af2_triangle": "hbm",
          "tiny_mha": "hbm"}
 # contractions (each 2*D flop per visible score element) a kernel performs
 CONTRACTIONS = {"fwd": 2, "recompute": 2, "dq": 3, "dkdv": 4, "dbias": 2, "table_reduce": 0, "dq_dkdv": 7}

@@ -66,6 +66,10 @@ WORKLOADS = {
                         gated=True, axis="row", k=(1, 4, 16)),
     "af2_triangle": dict(seed=5005, B=1024, H=4, S=1024, D=32, dtype="bf16", bias="dense", mask=None,
                          gated=True, axis="row", k=(4, 16, 64)),
+    # beyond the five headline configurations: the long-document setting of Section 6.3 (sequence
+    # lengths of 10k-16k tokens, where co-shard's memory argument is made) on the same GPT share
+    "gpt3_long": dict(seed=6006, B=1, H=12, S=12288, D=128, dtype="bf16", bias=None, mask="causal",
+                      gated=False, axis="head", k=(1, 2, 4)),
 }
 
 

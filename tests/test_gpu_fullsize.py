@@ -45,6 +45,28 @@ def test_full_workload_every_output(name, k):
         assert np.isfinite(e) and e <= (tol if n != "lse" else 1e-3), (n, e)
 
 
+def test_long_sequence_one_head_against_oracle():
+    """S = 12288 (the long-document setting): the kernels chosen for a chip-filling share.  The oracle
+    computes one whole head (heads are independent), the one after the chunk boundary of k = 2."""
+    name, k, h = "gpt3_long", 2, 6
+    print(f"full-size {name} k={k}, head {h} against the oracle", flush=True)
+    w, inp, dc = _run(name, k)
+    one = {n: np.ascontiguousarray(inp[n][:, :, h:h + 1]) for n in ("Q", "K", "V", "dY")}
+    p = oracle_problem(one, w)
+    Y, LSE = orc.attn_forward(p, orc.AXIS_HEAD)
+    g = orc.attn_backward(p, one["dY"].astype(np.float64), orc.AXIS_HEAD)
+    tol = TOL["bf16"]
+    errs = {"Y": rel_err(dc.host("Y")[:, :, h:h + 1], Y),
+            "lse": float(np.max(np.abs(dc.host("lse")[:, h:h + 1] - LSE)))}
+    for n in ("dQ", "dK", "dV"):
+        errs[n] = rel_err(dc.host(n)[:, :, h:h + 1], g[n])
+    print(name, {n: f"{e:.2e}" for n, e in errs.items()}, flush=True)
+    for n, e in errs.items():
+        assert np.isfinite(e) and e <= (tol if n != "lse" else 1e-3), (n, e)
+    for n in ("Y", "dQ", "dK", "dV"):
+        assert bool(getattr(dc, n).isfinite().all()), n
+
+
 def test_triangle_full_size_sampled():
     name, k = "af2_triangle", 16
     print(f"full-size {name} k={k} (sampled rows)", flush=True)

@@ -45,6 +45,9 @@ SMALL = {
     "long_seq_bias_causal_d32": dict(seed=50, B=1, H=3, S=520, D=32, dtype="bf16", bias="dense", mask="causal",
                                      axis="head"),
     "long_seq_mid_share": dict(seed=51, B=16, H=4, S=512, D=32, dtype="bf16", mask="causal", axis="row"),
+    # the paper's own split axis for window attention: heads (Section 2)
+    "swin_head_axis": dict(seed=52, B=20, H=4, S=49, D=32, dtype="bf16", bias="relpos", win=(7, 7),
+                           mask="region", axis="head"),
 }
 
 
@@ -74,7 +77,7 @@ def test_sub_range_and_saved_lse(name):
 
 @pytest.mark.parametrize("name", ["gpt_like", "swin_like", "msa_like", "tiny_mha", "bias_causal_d64",
                                   "short_dense_causal", "long_rows_many_groups", "long_seq_few_heads",
-                                  "long_seq_bias_d64"])
+                                  "long_seq_bias_d64", "swin_head_axis"])
 def test_results_identical_across_k(name):
     cfg = SMALL[name]
     ref = None
