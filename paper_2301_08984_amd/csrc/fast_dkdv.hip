@@ -75,7 +75,7 @@ __global__ __launch_bounds__(64 * NW) void dkdv_fast_kernel(KP p) {
       *(u32x4*)(&sQ[buf][row * LD + col]) = pq[c];
       *(u32x4*)(&sG[buf][row * LD + col]) = pg[c];
     }
-    if (tid < BN) sL[buf][tid] = pstat * LOG2E;
+    if (tid < BN) sL[buf][tid] = -pstat * LOG2E;  // stored negated: one fused multiply-add per score
     else if (tid < 2 * BN) sD[buf][tid - BN] = pstat;
   };
   // scores and dP of one 32-query sub-block
@@ -111,7 +111,7 @@ __global__ __launch_bounds__(64 * NW) void dkdv_fast_kernel(KP p) {
       }
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
-        float pe = fast_exp2(fmaf(sa[4 * g + e], c1, bl[e] - l4[e]));
+        float pe = fast_exp2(fmaf(sa[4 * g + e], c1, BIAS ? bl[e] + l4[e] : l4[e]));
         if (edge) {
           const int i = i0 + 32 * sub + 8 * g + 4 * hl + e;
           const bool dead = i >= p.S || key >= p.S || (CAUSAL && key > i);
@@ -166,6 +166,11 @@ __global__ __launch_bounds__(64 * NW) void dkdv_fast_kernel(KP p) {
       for (int j = 0; j < 8; ++j) bz[j] = *(const uint2*)(biasT_row + min(i0 + 8 * j + 4 * hl, p.S - 4));
     }
     auto tile = [&](auto edge_tag) {
+      // D = 128: keeps the 32 operand reads inside this block; they are common to both variants of
+      // the tile and would otherwise all be hoisted above the branch, out of reach of the schedule
+      // below, where their 128 registers push the transposed operands into the accumulation file
+      // (measured: 929 -> 785 us on the long-sequence GPT share; smaller D is faster without)
+      if (D >= 128) asm volatile("" ::: "memory");
       f32x16 sa0, pa0, sa1, pa1;
       bf16x8 pf0[2], df0[2], pf1[2], df1[2];
       stage_a(tq, tg, 0, sa0, pa0);
