@@ -24,7 +24,7 @@ PEAK_MFMA_BF16 = 2.5e15  # dense bf16 FLOP/s, MI355X
 PEAK_HBM = 8.0e12        # B/s
 # which published roofline bounds the dominant kernel of each workload
 BOUND = {"gpt3_shard": "mfma", "gpt3_long": "mfma", "swin_window": "hbm", "af2_msa_row": "hbm", "af2_triangle": "hbm",
-         "tiny_mha": "hbm"}
+         "af2_msa_col": "hbm", "af2_triangle_end": "hbm", "tiny_mha": "hbm"}
 # contractions (each 2*D flop per visible score element) a kernel performs
 CONTRACTIONS = {"fwd": 2, "recompute": 2, "dq": 3, "dkdv": 4, "dbias": 2, "table_reduce": 0, "dq_dkdv": 7}
 
@@ -135,7 +135,7 @@ def main():
     k_main = a.k if a.k is not None else (ks[1] if len(ks) > 1 else ks[0])
     ss.lib()  # fail loudly if the HIP library is missing
     dc = DeviceCase(make_inputs(**w), dtype=w["dtype"], bias=w["bias"], mask=w["mask"], gated=w["gated"],
-                    win=w.get("win"), fill=0.0)
+                    win=w.get("win"), fill=0.0, layout=w.get("layout", "bshd"))
     desc = dc.desc(w["axis"], 0, ext, k_main)
     family = ss.ss_attn_kernel_family(desc)
     dc.workspace(desc)
@@ -169,6 +169,7 @@ def main():
         "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": w["dtype"], "data": "synthetic",
         "config": {"workload": a.workload, "B": w["B"], "H": w["H"], "S": w["S"], "D": w["D"],
+                   "layout": w.get("layout", "bshd"),
                    "bias": w["bias"], "mask": w["mask"], "gated": w["gated"], "shard_axis": w["axis"],
                    "k": k_main, "kernels": family},
         "pct_mfma_peak": 100.0 * value * 1e12 / PEAK_MFMA_BF16,

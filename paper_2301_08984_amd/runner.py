@@ -19,25 +19,37 @@ class DeviceCase:
     """One attention operator resident on the GPU plus its output buffers."""
 
     def __init__(self, inputs: dict, *, dtype: str, bias=None, mask=None, gated=False, win=None,
-                 scale=None, device="cuda:0", fill=float("nan")):
+                 scale=None, device="cuda:0", fill=float("nan"), layout="bshd"):
+        """`layout`: how the [B,S,H,D] activations sit in memory.  "bshd": packed as indexed.  "sbhd":
+        the two leading axes swapped in storage (the operator walks the *second* storage axis as its
+        sequence): the transposed variants of a row-wise operator, e.g. attention along MSA columns,
+        reached through stride_b / stride_s alone."""
         if not torch.cuda.is_available():
             raise RuntimeError("no GPU: the HIP path has no CPU fallback")
         self.dev = torch.device(device)
         self.tdtype = torch.bfloat16 if dtype == "bf16" else torch.float32
         self.dtype = ss.SS_BF16 if dtype == "bf16" else ss.SS_F32
         up = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(self.dev).to(self.tdtype).contiguous()
-        self.Q, self.K, self.V, self.dY = (up(inputs[n]) for n in ("Q", "K", "V", "dY"))
+        self.layout = layout
+        if layout == "sbhd":
+            # stored [S,B,H,D]; every activation is kept as its logical [B,S,H,D] view of that storage
+            act = lambda a: up(a).permute(1, 0, 2, 3).contiguous().permute(1, 0, 2, 3)
+        elif layout == "bshd":
+            act = up
+        else:
+            raise ValueError(layout)
+        self.Q, self.K, self.V, self.dY = (act(inputs[n]) for n in ("Q", "K", "V", "dY"))
         self.B, self.S, self.H, self.D = self.Q.shape
         self.scale = (1.0 / math.sqrt(self.D)) if scale is None else scale
         self.bias_kind, self.mask_kind, self.gated, self.win = _BIAS[bias], _MASK[mask], gated, win or (0, 0)
         self.bias = up(inputs["bias"]) if bias else None
-        self.G = up(inputs["G"]) if gated else None
+        self.G = act(inputs["G"]) if gated else None
         self.region = None
         self.mask_period = 0
         if mask == "region":
             self.region = torch.from_numpy(np.ascontiguousarray(inputs["region_ids"], dtype=np.int32)).to(self.dev)
             self.mask_period = self.region.shape[0]
-        mk = lambda: torch.full_like(self.Q, fill)
+        mk = lambda: torch.full_like(self.Q, fill, memory_format=torch.preserve_format)
         self.Y, self.dQ, self.dK, self.dV = mk(), mk(), mk(), mk()
         self.dG = mk() if gated else None
         self.lse = torch.full((self.B, self.H, self.S), fill, dtype=torch.float32, device=self.dev)
@@ -46,8 +58,10 @@ class DeviceCase:
         self.ws = None
 
     def desc(self, axis, lo, hi, k, flags=0):
+        sb, ss_, sh, sd = self.Q.stride()
+        assert sd == 1
         return ss.make_desc(self.B, self.H, self.S, self.D, self.dtype, self.scale, _AXIS[axis], lo, hi, k,
-                            bias_kind=self.bias_kind, win=self.win, mask_kind=self.mask_kind,
+                            stride_b=sb, stride_s=ss_, stride_h=sh, bias_kind=self.bias_kind, win=self.win, mask_kind=self.mask_kind,
                             mask_period=self.mask_period, gated=self.gated, flags=flags)
 
     def workspace(self, desc):

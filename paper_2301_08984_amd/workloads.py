@@ -68,6 +68,14 @@ WORKLOADS = {
                          gated=True, axis="row", k=(4, 16, 64)),
     # beyond the five headline configurations: the long-document setting of Section 6.3 (sequence
     # lengths of 10k-16k tokens, where co-shard's memory argument is made) on the same GPT share
+    # the transposed AlphaFold2 operators: same kernels, the two leading axes swapped in storage
+    # (`layout="sbhd"`: stride_b < stride_s, every row of a tile a separate 64-byte segment):
+    # MSA column attention (per residue column, across the 512 sequences; gated, no pair bias) and
+    # triangle attention around the ending node
+    "af2_msa_col": dict(seed=7007, B=384, H=8, S=512, D=32, dtype="bf16", bias=None, mask=None,
+                        gated=True, axis="row", k=(1, 4, 16), layout="sbhd"),
+    "af2_triangle_end": dict(seed=8008, B=1024, H=4, S=1024, D=32, dtype="bf16", bias="dense", mask=None,
+                             gated=True, axis="row", k=(4, 16, 64), layout="sbhd"),
     "gpt3_long": dict(seed=6006, B=1, H=12, S=12288, D=128, dtype="bf16", bias=None, mask="causal",
                       gated=False, axis="head", k=(1, 2, 4)),
 }

@@ -52,7 +52,8 @@ def run_case(cfg, lo=None, hi=None, k=1, flags=0, use_lse=False, inputs=None, sc
     """Returns (DeviceCase after fwd+bwd, inputs)."""
     inp = make_inputs(**cfg) if inputs is None else inputs
     dc = DeviceCase(inp, dtype=cfg["dtype"], bias=cfg.get("bias"), mask=cfg.get("mask"),
-                    gated=cfg.get("gated", False), win=cfg.get("win"), scale=scale)
+                    gated=cfg.get("gated", False), win=cfg.get("win"), scale=scale,
+                    layout=cfg.get("layout", "bshd"))
     ext = dc.H if cfg["axis"] == "head" else dc.B
     lo = 0 if lo is None else lo
     hi = ext if hi is None else hi

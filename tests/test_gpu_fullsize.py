@@ -19,7 +19,8 @@ def _run(name, k):
     import torch
     w = dict(WORKLOADS[name])
     inp = make_inputs(**w)
-    dc = DeviceCase(inp, dtype=w["dtype"], bias=w["bias"], mask=w["mask"], gated=w["gated"], win=w.get("win"))
+    dc = DeviceCase(inp, dtype=w["dtype"], bias=w["bias"], mask=w["mask"], gated=w["gated"], win=w.get("win"),
+                    layout=w.get("layout", "bshd"))
     ext = w["H"] if w["axis"] == "head" else w["B"]
     d = dc.desc(w["axis"], 0, ext, k)
     assert ss.ss_attn_kernel_family(d) != "plain_fp32"
@@ -29,7 +30,7 @@ def _run(name, k):
     return w, inp, dc
 
 
-@pytest.mark.parametrize("name,k", [("gpt3_shard", 2), ("af2_msa_row", 4), ("swin_window", 4)])
+@pytest.mark.parametrize("name,k", [("gpt3_shard", 2), ("af2_msa_row", 4), ("swin_window", 4), ("af2_msa_col", 4)])
 def test_full_workload_every_output(name, k):
     print(f"full-size {name} k={k}", flush=True)
     w, inp, dc = _run(name, k)
@@ -67,8 +68,9 @@ def test_long_sequence_one_head_against_oracle():
         assert bool(getattr(dc, n).isfinite().all()), n
 
 
-def test_triangle_full_size_sampled():
-    name, k = "af2_triangle", 16
+@pytest.mark.parametrize("name", ["af2_triangle", "af2_triangle_end"])
+def test_triangle_full_size_sampled(name):
+    k = 16
     print(f"full-size {name} k={k} (sampled rows)", flush=True)
     w, inp, dc = _run(name, k)
     p = oracle_problem(inp, w)

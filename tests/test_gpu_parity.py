@@ -45,6 +45,14 @@ SMALL = {
     "long_seq_bias_causal_d32": dict(seed=50, B=1, H=3, S=520, D=32, dtype="bf16", bias="dense", mask="causal",
                                      axis="head"),
     "long_seq_mid_share": dict(seed=51, B=16, H=4, S=512, D=32, dtype="bf16", mask="causal", axis="row"),
+    # transposed storage (attention along the first storage axis): strides alone select the variant
+    "msa_col_like": dict(seed=53, B=7, H=2, S=150, D=32, dtype="bf16", gated=True, axis="row", layout="sbhd"),
+    "tri_end_like": dict(seed=54, B=5, H=2, S=200, D=32, dtype="bf16", bias="dense", gated=True, axis="row",
+                         layout="sbhd"),
+    "gpt_like_transposed": dict(seed=55, B=2, H=2, S=600, D=128, dtype="bf16", mask="causal", axis="head",
+                                layout="sbhd"),
+    "swin_like_transposed": dict(seed=56, B=20, H=4, S=49, D=32, dtype="bf16", bias="relpos", win=(7, 7),
+                                 mask="region", axis="row", layout="sbhd"),
     # the paper's own split axis for window attention: heads (Section 2)
     "swin_head_axis": dict(seed=52, B=20, H=4, S=49, D=32, dtype="bf16", bias="relpos", win=(7, 7),
                            mask="region", axis="head"),
@@ -77,7 +85,7 @@ def test_sub_range_and_saved_lse(name):
 
 @pytest.mark.parametrize("name", ["gpt_like", "swin_like", "msa_like", "tiny_mha", "bias_causal_d64",
                                   "short_dense_causal", "long_rows_many_groups", "long_seq_few_heads",
-                                  "long_seq_bias_d64", "swin_head_axis"])
+                                  "long_seq_bias_d64", "swin_head_axis", "tri_end_like"])
 def test_results_identical_across_k(name):
     cfg = SMALL[name]
     ref = None
