@@ -1,0 +1,90 @@
+/* ss_ffn.h -- C ABI of the co-sharded feed-forward operator for MI355X (gfx950).
+ *
+ * The other half of the co-shard plan (Section 6.1, "parallelization plans": attention heads and
+ * feed-forward hidden dimensions are partitioned; Section 6.3: co-shard is applied to the
+ * attention and feed-forward operators, with recompute).  One call runs one GPU's share of the
+ * position-wise feed-forward operator the paper cites,
+ *
+ *     Z = X W1 + b1 ;  H = act(Z) ;  Y = H W2 (+ b2)        X [T,dm], W1 [dm,dh], W2 [dh,dm]
+ *
+ * as k sub-operators executed one after another on one HIP stream (op-trans along the hidden
+ * dimension, Section 3.1; op-assign to one device and op-order, Section 3.2).  The share is the
+ * hidden range [lo,hi).  Unlike the head split of attention every sub-operator contributes to the
+ * whole output: Y and dX are value-split partial sums (Section 4; Section 5 for the gradient of
+ * the shared input) which the library accumulates in fp32 in the workspace, in an order that does
+ * not depend on k; dW1, db1 and dW2 are disjoint slices.  Only one chunk's hidden activations
+ * [T, (hi-lo)/k] are alive at a time, and the backward recomputes them (Sections 2 and 6.3).
+ *
+ * All pointers are DEVICE pointers unless said otherwise; the descriptor and size outputs are HOST
+ * memory.  The library allocates no device memory and never synchronises; everything is enqueued
+ * on the caller's stream.  Error codes are those of ss_attn.h.
+ */
+#ifndef SS_FFN_H
+#define SS_FFN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#include "ss_attn.h"
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { SS_ACT_RELU = 0, SS_ACT_GELU_TANH = 1 } ss_act;
+
+/* Describes the operator and this GPU's share.  All matrices are row-major bf16 (dtype must be
+ * SS_BF16), leading dimensions in elements and multiples of 8, base pointers 16-byte aligned:
+ *   X, Y, dY, dX : [T, dm], row stride ld_x
+ *   W1, dW1      : [dm, dh], row stride ld_w1        b1, db1 : [dh]
+ *   W2, dW2      : [dh, dm], row stride ld_w2        b2, db2 : [dm]
+ * dm and dh multiples of 8.  lo and hi-lo need no alignment, but chunk boundaries fall on
+ * multiples of 16 hidden columns counted from lo (ss_ffn_chunk_range). */
+typedef struct {
+  int32_t T, dm, dh;
+  int32_t dtype; /* SS_BF16 */
+  int32_t act;   /* ss_act */
+  int64_t ld_x, ld_w1, ld_w2;
+  int32_t lo, hi; /* this GPU's hidden range */
+  int32_t k;      /* co-shard factor, 1 <= k <= ceil((hi-lo)/16) */
+  int32_t flags;  /* 0 */
+} ss_ffn_desc;
+
+/* Workspace bytes ss_ffn_fwd / ss_ffn_bwd need (host outputs).  Forward: one chunk's H plus, for
+ * k > 1, the fp32 accumulator of Y.  Backward: one chunk's H and act'(Z) (overwritten by dZ) plus,
+ * for k > 1, the fp32 accumulator of dX.  The hidden-activation part shrinks with k. */
+int ss_ffn_workspace_bytes(const ss_ffn_desc* desc, size_t* fwd_bytes, size_t* bwd_bytes);
+
+/* Hidden range of chunk c (0 <= c < k): balanced in units of 16 columns counted from lo. */
+int ss_ffn_chunk_range(const ss_ffn_desc* desc, int32_t c, int32_t* lo, int32_t* hi);
+
+/* Y = sum over the share's chunks of act(X W1[:,c] + b1[c]) W2[c,:], plus b2 if b2 != NULL.
+ * Y is written once, by the last chunk.  workspace: 256-byte aligned, >= fwd_bytes. */
+int ss_ffn_fwd(const ss_ffn_desc* desc, const void* X, const void* W1, const void* b1, const void* W2, const void* b2,
+               void* Y, void* workspace, size_t workspace_bytes, void* stream);
+
+/* Gradients for dY.  dX [T,dm]: partial sum over the share.  dW1 / db1 / dW2: only columns / entries
+ * / rows [lo,hi) are written (the rest of these full-size tensors is left untouched).  db2 [dm] may
+ * be NULL (skipped); it is the full gradient of b2, independent of the share. */
+int ss_ffn_bwd(const ss_ffn_desc* desc, const void* X, const void* W1, const void* b1, const void* W2, const void* dY,
+               void* dX, void* dW1, void* db1, void* dW2, void* db2, void* workspace, size_t workspace_bytes,
+               void* stream);
+
+/* Benchmark instrumentation as in ss_attn.h: kernels of the feed-forward path. */
+typedef enum {
+  SS_FK_UP = 0,      /* H = act(X W1 + b1) (forward and recompute)   */
+  SS_FK_DOWN = 1,    /* Y += H W2                                    */
+  SS_FK_DH = 2,      /* dZ = (dY W2^T) * act'(Z)                     */
+  SS_FK_DW2 = 3,     /* dW2 = H^T dY                                 */
+  SS_FK_DW1 = 4,     /* dW1 = X^T dZ                                 */
+  SS_FK_DX = 5,      /* dX += dZ W1^T                                */
+  SS_FK_COLSUM = 6,  /* db1, db2                                     */
+  SS_FK_COUNT = 7
+} ss_ffn_kernel_id;
+int ss_ffn_profile_enable(int on);
+int ss_ffn_profile_read(int kernel, double* total_ms, int64_t* launches);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SS_FFN_H */

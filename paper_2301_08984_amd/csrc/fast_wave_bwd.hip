@@ -47,12 +47,11 @@ __device__ __forceinline__ void dq_wave_block(const KP& p, uint16_t* smem, int r
   const int n = j0 < nj ? (nj - 1 - j0) / NG + 1 : 0;
   const int jlast = j0 + (n - 1) * NG;
 
-  const __amdgpu_buffer_rsrc_t rsK = slice_rsrc(Kb, p.ss, p.S, D), rsV = slice_rsrc(Vb, p.ss, p.S, D);
   u32x4 pk[CPT], pv[CPT];
   uint2 bzn[4], bzc[4];
   auto gload = [&](int j) {
-    sub_load<D>(pk, rsK, p.ss, j * SUB, loff);
-    sub_load<D>(pv, rsV, p.ss, j * SUB, loff);
+    sub_load<D>(pk, Kb, p.ss, p.S, j * SUB, loff);
+    sub_load<D>(pv, Vb, p.ss, p.S, j * SUB, loff);
     if (BIAS) {
 #pragma unroll
       for (int g = 0; g < 4; ++g) bzn[g] = *(const uint2*)(bias_row + min(j * SUB + 8 * g + 4 * hl, p.S - 4));
@@ -67,8 +66,8 @@ __device__ __forceinline__ void dq_wave_block(const KP& p, uint16_t* smem, int r
   bf16x8 qf[KS], gf[KS];
   {
     u32x4 pq[CPT], pg[CPT];
-    sub_load<D>(pq, slice_rsrc(Qb, p.ss, p.S, D), p.ss, q0, loff);
-    sub_load<D>(pg, slice_rsrc(dOb, p.do_ss, p.S, D), p.do_ss, q0, loff_g);
+    sub_load<D>(pq, Qb, p.ss, p.S, q0, loff);
+    sub_load<D>(pg, dOb, p.do_ss, p.S, q0, loff_g);
     if (n > 0) gload(j0);
     sub_store<D, LDK>(slot + BUF, pq, lane);
     sub_store<D, LDV>(slot + BUF + SUB * LDK, pg, lane);
@@ -278,25 +277,14 @@ __device__ __forceinline__ void dkdv_wave_block(const KP& p, uint16_t* smem, int
   const int n = j0 < nsub ? (nsub - 1 - j0) / QG + 1 : 0;
   const int jlast = j0 + (n - 1) * QG;
 
-  // bounds-checked staging loads: a scalar offset per chunk plus the lane's constant byte offset, zeros
-  // past the last row (the slices span less than 2 GiB: checked on the host)
-  const __amdgpu_buffer_rsrc_t rsQ = __builtin_amdgcn_make_buffer_rsrc(
-      (void*)Qb, 0, (int)(((int64_t)(p.S - 1) * p.ss + D) * 2), 0x00020000);
-  const __amdgpu_buffer_rsrc_t rsG = __builtin_amdgcn_make_buffer_rsrc(
-      (void*)dOb, 0, (int)(((int64_t)(p.S - 1) * p.do_ss + D) * 2), 0x00020000);
   const uint32_t loff_q = ((uint32_t)(lane / CPR) * (uint32_t)p.ss + 8u * (lane % CPR)) * 2u;
   const uint32_t loff_g = ((uint32_t)(lane / CPR) * (uint32_t)p.do_ss + 8u * (lane % CPR)) * 2u;
   u32x4 pq[CPT], pg[CPT];
   float pstat = 0.f;
   uint2 bzn[4], bzc[4];  // bias slices of the sub-tile in the registers / of the one about to be used
   auto gload = [&](int j) {
-    const uint32_t so_q = (uint32_t)(j * SUB) * (uint32_t)p.ss * 2u, st_q = (uint32_t)(64 / CPR) * (uint32_t)p.ss * 2u;
-    const uint32_t so_g = (uint32_t)(j * SUB) * (uint32_t)p.do_ss * 2u, st_g = (uint32_t)(64 / CPR) * (uint32_t)p.do_ss * 2u;
-#pragma unroll
-    for (int c = 0; c < CPT; ++c) {
-      pq[c] = __builtin_amdgcn_raw_buffer_load_b128(rsQ, loff_q, so_q + c * st_q, 0);
-      pg[c] = __builtin_amdgcn_raw_buffer_load_b128(rsG, loff_g, so_g + c * st_g, 0);
-    }
+    sub_load<D>(pq, Qb, p.ss, p.S, j * SUB, loff_q);
+    sub_load<D>(pg, dOb, p.do_ss, p.S, j * SUB, loff_g);
     const int i = min(j * SUB + r, p.S - 1);
     pstat = hl == 0 ? lse_b[i] : dl_b[i];
     if (BIAS) {

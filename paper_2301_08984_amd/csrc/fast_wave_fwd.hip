@@ -51,7 +51,6 @@ __global__ __launch_bounds__(64 * NG) __attribute__((amdgpu_waves_per_eu(2, 2)))
   const int jlast = j0 + (n - 1) * NG;
   auto jc = [&](int j) { return min(j, jlast); };  // past the wavefront's last sub-tile: fetch it again
 
-  const __amdgpu_buffer_rsrc_t rsK = slice_rsrc(Kb, p.ss, p.S, D), rsV = slice_rsrc(Vb, p.ss, p.S, D);
   u32x4 pk[CPT], pv[CPT];
   uint2 bzn[4], bzc[4];  // bias slices of the next sub-tile / of the one about to be used
   auto bload = [&](int j) {
@@ -63,10 +62,10 @@ __global__ __launch_bounds__(64 * NG) __attribute__((amdgpu_waves_per_eu(2, 2)))
   bf16x8 qf[KS];
   {
     u32x4 pq[CPT];
-    sub_load<D>(pq, slice_rsrc(Qb, p.ss, p.S, D), p.ss, q0, loff);
+    sub_load<D>(pq, Qb, p.ss, p.S, q0, loff);
     if (n > 0) {
-      sub_load<D>(pk, rsK, p.ss, j0 * SUB, loff);
-      sub_load<D>(pv, rsV, p.ss, j0 * SUB, loff);
+      sub_load<D>(pk, Kb, p.ss, p.S, j0 * SUB, loff);
+      sub_load<D>(pv, Vb, p.ss, p.S, j0 * SUB, loff);
       if (BIAS) bload(j0);
     }
     sub_store<D, LDK>(sK, pq, lane);
@@ -154,12 +153,12 @@ __global__ __launch_bounds__(64 * NG) __attribute__((amdgpu_waves_per_eu(2, 2)))
     f32x16 sc, sn;
     // K(j0) -> LDS -> scores; then K(j0+NG) -> LDS with K(j0+2NG) in flight, V(j0) -> LDS with V(j0+NG) in flight
     sub_store<D, LDK>(sK, pk, lane);
-    sub_load<D>(pk, rsK, p.ss, jc(j0 + NG) * SUB, loff);
+    sub_load<D>(pk, Kb, p.ss, p.S, jc(j0 + NG) * SUB, loff);
     stage_s(sc);
     sub_store<D, LDK>(sK, pk, lane);
-    sub_load<D>(pk, rsK, p.ss, jc(j0 + 2 * NG) * SUB, loff);
+    sub_load<D>(pk, Kb, p.ss, p.S, jc(j0 + 2 * NG) * SUB, loff);
     sub_store<D, LDV>(sV, pv, lane);
-    sub_load<D>(pv, rsV, p.ss, jc(j0 + NG) * SUB, loff);
+    sub_load<D>(pv, Vb, p.ss, p.S, jc(j0 + NG) * SUB, loff);
     if (BIAS) {
 #pragma unroll
       for (int g = 0; g < 4; ++g) bzc[g] = bzn[g];
@@ -173,12 +172,12 @@ __global__ __launch_bounds__(64 * NG) __attribute__((amdgpu_waves_per_eu(2, 2)))
       if (BIAS) bload(jc(j + NG));
       stage_s(sn);
       sub_store<D, LDK>(sK, pk, lane);
-      sub_load<D>(pk, rsK, p.ss, jc(j + 3 * NG) * SUB, loff);
+      sub_load<D>(pk, Kb, p.ss, p.S, jc(j + 3 * NG) * SUB, loff);
       bf16x8 pf[2];
       softmax_exp(sc, pf);
       stage_pv(pf);
       sub_store<D, LDV>(sV, pv, lane);
-      sub_load<D>(pv, rsV, p.ss, jc(j + 2 * NG) * SUB, loff);
+      sub_load<D>(pv, Vb, p.ss, p.S, jc(j + 2 * NG) * SUB, loff);
       if (BIAS) {
 #pragma unroll
         for (int g = 0; g < 4; ++g) bzc[g] = bzn[g];

@@ -21,22 +21,23 @@ __device__ inline BlockId heavy_first_block_id() {
   return b;
 }
 
-// Buffer descriptor over one (row, head) slice of a [.., S, .., D] bf16 tensor whose rows are
-// `ss` elements apart: loads past the last valid row return zeros, so the staging loads need
-// neither clamps nor branches.  The slice must span less than 2 GiB (checked on the host).
-__device__ inline __amdgpu_buffer_rsrc_t slice_rsrc(const uint16_t* base, int64_t ss, int S, int D) {
-  return __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, (int)(((int64_t)(S - 1) * ss + D) * 2), 0x00020000);
-}
-// coalesced fetch of a 32-row sub-tile: lane l takes the 16-byte chunks l, l+64, ... (chunk i =
-// row i / (D/8), columns 8 * (i % (D/8)) ..).  `row0` is uniform over the wavefront, so every
-// chunk is addressed by a scalar offset plus the lane's constant byte offset
-// `loff` = ((l / (D/8)) * ss + 8 * (l % (D/8))) * 2: no vector arithmetic per load.
+// coalesced fetch of the 32-row sub-tile starting at row `row0` (uniform over the wavefront) of one
+// (row, head) slice of a [.., S, .., D] bf16 tensor whose rows are `ss` elements apart: lane l takes
+// the 16-byte chunks l, l+64, ... (chunk i = row i / (D/8), columns 8 * (i % (D/8)) ..).  Buffer
+// loads with a descriptor over the slice: rows past S-1 return zeros, so the staging needs neither
+// clamps nor branches.  The hardware bounds-checks the lane offset only (not the scalar offset), so
+// the whole offset is the lane offset: `loff` = ((l / (D/8)) * ss + 8 * (l % (D/8))) * 2 bytes plus
+// the chunk's and the sub-tile's row offsets.  The slice spans less than 2 GiB (checked on the host).
 template <int D>
-__device__ inline void sub_load(u32x4 (&dst)[D / 16], __amdgpu_buffer_rsrc_t rs, int64_t ss, int row0, uint32_t loff) {
+__device__ inline void sub_load(u32x4 (&dst)[D / 16], const uint16_t* base, int64_t ss, int S, int row0,
+                                uint32_t loff) {
   constexpr int RSTEP = 64 / (D / 8);
-  const uint32_t so = (uint32_t)row0 * (uint32_t)ss * 2u, step = (uint32_t)RSTEP * (uint32_t)ss * 2u;
+  const __amdgpu_buffer_rsrc_t rs =
+      __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, (int)(((int64_t)(S - 1) * ss + D) * 2), 0x00020000);
+  const uint32_t step = (uint32_t)RSTEP * (uint32_t)ss * 2u;
+  const uint32_t off = loff + (uint32_t)row0 * (uint32_t)ss * 2u;
 #pragma unroll
-  for (int c = 0; c < D / 16; ++c) dst[c] = __builtin_amdgcn_raw_buffer_load_b128(rs, loff, so + c * step, 0);
+  for (int c = 0; c < D / 16; ++c) dst[c] = __builtin_amdgcn_raw_buffer_load_b128(rs, off + c * step, 0, 0);
 }
 // O accumulators *= alpha, for the rare step on which the running maximum is raised.  Written so that
 // the accumulators stay in the accumulation registers on the common path: as ordinary C++ the

@@ -119,6 +119,39 @@ def test_rising_scores_raise_the_running_maximum(name):
         check_against_oracle(cfg, k=k, inputs=inp)
 
 
+@pytest.mark.parametrize("name", ["long_seq_few_heads", "long_seq_bias_d64", "gpt_like", "tri_like", "swin_like"])
+def test_rows_past_the_sequence_end_are_never_used(name):
+    """Ragged S: the staged tiles extend past row S-1.  Every activation is followed in memory by a
+    NaN-filled batch, so anything read past the end of the last batch and used would poison the result."""
+    import torch
+    from paper_2301_08984_amd.runner import DeviceCase
+    from paper_2301_08984_amd.workloads import make_inputs
+    cfg = SMALL[name]
+    inp = make_inputs(**cfg)
+    dc = DeviceCase(inp, dtype=cfg["dtype"], bias=cfg.get("bias"), mask=cfg.get("mask"), gated=cfg.get("gated", False),
+                    win=cfg.get("win"))
+    ref = DeviceCase(inp, dtype=cfg["dtype"], bias=cfg.get("bias"), mask=cfg.get("mask"), gated=cfg.get("gated", False),
+                     win=cfg.get("win"))
+    for n in ("Q", "K", "V", "dY", "G", "Y", "dQ", "dK", "dV", "dG"):
+        t = getattr(dc, n)
+        if t is None:
+            continue
+        big = torch.full((dc.B + 1,) + tuple(t.shape[1:]), float("nan"), dtype=t.dtype, device=t.device)
+        big[: dc.B] = t
+        setattr(dc, n, big[: dc.B])
+    ext = dc.H if cfg["axis"] == "head" else dc.B
+    for case in (dc, ref):
+        d = case.desc(cfg["axis"], 0, ext, 2)
+        case.fwd(d)
+        case.bwd(d)
+    torch.cuda.synchronize()
+    for n in ("Y", "dQ", "dK", "dV", "dG", "dBias", "lse"):
+        a, b = getattr(dc, n), getattr(ref, n)
+        if a is not None:
+            assert torch.equal(a, b), n   # bit-identical to the run without the poisoned neighbour, and finite
+            assert bool(a.isfinite().all()), n
+
+
 def test_other_scale_and_strided_layout():
     """scale is an argument; activations may sit in a wider buffer (stride_h > D)."""
     import torch
