@@ -1,0 +1,36 @@
+// Launchers of the feed-forward kernels (bf16 MFMA GEMM with fused epilogues, column sums).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace ssa {
+
+enum { EPI_ACT = 0, EPI_MUL = 1, EPI_ACC = 2, EPI_STORE = 3 };
+
+// C[M,N] = A B (see gemm_kernel for the operand layouts); what happens to C:
+//   EPI_ACT   out = act(C + bias[n]) (bf16); out2, if given, = act'(C + bias[n])
+//   EPI_MUL   out = C * mul[m][n] (bf16; out may be mul)
+//   EPI_ACC   the accumulator starts from acc32 if `accumulate`; then `last` ? out = C + bias[n] (bf16,
+//             bias may be NULL) : acc32 = C (fp32)
+//   EPI_STORE out = C (bf16)
+struct GemmArgs {
+  const uint16_t* A;
+  const uint16_t* B;
+  int64_t lda, ldb;
+  int M, N, K;
+  const uint16_t* bias;
+  uint16_t* out;
+  int64_t ldo;
+  uint16_t* out2;
+  const uint16_t* mul;
+  int64_t ldm;
+  float* acc32;
+  int64_t ld32;
+  int accumulate, last, act;
+};
+
+hipError_t launch_gemm(const GemmArgs& g, bool a_transposed, bool b_transposed, int epilogue, hipStream_t st);
+// out[n] (bf16) = sum over m of A[m][n] (bf16 in, fp32 sum, fixed order)
+hipError_t launch_colsum(const void* A, int64_t lda, int M, int N, void* out, hipStream_t st);
+
+}  // namespace ssa

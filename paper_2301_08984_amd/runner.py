@@ -92,3 +92,55 @@ class DeviceCase:
     def host(self, name):
         t = getattr(self, name)
         return None if t is None else t.detach().float().cpu().numpy().astype(np.float64)
+
+
+class FfnCase:
+    """One feed-forward operator resident on the GPU plus its output buffers (bf16)."""
+
+    def __init__(self, inputs: dict, *, act="gelu", device="cuda:0", fill=float("nan")):
+        from . import ffn_binding as fb
+        if not torch.cuda.is_available():
+            raise RuntimeError("no GPU: the HIP path has no CPU fallback")
+        self.fb = fb
+        self.dev = torch.device(device)
+        up = lambda a: None if a is None else torch.from_numpy(np.ascontiguousarray(a)).to(self.dev).to(
+            torch.bfloat16).contiguous()
+        self.X, self.W1, self.b1, self.W2, self.b2, self.dY = (up(inputs.get(n)) for n in
+                                                              ("X", "W1", "b1", "W2", "b2", "dY"))
+        self.T, self.dm = self.X.shape
+        self.dh = self.W1.shape[1]
+        self.act = fb.SS_ACT_GELU_TANH if act == "gelu" else fb.SS_ACT_RELU
+        mk = lambda t: torch.full_like(t, fill)
+        self.Y, self.dX, self.dW1, self.db1, self.dW2, self.db2 = (mk(self.X), mk(self.X), mk(self.W1), mk(self.b1),
+                                                                  mk(self.W2), mk(self.X[0]))
+        self.ws = None
+
+    def desc(self, lo, hi, k):
+        return self.fb.make_desc(self.T, self.dm, self.dh, lo, hi, k, act=self.act)
+
+    def workspace(self, desc):
+        f, b = self.fb.ss_ffn_workspace_bytes(desc)
+        need = max(f, b, 256)
+        if self.ws is None or self.ws.numel() < need:
+            self.ws = torch.empty(need, dtype=torch.uint8, device=self.dev)
+        return f, b
+
+    def fwd(self, desc):
+        self.workspace(desc)
+        st = torch.cuda.current_stream(self.dev).cuda_stream
+        self.fb.ss_ffn_fwd(desc, self.X, self.W1, self.b1, self.W2, self.b2, self.Y, self.ws, self.ws.numel(), st)
+
+    def bwd(self, desc):
+        self.workspace(desc)
+        st = torch.cuda.current_stream(self.dev).cuda_stream
+        self.fb.ss_ffn_bwd(desc, self.X, self.W1, self.b1, self.W2, self.dY, self.dX, self.dW1, self.db1, self.dW2,
+                           self.db2, self.ws, self.ws.numel(), st)
+
+    def caller_bytes(self):
+        ts = [self.X, self.W1, self.b1, self.W2, self.b2, self.dY, self.Y, self.dX, self.dW1, self.db1, self.dW2,
+              self.db2]
+        return sum(t.numel() * t.element_size() for t in ts if t is not None)
+
+    def host(self, name):
+        t = getattr(self, name)
+        return None if t is None else t.detach().float().cpu().numpy().astype(np.float64)

@@ -127,3 +127,28 @@ def make_inputs(B, H, S, D, dtype="bf16", bias=None, mask=None, gated=False, see
         # 16 windows per side, cyclic shift of half a window (7 -> 112x112 map, shift 3)
         out["region_ids"] = shifted_window_region_ids(16 * w, w, w // 2)
     return out
+
+
+# ---------------------------------------------------------------------------
+# Feed-forward operator (the other operator the co-shard plan is applied to, Sections 6.1 and 6.3)
+# ---------------------------------------------------------------------------
+FFN_WORKLOADS = {
+    "tiny_ffn": dict(seed=9001, T=100, dm=64, dh=256, lo=0, hi=256, act="gelu", k=(1, 2, 4)),
+    # one GPU's tensor-parallel share of a GPT-3 175B feed-forward block: d_model 12288, hidden 49152
+    # split 8 ways, 2048 tokens (the sequence of the attention share)
+    "gpt3_ffn": dict(seed=9002, T=2048, dm=12288, dh=6144, lo=0, hi=6144, act="gelu", k=(1, 2, 4)),
+}
+
+
+def make_ffn_inputs(T, dm, dh, seed=0, **_unused):
+    """Seeded float32 arrays already rounded to bf16: X, dY ~ N(0,1); W1 ~ N(0, 1/dm), W2 ~ N(0, 1/dh) (so
+    that pre-activations and outputs are O(1)); biases ~ N(0, 0.02^2)."""
+    g = np.random.Generator(np.random.PCG64(seed))
+    rnd = round_to_bf16
+    out = {"X": rnd(g.standard_normal((T, dm), dtype=np.float32)),
+           "dY": rnd(g.standard_normal((T, dm), dtype=np.float32)),
+           "W1": rnd(g.standard_normal((dm, dh), dtype=np.float32) * np.float32(dm ** -0.5)),
+           "W2": rnd(g.standard_normal((dh, dm), dtype=np.float32) * np.float32(dh ** -0.5)),
+           "b1": rnd(g.standard_normal(dh, dtype=np.float32) * np.float32(0.02)),
+           "b2": rnd(g.standard_normal(dm, dtype=np.float32) * np.float32(0.02))}
+    return out

@@ -1,0 +1,82 @@
+"""GPU parity of the co-sharded feed-forward operator: the HIP path through the C ABI against the
+fp64 oracle on the same seeded inputs, for every k; and the co-shard invariant bit for bit across k
+(the partial sums are continued in fp32 in the same order whatever the number of chunks)."""
+import numpy as np
+import pytest
+
+from oracle import ffn as orc
+from paper_2301_08984_amd.workloads import FFN_WORKLOADS, make_ffn_inputs
+
+from parity import rel_err
+
+pytestmark = pytest.mark.gpu
+
+TOL = 2e-2  # bf16 operands, fp32 accumulation: max|x - ref| / max|ref| per tensor
+
+SMALL = {
+    "tiny_ffn": FFN_WORKLOADS["tiny_ffn"],
+    "ragged": dict(seed=61, T=333, dm=200, dh=424, lo=0, hi=424, act="gelu"),
+    "sub_range_relu": dict(seed=62, T=130, dm=136, dh=512, lo=48, hi=400, act="relu"),
+    "several_tiles": dict(seed=63, T=600, dm=320, dh=704, lo=0, hi=704, act="gelu"),
+    "one_token": dict(seed=64, T=1, dm=64, dh=128, lo=0, hi=128, act="gelu"),
+}
+
+
+def _run(cfg, k):
+    import torch
+    from paper_2301_08984_amd.runner import FfnCase
+    inp = make_ffn_inputs(**cfg)
+    fc = FfnCase(inp, act=cfg["act"])
+    d = fc.desc(cfg["lo"], cfg["hi"], k)
+    fc.fwd(d)
+    fc.bwd(d)
+    torch.cuda.synchronize()
+    return fc, inp
+
+
+def _oracle(cfg, inp):
+    kind = orc.ACT_GELU_TANH if cfg["act"] == "gelu" else orc.ACT_RELU
+    p = orc.FfnProblem(inp["X"], inp["W1"], inp["b1"], inp["W2"], inp["b2"], kind)
+    return orc.ffn_forward(p, cfg["lo"], cfg["hi"]), orc.ffn_backward(p, inp["dY"].astype(np.float64), cfg["lo"], cfg["hi"])
+
+
+def _ks(cfg):
+    units = -(-(cfg["hi"] - cfg["lo"]) // 16)
+    return sorted({1, 2, 3, min(units, 7)})
+
+
+@pytest.mark.parametrize("name", list(SMALL))
+def test_matches_oracle_for_every_k(name):
+    cfg = SMALL[name]
+    lo, hi = cfg["lo"], cfg["hi"]
+    for k in _ks(cfg):
+        print(f"ffn case {name} k={k}", flush=True)
+        fc, inp = _run(cfg, k)
+        Y, g = _oracle(cfg, inp)
+        errs = {"Y": rel_err(fc.host("Y"), Y), "dX": rel_err(fc.host("dX"), g["dX"]),
+                "dW1": rel_err(fc.host("dW1")[:, lo:hi], g["dW1"][:, lo:hi]),
+                "db1": rel_err(fc.host("db1")[lo:hi], g["db1"][lo:hi]),
+                "dW2": rel_err(fc.host("dW2")[lo:hi], g["dW2"][lo:hi]), "db2": rel_err(fc.host("db2"), g["db2"])}
+        print(name, k, {n: f"{e:.2e}" for n, e in errs.items()}, flush=True)
+        for n, e in errs.items():
+            assert np.isfinite(e) and e <= TOL, (n, k, e)
+        # outside the share the weight gradients are left untouched (NaN fill)
+        if lo > 0:
+            assert np.all(np.isnan(fc.host("dW1")[:, :lo])) and np.all(np.isnan(fc.host("dW2")[:lo]))
+        if hi < cfg["dh"]:
+            assert np.all(np.isnan(fc.host("dW1")[:, hi:])) and np.all(np.isnan(fc.host("db1")[hi:]))
+
+
+@pytest.mark.parametrize("name", ["tiny_ffn", "ragged", "sub_range_relu", "several_tiles"])
+def test_results_identical_across_k(name):
+    cfg = SMALL[name]
+    ref = None
+    for k in _ks(cfg):
+        print(f"ffn case {name} bitwise k={k}", flush=True)
+        fc, _ = _run(cfg, k)
+        outs = {n: fc.host(n) for n in ("Y", "dX", "dW1", "db1", "dW2", "db2")}
+        if ref is None:
+            ref = outs
+        else:
+            for n in outs:
+                assert np.array_equal(outs[n], ref[n], equal_nan=True), (name, k, n)
