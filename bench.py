@@ -106,6 +106,122 @@ def cpu_baseline(w, budget_s=15.0):
             "seconds": t}
 
 
+def ffn_cpu_baseline(w, budget_s=15.0):
+    """The fp64 feed-forward oracle on a bounded sample of the workload's tokens."""
+    from oracle import ffn as orc
+    from paper_2301_08984_amd.workloads import make_ffn_inputs
+    inp = make_ffn_inputs(**w)
+    kind = orc.ACT_GELU_TANH if w["act"] == "gelu" else orc.ACT_RELU
+
+    def run(nt):
+        p = orc.FfnProblem(inp["X"][:nt], inp["W1"], inp["b1"], inp["W2"], inp["b2"], kind)
+        t0 = time.perf_counter()
+        orc.coshard_forward(p, w["lo"], w["hi"], 1)
+        orc.coshard_backward(p, inp["dY"][:nt].astype(np.float64), w["lo"], w["hi"], 1)
+        return time.perf_counter() - t0
+
+    t1 = run(16)
+    nt = int(max(16, min(w["T"], 16 * budget_s / max(t1, 1e-4))))
+    t = run(nt)
+    flops = 12.0 * nt * w["dm"] * (w["hi"] - w["lo"])
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([i.get("num_threads", 1) for i in threadpool_info()] + [1])
+    except Exception:
+        threads = 1
+    threads = min(threads, len(os.sched_getaffinity(0)))
+    return {"value": flops / t / 1e12, "unit": "TFLOP/s", "cores": threads, "kind": "oracle",
+            "sample": f"{nt} of {w['T']} tokens of {w['name']} (fwd+bwd, fp64 numpy), {t:.2f} s", "seconds": t}
+
+
+def ffn_main(a):
+    """Co-sharded feed-forward: one step = ss_ffn_fwd + ss_ffn_bwd over the whole hidden share."""
+    import torch
+    from paper_2301_08984_amd import ffn_binding as fb
+    from paper_2301_08984_amd.runner import FfnCase
+    from paper_2301_08984_amd.workloads import FFN_WORKLOADS, make_ffn_inputs
+
+    w = dict(FFN_WORKLOADS[a.workload], name=a.workload)
+    ks = list(w["k"])
+    k_main = a.k if a.k is not None else (ks[1] if len(ks) > 1 else ks[0])
+    fb.lib()
+    fc = FfnCase(make_ffn_inputs(**w), act=w["act"], fill=0.0)
+    nh = w["hi"] - w["lo"]
+    flops = 12.0 * w["T"] * w["dm"] * nh   # six products of 2*T*dm*nh (two forward, four backward; recompute not counted)
+    desc = fc.desc(w["lo"], w["hi"], k_main)
+
+    def step(d):
+        fc.fwd(d)
+        fc.bwd(d)
+
+    if a.calibration_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=fc.dev)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        torch.mul(src, 2.0, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
+    for _ in range(a.warmup):
+        step(desc)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(a.steps):
+        step(desc)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) / a.steps * 1e3
+    value = flops / (ms * 1e-3) / 1e12
+    out = {"metric": "feed-forward fwd+bwd TFLOP/s (1 GPU) + % MFMA peak; peak HBM bytes vs co-shard k",
+           "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": ms,
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+           "config": {"workload": a.workload, "T": w["T"], "d_model": w["dm"], "hidden_share": nh, "act": w["act"],
+                      "k": k_main},
+           "pct_mfma_peak": 100.0 * value * 1e12 / PEAK_MFMA_BF16}
+    if not a.no_extras:
+        fb.ss_ffn_profile_enable(True)
+        for _ in range(a.steps):
+            step(desc)
+        torch.cuda.synchronize()
+        fb.ss_ffn_profile_enable(False)
+        per_kernel = {}
+        for kid, name in enumerate(fb.KERNEL_NAMES):
+            tot, n = fb.ss_ffn_profile_read(kid)
+            if n:
+                per_kernel[name] = {"avg_us": tot / n * 1e3, "launches_per_step": n / a.steps, "ms_per_step": tot / a.steps}
+        dom = max(per_kernel, key=lambda n: per_kernel[n]["ms_per_step"])
+        # every product of a chunk is 2*T*dm*(nh/k) flop; `up` runs twice per step (forward and recompute)
+        ach = 2.0 * w["T"] * w["dm"] * (nh / k_main) / (per_kernel[dom]["avg_us"] * 1e-6) / 1e12
+        out["roofline"] = {"bound": "mfma", "achieved": ach, "peak": PEAK_MFMA_BF16 / 1e12, "unit": "TFLOP/s",
+                           "frac": ach * 1e12 / PEAK_MFMA_BF16, "traffic": None, "kernel": dom,
+                           "avg_launch_us": per_kernel[dom]["avg_us"]}
+        try:
+            with open(os.path.join(ROOT, "profiles", "hbm_traffic.json")) as fh:
+                out["roofline"]["traffic"] = json.load(fh).get(a.workload, {}).get(dom)
+        except OSError:
+            pass
+        out["kernels"] = per_kernel
+        table = []
+        caller = fc.caller_bytes()
+        for k in ([] if a.no_per_k else sorted(set(ks) | {k_main})):
+            d = fc.desc(w["lo"], w["hi"], k)
+            fwd_b, bwd_b = fb.ss_ffn_workspace_bytes(d)
+            for _ in range(2):
+                step(d)
+            torch.cuda.synchronize()
+            n = max(3, a.steps // 5)
+            t0 = time.perf_counter()
+            for _ in range(n):
+                step(d)
+            torch.cuda.synchronize()
+            t = (time.perf_counter() - t0) / n
+            table.append({"k": k, "ms_per_step": t * 1e3, "tflops": flops / t / 1e12, "workspace_bytes": max(fwd_b, bwd_b),
+                          "peak_hbm_bytes": caller + max(fwd_b, bwd_b),
+                          "hidden_activation_bytes_per_chunk": int(2 * w["T"] * -(-nh // k) * 2)})
+        out["per_k"] = table
+    if not a.no_cpu_baseline:
+        out["cpu_baseline"] = ffn_cpu_baseline(w)
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -127,8 +243,10 @@ def main():
     import torch
     from paper_2301_08984_amd import binding as ss
     from paper_2301_08984_amd.runner import DeviceCase
-    from paper_2301_08984_amd.workloads import WORKLOADS, make_inputs
+    from paper_2301_08984_amd.workloads import FFN_WORKLOADS, WORKLOADS, make_inputs
 
+    if a.workload in FFN_WORKLOADS:
+        return ffn_main(a)
     w = dict(WORKLOADS[a.workload], name=a.workload)
     ext = w["H"] if w["axis"] == "head" else w["B"]
     ks = list(w["k"])

@@ -199,18 +199,36 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(GemmArgs g) {
   }
 }
 
-// out[n] = sum over m of A[m][n], fp32, fixed order: four row groups per column (rows g, g+4, ..
-// summed in ascending order), then (p0 + p1) + (p2 + p3)
+// out[n] = sum over m of A[m][n], fp32, fixed order: a work-group takes 64 columns; 32 row groups
+// per column (rows g, g+32, .. summed in ascending order, 16-byte loads of 8 columns), then the 32
+// partial sums in ascending g.  N is a multiple of 8 and A + n 16-byte aligned for n % 8 == 0.
 __global__ __launch_bounds__(256) void colsum_kernel(const uint16_t* A, int64_t lda, int M, int N, uint16_t* out) {
-  __shared__ float part[4][64];
-  const int cx = threadIdx.x & 63, ry = threadIdx.x >> 6;
-  const int n = blockIdx.x * 64 + cx;
-  float s = 0.f;
-  if (n < N)
-    for (int m = ry; m < M; m += 4) s += bf2f(A[(int64_t)m * lda + n]);
-  part[ry][cx] = s;
+  __shared__ float part[32][65];
+  const int cl = threadIdx.x & 7, rg = threadIdx.x >> 3;
+  const int n = blockIdx.x * 64 + cl * 8;
+  float s[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  if (n < N) {
+    const uint16_t* col = A + n;
+#pragma unroll 4
+    for (int m = rg; m < M; m += 32) {
+      const u32x4 v = *(const u32x4*)(col + (int64_t)m * lda);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        s[2 * e] += __uint_as_float(v[e] << 16);
+        s[2 * e + 1] += __uint_as_float(v[e] & 0xffff0000u);
+      }
+    }
+  }
+#pragma unroll
+  for (int e = 0; e < 8; ++e) part[rg][cl * 8 + e] = s[e];
   __syncthreads();
-  if (ry == 0 && n < N) out[n] = f2bf((part[0][cx] + part[1][cx]) + (part[2][cx] + part[3][cx]));
+  const int c = threadIdx.x;
+  if (c < 64 && blockIdx.x * 64 + c < N) {
+    float t = part[0][c];
+#pragma unroll
+    for (int g = 1; g < 32; ++g) t += part[g][c];
+    out[blockIdx.x * 64 + c] = f2bf(t);
+  }
 }
 
 template <bool AT, bool BT>

@@ -80,3 +80,32 @@ def test_results_identical_across_k(name):
         else:
             for n in outs:
                 assert np.array_equal(outs[n], ref[n], equal_nan=True), (name, k, n)
+
+
+def test_full_size_gpt3_share_sampled():
+    """The benchmark configuration (k = 2).  The oracle checks Y and dX on sampled tokens (rows are
+    independent), dW1 / dW2 / db1 on sampled hidden columns (each needs all tokens but only its own
+    column of the hidden layer), db2 in full."""
+    cfg = dict(FFN_WORKLOADS["gpt3_ffn"])
+    k = 2
+    print("ffn full size gpt3_ffn k=2 (sampled)", flush=True)
+    fc, inp = _run(cfg, k)
+    kind = orc.ACT_GELU_TANH
+    dY = inp["dY"].astype(np.float64)
+    rows = [0, 1, 777, 2047]
+    p = orc.FfnProblem(inp["X"][rows], inp["W1"], inp["b1"], inp["W2"], inp["b2"], kind)
+    Y = orc.ffn_forward(p)
+    g = orc.ffn_backward(p, dY[rows])
+    scale_y = float(np.max(np.abs(fc.host("Y"))))
+    scale_x = float(np.max(np.abs(fc.host("dX"))))
+    assert np.max(np.abs(fc.host("Y")[rows] - Y)) <= TOL * scale_y
+    assert np.max(np.abs(fc.host("dX")[rows] - g["dX"])) <= TOL * scale_x
+    cols = [0, 15, 16, 3071, 3072, 6143]   # both sides of the chunk boundary of k = 2
+    q = orc.FfnProblem(inp["X"], inp["W1"][:, cols], inp["b1"][cols], inp["W2"][cols], None, kind)
+    gq = orc.ffn_backward(q, dY)
+    for n, got, ref in (("dW1", fc.host("dW1")[:, cols], gq["dW1"]), ("dW2", fc.host("dW2")[cols], gq["dW2"]),
+                        ("db1", fc.host("db1")[cols], gq["db1"]), ("db2", fc.host("db2"), gq["db2"])):
+        full = fc.host(n)
+        assert np.max(np.abs(got - ref)) <= TOL * float(np.max(np.abs(full))), n
+    for n in ("Y", "dX", "dW1", "db1", "dW2", "db2"):
+        assert np.all(np.isfinite(fc.host(n))), n
