@@ -53,7 +53,7 @@ Ws layout(const ss_ffn_desc* d, bool backward) {
   size_t off = 0;
   w.H = off; off += hb;
   w.D = off; if (backward) off += hb;
-  w.acc = off; if (d->k > 1) off += align256((size_t)d->T * d->dm * 4);
+  w.acc = off; if (d->k > 1) off += align256(ssa::gemm_acc_bytes(d->T, d->dm));
   w.total = off;
   return w;
 }
@@ -152,7 +152,7 @@ int ss_ffn_fwd(const ss_ffn_desc* d, const void* X, const void* W1, const void* 
     FF_LAUNCH(SS_FK_UP, ssa::launch_gemm(up, false, false, ssa::EPI_ACT, st), "H = act(X W1 + b1)");
     // Y += H_c W2[a:b, :]; the last chunk adds b2 and writes Y
     ssa::GemmArgs dn = gemm(ws + w.H, w.ldh, W2p + (int64_t)a * d->ld_w2, d->ld_w2, d->T, d->dm, nc);
-    dn.acc32 = (float*)(ws + w.acc); dn.ld32 = d->dm; dn.accumulate = c > 0; dn.last = c == d->k - 1;
+    dn.acc32 = (float*)(ws + w.acc); dn.accumulate = c > 0; dn.last = c == d->k - 1;
     dn.bias = (const uint16_t*)b2; dn.out = (uint16_t*)Y; dn.ldo = d->ld_x;
     FF_LAUNCH(SS_FK_DOWN, ssa::launch_gemm(dn, false, false, ssa::EPI_ACC, st), "Y += H W2");
   }
@@ -199,7 +199,7 @@ int ss_ffn_bwd(const ss_ffn_desc* d, const void* X, const void* W1, const void* 
     FF_LAUNCH(SS_FK_COLSUM, ssa::launch_colsum(Dc, w.ldh, d->T, nc, (uint16_t*)db1 + a, st), "db1");
     // dX += dZ_c W1[:, a:b]^T; the last chunk writes dX
     ssa::GemmArgs gx = gemm(Dc, w.ldh, W1p + a, d->ld_w1, d->T, d->dm, nc);
-    gx.acc32 = (float*)(ws + w.acc); gx.ld32 = d->dm; gx.accumulate = c > 0; gx.last = c == d->k - 1;
+    gx.acc32 = (float*)(ws + w.acc); gx.accumulate = c > 0; gx.last = c == d->k - 1;
     gx.out = (uint16_t*)dX; gx.ldo = d->ld_x;
     FF_LAUNCH(SS_FK_DX, ssa::launch_gemm(gx, false, true, ssa::EPI_ACC, st), "dX += dZ W1^T");
   }

@@ -11,7 +11,7 @@ enum { EPI_ACT = 0, EPI_MUL = 1, EPI_ACC = 2, EPI_STORE = 3 };
 //   EPI_ACT   out = act(C + bias[n]) (bf16); out2, if given, = act'(C + bias[n])
 //   EPI_MUL   out = C * mul[m][n] (bf16; out may be mul)
 //   EPI_ACC   the accumulator starts from acc32 if `accumulate`; then `last` ? out = C + bias[n] (bf16,
-//             bias may be NULL) : acc32 = C (fp32)
+//             bias may be NULL) : acc32 = C (fp32, whole tiles in the kernel's own order; see gemm_acc_bytes)
 //   EPI_STORE out = C (bf16)
 struct GemmArgs {
   const uint16_t* A;
@@ -24,11 +24,16 @@ struct GemmArgs {
   uint16_t* out2;
   const uint16_t* mul;
   int64_t ldm;
-  float* acc32;
-  int64_t ld32;
+  float* acc32;  // ceil(M/256) * ceil(N/256) tiles of 256 x 256 fp32, in the kernel's own order
   int accumulate, last, act;
+#ifdef SS_TRACE
+  unsigned long long* trace;  // development builds only: time stamps of one work-group
+  int trace_block;
+#endif
 };
 
+// bytes of the fp32 partial-result buffer of an M x N product
+size_t gemm_acc_bytes(int M, int N);
 hipError_t launch_gemm(const GemmArgs& g, bool a_transposed, bool b_transposed, int epilogue, hipStream_t st);
 // out[n] (bf16) = sum over m of A[m][n] (bf16 in, fp32 sum, fixed order)
 hipError_t launch_colsum(const void* A, int64_t lda, int M, int N, void* out, hipStream_t st);

@@ -7,196 +7,435 @@
 namespace ssa {
 namespace {
 
-constexpr int GBM = 256, GBN = 128, GBK = 64;  // work-group tile; four wavefronts, 2 x 2, 128 x 64 each
+constexpr int GBK = 32;  // contraction depth of one stage
 constexpr float GELU_C0 = 0.7978845608028654f, GELU_C1 = 0.044715f;
 
-// k-slots of one 16-wide contraction step as the transposed LDS read delivers them to half hl of the
-// wavefront: {4hl .. 4hl+3, 8+4hl .. 8+4hl+3}.  A k-contiguous operand paired with a transposed one
-// is read in the same order, as two 8-byte pieces.
-template <int LD>
-__device__ inline bf16x8 lds_nat_perm(const uint16_t* t, int row, int ks, int hl) {
-  union { uint2 h[2]; bf16x8 v; } o;
-  o.h[0] = *(const uint2*)(t + row * LD + 16 * ks + 4 * hl);
-  o.h[1] = *(const uint2*)(t + row * LD + 16 * ks + 8 + 4 * hl);
-  return o.v;
-}
-
-__device__ inline float act_f(float z, int kind) {
-  if (kind == 0) return fmaxf(z, 0.f);
-  const float u = GELU_C0 * (z + GELU_C1 * z * z * z);
-  const float t = 1.f - 2.f * __builtin_amdgcn_rcpf(1.f + fast_exp2(2.f * LOG2E * u));
-  return 0.5f * z * (1.f + t);
-}
-__device__ inline void act_and_grad(float z, int kind, float& h, float& d) {
-  if (kind == 0) {
-    h = fmaxf(z, 0.f);
-    d = z > 0.f ? 1.f : 0.f;
-    return;
+// gelu(z) = z (1 - r), r = 1 / (1 + exp(2u)), u = C0 (z + C1 z^3)   [0.5 (1 + tanh u) = 1 - r]
+// gelu'(z) = (1 - r) (1 + 2 z r u'(z)), u'(z) = C0 (1 + 3 C1 z^2)      [1 - tanh^2 u = 4 r (1 - r)]
+template <bool GRAD>
+__device__ inline void gelu4(const float (&z)[4], float (&h)[4], float (&d)[4]) {
+  constexpr float K0 = 2.f * LOG2E * GELU_C0, K1 = K0 * GELU_C1;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const float z2 = z[e] * z[e];
+    const float r = __builtin_amdgcn_rcpf(1.f + fast_exp2(z[e] * fmaf(z2, K1, K0)));
+    const float s = 1.f - r;
+    h[e] = z[e] * s;
+    if (GRAD) d[e] = s * fmaf(2.f * z[e] * r, fmaf(z2, 3.f * GELU_C0 * GELU_C1, GELU_C0), 1.f);
   }
-  const float u = GELU_C0 * (z + GELU_C1 * z * z * z);
-  const float t = 1.f - 2.f * __builtin_amdgcn_rcpf(1.f + fast_exp2(2.f * LOG2E * u));
-  h = 0.5f * z * (1.f + t);
-  d = 0.5f * (1.f + t) + 0.5f * z * (1.f - t * t) * GELU_C0 * (1.f + 3.f * GELU_C1 * z * z);
+}
+template <bool GRAD>
+__device__ inline void relu4(const float (&z)[4], float (&h)[4], float (&d)[4]) {
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    h[e] = fmaxf(z[e], 0.f);
+    if (GRAD) d[e] = z[e] > 0.f ? 1.f : 0.f;
+  }
+}
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+// four fp32 -> four bf16 (round to nearest even, the hardware conversion)
+__device__ inline uint2 pack4(const float (&y)[4]) {
+  union { bf16x2 v; uint32_t u; } a, b;
+  a.v = __builtin_convertvector(f32x2{y[0], y[1]}, bf16x2);
+  b.v = __builtin_convertvector(f32x2{y[2], y[3]}, bf16x2);
+  return uint2{a.u, b.u};
+}
+__device__ inline void unpack4(uint2 u, float (&y)[4]) {
+  y[0] = __uint_as_float(u.x << 16); y[1] = __uint_as_float(u.x & 0xffff0000u);
+  y[2] = __uint_as_float(u.y << 16); y[3] = __uint_as_float(u.y & 0xffff0000u);
 }
 
-// Stages a ROWS x COLS tile (COLS contiguous in memory, rows `ld` elements apart) starting at
-// (r0, c0) of a matrix with rtot x ctot valid elements: thread t takes the 16-byte chunks t, t+256, ..
-// Bounds-checked buffer loads: everything outside the matrix reads as zero (the whole offset is the
-// lane offset, the only part the hardware range-checks; a column past ctot gets an offset past the
-// descriptor's extent).
-template <int ROWS, int COLS>
-struct TileLoader {
-  static constexpr int CPR = COLS / 8, CPT = ROWS * CPR / 256;
+// Work-group -> tile.  Work-groups go to the 8 XCDs round-robin in launch order and each XCD has its
+// own L2: work-group b becomes logical index (b % 8) * (tiles / 8) + b / 8, so an XCD works on a
+// contiguous range of logical indices, and logical indices walk the tile grid in bands of four
+// tile rows, down the band's rows first: the tiles an XCD runs at a time share a few row panels of
+// A and column panels of B.
+struct TilePos { int mt, nt; };
+__device__ inline TilePos tile_pos(int mtiles, int ntiles) {
+  const int tiles = mtiles * ntiles;
+  const int b = blockIdx.x, xcd = b % 8, idx = b / 8;
+  const int id = xcd * (tiles / 8) + min(xcd, tiles % 8) + idx;
+  constexpr int BAND = 4;
+  const int per_band = BAND * ntiles, band = id / per_band, in_band = id % per_band;
+  const int rows = min(BAND, mtiles - band * BAND);
+  TilePos t;
+  t.mt = band * BAND + in_band % rows;
+  t.nt = in_band / rows;
+  return t;
+}
+
+typedef __attribute__((address_space(3))) void lds_void;
+typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+constexpr uint32_t OUTSIDE = 0x7ffffff0u;  // a lane offset past every descriptor's extent: the load returns zeros
+
+// One operand of a 16 KS deep contraction stage (KS = 16-wide contraction steps per stage), 64 F
+// rows (of A) or columns (of B) -- "rho" below; F = 32-wide fragments per wavefront -- fetched from
+// global memory straight into LDS, 16 bytes per lane, 1 KB per wavefront instruction, F KS / 2
+// instructions per wavefront.  Bounds-checked buffer loads (the whole offset is the lane offset,
+// the only part the hardware range-checks): everything outside the matrix lands as zeros.  The LDS
+// image is swizzled at 16-byte granularity by choosing WHICH global chunk a lane fetches for its
+// fixed LDS slot, so that the fragment reads below are free of bank conflicts:
+//   TR = false (contraction index contiguous in memory): LDS row = rho, 32 KS bytes = 2 KS chunks;
+//        chunk c of row rho sits at slot c ^ ((rho >> 2) & 3) (KS = 2), c ^ ((rho >> 1) & 7) (KS = 4)
+//   TR = true  (rho contiguous in memory): LDS row = k, 128 F bytes = 8 F chunks; chunk c of row k
+//        sits at slot c ^ (4 * (k & 3))
+// With KS = 2 a row of a contraction-contiguous operand is half a cache line per stage, and the
+// compute unit's load path then moves whole lines for half the bytes: KS = 4 for such operands.
+template <bool TR, int F, int KS>
+struct Stager {
+  static constexpr int BYTES = 2048 * F * KS, NI = F * KS / 2, BK = 16 * KS;
+  const char* base;      // start of the next stage to fetch
+  int64_t step;          // bytes from one stage to the next
+  int left;              // bytes from `base` to the end of the matrix (meaningful while k0 < ktot)
+  int k0, kcur, ktot;
+  uint32_t lane_off[NI]; // lane offset of instruction t inside a stage (OUTSIDE if its rho are not in the matrix)
+  int klimit[2];         // !TR: the lane's chunk (even / odd instruction) is inside the contraction range while k0 <= klimit
   __amdgpu_buffer_rsrc_t rs;
-  uint32_t lane_off[CPT];  // (row_in_tile * ld + 8 * chunk_in_row) * 2
-  int ccol;                // 8 * chunk_in_row (the same for all of a thread's chunks: 256 % CPR == 0)
-  uint32_t ld2;
-  int ctot;
-  __device__ void init(const uint16_t* base, int64_t ld, int rtot, int ctot_, int tid) {
-    rs = __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, (int)(((int64_t)(rtot - 1) * ld + ctot_) * 2), 0x00020000);
-    ld2 = (uint32_t)ld * 2u;
-    ctot = ctot_;
-    ccol = (tid % CPR) * 8;
+  __device__ void init(const uint16_t* base_, int64_t ld, int rho_tot, int ktot_, int rho0, int lane, int w) {
+    base = (const char*)base_;
+    const uint32_t ld2 = (uint32_t)ld * 2u;
+    ktot = ktot_;
+    k0 = kcur = 0;
+    klimit[0] = klimit[1] = 0;
+    if (!TR) {
+      constexpr int CPR = 2 * KS, RPI = 64 / CPR;  // chunks per LDS row, rows per instruction
+      step = 2 * BK;
+      left = (int)(((int64_t)(rho_tot - 1) * ld + ktot_) * 2);
 #pragma unroll
-    for (int c = 0; c < CPT; ++c) lane_off[c] = (uint32_t)((tid + c * 256) / CPR) * ld2 + (uint32_t)ccol * 2u;
+      for (int t = 0; t < NI; ++t) {
+        const int row = RPI * (w * NI + t) + lane / CPR;
+        const int c = (lane % CPR) ^ (KS == 2 ? (row >> 2) & 3 : (row >> 1) & 7);
+        lane_off[t] = (uint32_t)(rho0 + row) * ld2 + 16u * c;
+        if (t < 2) klimit[t] = ktot_ - 8 * c - 8;  // the chunk depends on the parity of t only
+      }
+    } else {
+      constexpr int LPR = 8 * F, RPI = 64 / LPR;  // lanes per LDS row, rows per instruction
+      step = (int64_t)BK * ld * 2;
+      left = (int)(((int64_t)(ktot_ - 1) * ld + rho_tot) * 2);
+#pragma unroll
+      for (int t = 0; t < NI; ++t) {
+        const int krow = RPI * (w * NI + t) + lane / LPR;
+        const int c = (lane % LPR) ^ (4 * (krow & 3));
+        lane_off[t] = rho0 + 8 * c + 8 <= rho_tot ? (uint32_t)krow * ld2 + (uint32_t)(rho0 + 8 * c) * 2u : OUTSIDE;
+      }
+    }
   }
-  __device__ void load(u32x4 (&dst)[CPT], int r0, int c0) const {
-    const uint32_t so = (uint32_t)r0 * ld2 + (uint32_t)c0 * 2u;
-    const bool inside = c0 + ccol < ctot;
-#pragma unroll
-    for (int c = 0; c < CPT; ++c)
-      dst[c] = __builtin_amdgcn_raw_buffer_load_b128(rs, inside ? lane_off[c] + so : 0x7ffffff0u, 0, 0);
+  // Scalar work once per stage, stages in ascending order: a descriptor that starts at the stage's
+  // first contraction index and ends with the matrix, so the lane offsets are the same for every
+  // stage, and is empty for stages past the end of the contraction (they load zeros).
+  __device__ void begin_stage() {
+    rs = __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, k0 < ktot ? left : 0, 0x00020000);
+    kcur = k0;
+    base += step;
+    left -= (int)step;
+    k0 += BK;
   }
-  template <int LD>
-  __device__ static void store(uint16_t* t, const u32x4 (&src)[CPT], int tid) {
+  // instruction t (0..NI-1) of the stage -> LDS at `dst` (this operand's part of a stage buffer)
+  __device__ void issue(char* dst, int w, int t) const {
+    const bool ok = TR || kcur <= klimit[t & 1];
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_void*)(dst + (w * NI + t) * 1024), 16, ok ? lane_off[t] : OUTSIDE, 0, 0, 0);
+  }
+};
+
+// Fragment addresses of one operand for one wavefront (`wr` = which half of the tile's rho).
+// A fragment is 32 rho x 16 k, lane (r = lane % 32, hl = lane / 32) holding rho = r, k = 8 hl .. 8 hl + 7.
+template <bool TR, int F, int KS>
+struct FragReader {
+  uint32_t a0;
+  uint32_t blk[TR ? F : 1];
+  __device__ void init(int lane, int wr) {
+    const int r = lane & 31, hl = lane >> 5;
+    if (!TR) {
+      const int sw = KS == 2 ? (r >> 2) & 3 : (r >> 1) & 7;
+      a0 = (uint32_t)(32 * F * wr + r) * (32u * KS) + (uint32_t)((hl ^ sw) << 4);
+      blk[0] = 0;
+    } else {
+      const int i = lane & 15, bk = lane >> 4, kk = 8 * (bk >> 1) + (i >> 2);
+      a0 = (uint32_t)kk * (128u * F) + 32u * (bk & 1) + 8u * (i & 3);
 #pragma unroll
-    for (int c = 0; c < CPT; ++c) {
-      const int idx = tid + c * 256, row = idx / CPR, col = (idx % CPR) * 8;
-      *(u32x4*)(t + row * LD + col) = src[c];
+      for (int f = 0; f < F; ++f) blk[f] = (uint32_t)(((F * wr + f) ^ ((i >> 2) & 3)) << 6);
+    }
+  }
+  // fragment f (rho = 32 F wr + 32 f ..) of contraction step ks of the stage at `op`
+  __device__ bf16x8 read(const char* op, int f, int ks) const {
+#ifdef SS_NO_DSREAD
+    union { u32x4 u; bf16x8 v; } z;
+    z.u = u32x4{a0, a0 + f, a0 + ks, a0};
+    return z.v;
+#endif
+    if (!TR) {
+      return *(const bf16x8*)(op + ((a0 ^ (uint32_t)(ks << 5)) + (uint32_t)f * (1024u * KS)));
+    } else {
+      const char* p = op + (a0 + blk[f] + (uint32_t)ks * (2048u * F));
+      union { s16x4 h[2]; bf16x8 v; } o;
+      o.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)p);
+      o.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p + 512 * F));
+      return o.v;
     }
   }
 };
+
+// slot of item `i` when `n` items are dealt out evenly over `slots` slots; how many come before `slot`
+constexpr int slot_of(int i, int n, int slots) { return i * slots / n; }
+constexpr int items_before(int slot, int n, int slots) {
+  int c = 0;
+  for (int i = 0; i < n; ++i) c += slot_of(i, n, slots) < slot ? 1 : 0;
+  return c;
+}
 
 // ---------------------------------------------------------------------------
 // C[M,N] = A B with bf16 operands and fp32 accumulation on v_mfma_f32_32x32x16_bf16.
 //   AT = false: A[m][k] at A + m*lda + k      AT = true: A[k][m] at A + k*lda + m
 //   BT = false: B[k][n] at B + k*ldb + n      BT = true: B[n][k] at B + n*ldb + k
-// A 256 x 128 tile per work-group, 64-wide contraction stages through LDS (one buffer per operand,
-// the next stage travels global -> registers meanwhile; two work-groups per compute unit overlap
-// each other's staging).  Operands whose contraction index is not contiguous in memory are read
-// from LDS with the transposed read.  The contraction runs in ascending k, 16 at a time, whatever
-// the tile position: with EPI_ACC the accumulator starts from the fp32 partial result of the
-// previous chunks, so a sum cut into chunks at multiples of 16 is the same sum.
+// Four wavefronts, 2 x 2, each with 32 FI x 32 FJ of the result in accumulation registers; a stage
+// is KS contraction steps of 16 deep; NS stage buffers form a ring:
+//   FI = 4, FJ = 2, KS = 2, NS = 3: 256 x 128 tile, 72 KB of LDS and 128 accumulation registers:
+//        two work-groups per compute unit, which overlap each other's prologue, epilogue and
+//        barriers.  For products whose operands are both read transposed.
+//   FI = 4, FJ = 2, KS = 4, NS = 3: 144 KB of LDS, one work-group per compute unit, half as many
+//        barriers per MFMA.  For products with a contraction-contiguous operand (see Stager).
+//   FI = FJ = 4, KS = 2, NS = 4: 256 x 256 tile, 256 accumulation registers (half the LDS reads and
+//        loads per MFMA of the others); not used by the feed-forward shapes, which have too few
+//        such tiles to go round.
+// Stages travel global -> LDS directly, NS - 1 stages ahead of the multiplication, the load
+// instructions spread evenly between the MFMAs (the compute unit's load path moves 64 bytes per
+// cycle, of which the kernel needs 32 to 48), and one barrier per stage, issued with half a step of
+// MFMAs still to go so the matrix cores keep busy across it.  Operands whose contraction index is
+// not contiguous in memory are read from LDS with the transposed read.
+// The matrix cores are fed B fragments as their row operand and A fragments as their column
+// operand, so a lane ends up with one row m and runs of four consecutive columns n.
+// The contraction runs in ascending k, 16 at a time, whatever the tile position or shape: with
+// EPI_ACC the accumulator starts from the fp32 partial result of the previous chunks, so a sum
+// cut into chunks at multiples of 16 is the same sum.
 // ---------------------------------------------------------------------------
-template <bool AT, bool BT, int EPI>
-__global__ __launch_bounds__(256, 2) void gemm_kernel(GemmArgs g) {
-  constexpr int LDA = AT ? GBM + 16 : GBK + 8, LDB = BT ? GBK + 8 : GBN + 16;
-  constexpr int A_ELEMS = AT ? GBK * LDA : GBM * LDA, B_ELEMS = BT ? GBN * LDB : GBK * LDB;
-  __shared__ __attribute__((aligned(16))) uint16_t sA[A_ELEMS];
-  __shared__ __attribute__((aligned(16))) uint16_t sB[B_ELEMS];
-  using LoadA = TileLoader<AT ? GBK : GBM, AT ? GBM : GBK>;
-  using LoadB = TileLoader<BT ? GBN : GBK, BT ? GBK : GBN>;
-  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, r = lane & 31, hl = lane >> 5;
+template <bool AT, bool BT, int EPI, int FI, int FJ, int KS>
+__global__ __launch_bounds__(256, (FI * FJ <= 8 && KS == 2) ? 2 : 1) void gemm_kernel(GemmArgs g) {
+  constexpr int NS = FI * FJ <= 8 ? 3 : 4;  // stage buffers
+  constexpr int GBM = 64 * FI, GBN = 64 * FJ;
+  using StageA = Stager<AT, FI, KS>;
+  using StageB = Stager<!BT, FJ, KS>;
+  constexpr int A_BYTES = StageA::BYTES, STAGE_BYTES = StageA::BYTES + StageB::BYTES;
+  constexpr int NM = FI * FJ, SLOTS = KS * NM;             // MFMAs per contraction step / per stage
+  constexpr int LA = StageA::NI, NL = LA + StageB::NI;     // loads per stage (per wavefront): A first
+  constexpr int NR = FI + FJ;                              // fragment reads per step
+  constexpr int BAR = SLOTS - NM / 2;                      // the barrier sits before this slot
+  // the stage buffers are separate arrays: the compiler then knows that a load into one does not
+  // feed a read of another, and does not wait for it
+  __shared__ __attribute__((aligned(1024))) char stage0[STAGE_BYTES];
+  __shared__ __attribute__((aligned(1024))) char stage1[STAGE_BYTES];
+  __shared__ __attribute__((aligned(1024))) char stage2[STAGE_BYTES];
+  __shared__ __attribute__((aligned(1024))) char stage3[NS == 4 ? STAGE_BYTES : 16];
+  const int tid = threadIdx.x, lane = tid & 63, r = lane & 31, hl = lane >> 5;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = w >> 1, wn = w & 1;
-  const int m0 = blockIdx.y * GBM, n0 = blockIdx.x * GBN;
+  const int mtiles = (g.M + GBM - 1) / GBM, ntiles = (g.N + GBN - 1) / GBN;
+  const TilePos tp = tile_pos(mtiles, ntiles);
+  const int m0 = tp.mt * GBM, n0 = tp.nt * GBN;
 
-  LoadA la;
-  LoadB lb;
-  la.init(g.A, g.lda, AT ? g.K : g.M, AT ? g.M : g.K, tid);
-  lb.init(g.B, g.ldb, BT ? g.N : g.K, BT ? g.K : g.N, tid);
-  u32x4 pa[LoadA::CPT], pb[LoadB::CPT];
-  auto gload = [&](int k0) {
-    if (AT) la.load(pa, k0, m0); else la.load(pa, m0, k0);
-    if (BT) lb.load(pb, n0, k0); else lb.load(pb, k0, n0);
-  };
+  StageA sa;
+  StageB sb;
+  sa.init(g.A, g.lda, g.M, g.K, m0, lane, w);
+  sb.init(g.B, g.ldb, g.N, g.K, n0, lane, w);
+  FragReader<AT, FI, KS> ra;
+  FragReader<!BT, FJ, KS> rb;
+  ra.init(lane, wm);
+  rb.init(lane, wn);
 
-  f32x16 acc[4][2];
+#ifdef SS_TRACE
+  __shared__ uint64_t tr_buf[16];
+  int tr_n = 0;
+  auto stamp = [&] { if (tr_n < 16) tr_buf[tr_n] = __builtin_amdgcn_s_memtime(); ++tr_n; };
+#define SS_MARK() do { if (w == 0) stamp(); } while (0)
+#else
+#define SS_MARK() do {} while (0)
+#endif
+  SS_MARK();
+  // acc[j][i]: row m0 + 32 FI wm + 32 i + r, columns n0 + 32 FJ wn + 32 j + key_of(v, hl).
+  // The fp32 partial result between chunks lives in the workspace in the order the registers hold
+  // it (tile, wavefront, (j, i, quad), lane): 1 KB per wavefront instruction, fully coalesced.
+  f32x16 acc[FJ][FI];
+  f32x4* frag32 = nullptr;
+  if (EPI == EPI_ACC) frag32 = (f32x4*)g.acc32 + ((int64_t)(tp.mt * ntiles + tp.nt) * 4 + w) * (NM * 4 * 64) + lane;
   if (EPI == EPI_ACC && g.accumulate) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int j = 0; j < FJ; ++j)
 #pragma unroll
-      for (int j = 0; j < 2; ++j) {
-        const int n = n0 + wn * 64 + 32 * j + r;
+      for (int i = 0; i < FI; ++i)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int m = m0 + wm * 128 + 32 * i + key_of(v, hl);
-          acc[i][j][v] = (m < g.M && n < g.N) ? g.acc32[(int64_t)m * g.ld32 + n] : 0.f;
+        for (int q = 0; q < 4; ++q) {
+          const f32x4 v = frag32[((j * FI + i) * 4 + q) * 64];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) acc[j][i][4 * q + e] = v[e];
         }
-      }
   } else {
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int j = 0; j < FJ; ++j)
 #pragma unroll
-      for (int j = 0; j < 2; ++j)
+      for (int i = 0; i < FI; ++i)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+        for (int v = 0; v < 16; ++v) acc[j][i][v] = 0.f;
   }
 
-  const int nk = (g.K + GBK - 1) / GBK;
-  gload(0);
-  for (int kt = 0; kt < nk; ++kt) {
-    __syncthreads();
-    LoadA::template store<LDA>(sA, pa, tid);
-    LoadB::template store<LDB>(sB, pb, tid);
-    if (kt + 1 < nk) gload((kt + 1) * GBK);
-    __syncthreads();
+  // the stage count is rounded up to a multiple of the ring: stages past the end load zeros and add nothing
+  const int nk = (g.K + 16 * KS - 1) / (16 * KS), nkr = (nk + NS - 1) / NS * NS;
+  bf16x8 fa[2][FI], fb[2][FJ];  // fragments of the contraction step being multiplied and of the next one
+  // fragment reads of one contraction step in the order of their first use: B 0, A 0 .. FI-1, B 1 .. FJ-1
+  auto read_item = [&](const char* st, int item, int ks, int set) {
+    if (item == 0) fb[set][0] = rb.read(st + A_BYTES, 0, ks);
+    else if (item <= FI) fa[set][item - 1] = ra.read(st, item - 1, ks);
+    else fb[set][item - FI] = rb.read(st + A_BYTES, item - FI, ks);
+  };
+  // One stage: multiply `cur` (the fragments of its first step are in registers), fetch the stage
+  // NS - 1 ahead into `ldst` (the buffer of the stage before `cur`, free since the last barrier),
+  // and, once the stage after `cur` has landed for every wavefront, read the fragments of its
+  // first step from `nxt`.  KS NM slots of one MFMA each; the other instructions are dealt out over
+  // the slots (loads evenly over the stage, the fragments of the next step over a step, in the
+  // order of their first use) and the scheduler is told to keep every slot together: the matrix
+  // cores stall as soon as the instructions between two MFMAs take longer to issue than one MFMA
+  // takes to run.
+  auto stage = [&](const char* cur, const char* nxt, char* ldst) {
+#ifdef SS_NO_DMA
+    const bool dma = false;
+#else
+    const bool dma = true;
+#endif
+    sa.begin_stage();
+    sb.begin_stage();
 #pragma unroll
-    for (int ks = 0; ks < GBK / 16; ++ks) {
-      bf16x8 fa[4], fb[2];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int mrow = wm * 128 + 32 * i;
-        if (AT) fa[i] = lds_tr<LDA>(sA, 16 * ks, mrow, lane);
-        else if (!BT) fa[i] = lds_nat_perm<LDA>(sA, mrow + r, ks, hl);
-        else fa[i] = lds_nat<LDA>(sA, mrow + r, ks, hl);
+    for (int s = 0; s < SLOTS; ++s) {
+      const int ks = s / NM, x = s % NM, j = x / FI, i = x % FI;
+      if (s == BAR) {
+        // all but the youngest loads are done: the next stage is in LDS (this wavefront's part), and
+        // so are this wavefront's reads of `cur`.  A bare barrier: __syncthreads() would wait for
+        // every load in flight.
+        asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"((NS - 3) * NL + items_before(BAR, NL, SLOTS)) : "memory");
+#ifndef SS_NO_BARRIER
+        __builtin_amdgcn_s_barrier();
+#endif
+        asm volatile("" ::: "memory");
       }
+      acc[j][i] = mfma(fb[ks & 1][j], fa[ks & 1][i], acc[j][i]);
 #pragma unroll
-      for (int j = 0; j < 2; ++j) {
-        const int ncol = wn * 64 + 32 * j;
-        if (!BT) fb[j] = lds_tr<LDB>(sB, 16 * ks, ncol, lane);
-        else if (AT) fb[j] = lds_nat_perm<LDB>(sB, ncol + r, ks, hl);
-        else fb[j] = lds_nat<LDB>(sB, ncol + r, ks, hl);
+      for (int l = 0; l < NL; ++l)
+        if (dma && s == slot_of(l, NL, SLOTS)) {
+          if (l < LA) sa.issue(ldst, w, l);
+          else sb.issue(ldst + A_BYTES, w, l - LA);
+        }
+      if (ks + 1 < KS) {  // fragments of the next step of this stage
+#pragma unroll
+        for (int item = 0; item < NR; ++item)
+          if (x == 1 + slot_of(item, NR, NM - 2)) read_item(cur, item, ks + 1, (ks + 1) & 1);
+      } else if (s >= BAR) {  // fragments of the first step of the next stage
+#pragma unroll
+        for (int item = 0; item < NR; ++item)
+          if (s - BAR == slot_of(item, NR, NM / 2)) read_item(nxt, item, 0, 0);
       }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  };
+  auto fetch_all = [&](char* dst) {
+    sa.begin_stage();
+    sb.begin_stage();
 #pragma unroll
-      for (int i = 0; i < 4; ++i)
+    for (int t = 0; t < LA; ++t) sa.issue(dst, w, t);
 #pragma unroll
-        for (int j = 0; j < 2; ++j) acc[i][j] = mfma(fa[i], fb[j], acc[i][j]);
+    for (int t = 0; t < NL - LA; ++t) sb.issue(dst + A_BYTES, w, t);
+  };
+  SS_MARK();
+  fetch_all(stage0);
+  fetch_all(stage1);
+  if (NS == 4) fetch_all(stage2);
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NS - 2) * NL) : "memory");
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+#pragma unroll
+  for (int item = 0; item < NR; ++item) read_item(stage0, item, 0, 0);
+  SS_MARK();
+  for (int kt = 0; kt < nkr; kt += NS) {
+    if (NS == 4) {
+      stage(stage0, stage1, stage3);
+      stage(stage1, stage2, stage0);
+      stage(stage2, stage3, stage1);
+      stage(stage3, stage0, stage2);
+    } else {
+      stage(stage0, stage1, stage2);
+      stage(stage1, stage2, stage0);
+      stage(stage2, stage0, stage1);
     }
   }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  SS_MARK();
 
-  // epilogue: lane = column n, register v = row m
+  if (EPI == EPI_ACC && !g.last) {
 #pragma unroll
-  for (int j = 0; j < 2; ++j) {
-    const int n = n0 + wn * 64 + 32 * j + r;
-    if (n >= g.N) continue;
-    float bias = 0.f;
-    if ((EPI == EPI_ACT || (EPI == EPI_ACC && g.last)) && g.bias) bias = bf2f(g.bias[n]);
+    for (int j = 0; j < FJ; ++j)
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+      for (int i = 0; i < FI; ++i)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int m = m0 + wm * 128 + 32 * i + key_of(v, hl);
-        if (m >= g.M) continue;
-        const float x = acc[i][j][v];
+        for (int q = 0; q < 4; ++q)
+          frag32[((j * FI + i) * 4 + q) * 64] =
+              f32x4{acc[j][i][4 * q], acc[j][i][4 * q + 1], acc[j][i][4 * q + 2], acc[j][i][4 * q + 3]};
+  } else {
+    // Epilogue through LDS, one 32-row block of the wavefront's part at a time: the registers hold
+    // one row and scattered column quads per lane; written to a piece of stage buffer of the
+    // wavefront's own (rows padded by 16 bytes: conflict-free both ways) and read back as whole
+    // rows, 8 FJ lanes x 4 columns, so that every global access of the epilogue is 64 FJ
+    // contiguous bytes per row.  Everybody's loads have landed and everybody has left the main loop
+    // before a buffer is reused.
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    constexpr int TLD = 128 * FJ + 16, LPR = 8 * FJ, RPI = 64 / LPR;
+    static_assert(32 * TLD <= (NS == 4 ? STAGE_BYTES : STAGE_BYTES / 2), "epilogue staging does not fit");
+    char* tb = NS == 4 ? (w == 0 ? stage0 : w == 1 ? stage1 : w == 2 ? stage2 : stage3)
+                       : (w == 0 ? stage0 : w == 1 ? stage1 : w == 2 ? stage2 : stage0 + STAGE_BYTES / 2);
+    const int c4 = 4 * (lane % LPR), rsub = lane / LPR;
+    const int n = n0 + wn * 32 * FJ + c4;
+    float bias[4] = {0.f, 0.f, 0.f, 0.f};
+    if ((EPI == EPI_ACT || EPI == EPI_ACC) && g.bias && n < g.N) unpack4(*(const uint2*)(g.bias + n), bias);
+#pragma unroll
+    for (int i = 0; i < FI; ++i) {
+#pragma unroll
+      for (int j = 0; j < FJ; ++j)
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+          *(f32x4*)(tb + r * TLD + (32 * j + 8 * q + 4 * hl) * 4) =
+              f32x4{acc[j][i][4 * q], acc[j][i][4 * q + 1], acc[j][i][4 * q + 2], acc[j][i][4 * q + 3]};
+#pragma unroll
+      for (int it = 0; it < 32 / RPI; ++it) {
+        const int row = RPI * it + rsub, m = m0 + wm * 32 * FI + 32 * i + row;
+        const f32x4 v = *(const f32x4*)(tb + row * TLD + c4 * 4);
+        if (m >= g.M || n >= g.N) continue;
+        float x[4] = {v[0] + bias[0], v[1] + bias[1], v[2] + bias[2], v[3] + bias[3]};
+        uint16_t* orow = g.out + (int64_t)m * g.ldo + n;
         if (EPI == EPI_ACT) {
+          float h[4], d[4];
           if (g.out2) {
-            float h, d;
-            act_and_grad(x + bias, g.act, h, d);
-            g.out[(int64_t)m * g.ldo + n] = f2bf(h);
-            g.out2[(int64_t)m * g.ldo + n] = f2bf(d);
+            if (g.act == 0) relu4<true>(x, h, d); else gelu4<true>(x, h, d);
+            *(uint2*)(g.out2 + (int64_t)m * g.ldo + n) = pack4(d);
           } else {
-            g.out[(int64_t)m * g.ldo + n] = f2bf(act_f(x + bias, g.act));
+            if (g.act == 0) relu4<false>(x, h, d); else gelu4<false>(x, h, d);
           }
+          *(uint2*)orow = pack4(h);
         } else if (EPI == EPI_MUL) {
-          g.out[(int64_t)m * g.ldo + n] = f2bf(x * bf2f(g.mul[(int64_t)m * g.ldm + n]));
-        } else if (EPI == EPI_ACC) {
-          if (g.last) g.out[(int64_t)m * g.ldo + n] = f2bf(x + bias);
-          else g.acc32[(int64_t)m * g.ld32 + n] = x;
+          float mu[4];
+          unpack4(*(const uint2*)(g.mul + (int64_t)m * g.ldm + n), mu);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) x[e] *= mu[e];
+          *(uint2*)orow = pack4(x);
         } else {
-          g.out[(int64_t)m * g.ldo + n] = f2bf(x);
+          *(uint2*)orow = pack4(x);
         }
       }
+    }
   }
+#ifdef SS_TRACE
+  __builtin_amdgcn_s_waitcnt(0);
+  SS_MARK();
+  if (w == 0 && lane == 0 && g.trace && (int)blockIdx.x == g.trace_block) {
+    for (int i = 0; i < 16 && i < tr_n; ++i) g.trace[i] = tr_buf[i];
+  }
+#endif
 }
 
 // out[n] = sum over m of A[m][n], fp32, fixed order: a work-group takes 64 columns; 32 row groups
@@ -231,19 +470,53 @@ __global__ __launch_bounds__(256) void colsum_kernel(const uint16_t* A, int64_t 
   }
 }
 
-template <bool AT, bool BT>
-hipError_t launch_epi(const GemmArgs& g, int epi, hipStream_t st) {
-  const dim3 grid((g.N + GBN - 1) / GBN, (g.M + GBM - 1) / GBM);
-  switch (epi) {
-    case EPI_ACT: gemm_kernel<AT, BT, EPI_ACT><<<grid, 256, 0, st>>>(g); break;
-    case EPI_MUL: gemm_kernel<AT, BT, EPI_MUL><<<grid, 256, 0, st>>>(g); break;
-    case EPI_ACC: gemm_kernel<AT, BT, EPI_ACC><<<grid, 256, 0, st>>>(g); break;
-    default: gemm_kernel<AT, BT, EPI_STORE><<<grid, 256, 0, st>>>(g); break;
-  }
+// Explicit instantiations: the host compiler emits the launch stub of the first implicit
+// instantiation only.
+#define SS_GEMM_INST(a, b, e, fi, fj, ks) template __global__ void gemm_kernel<a, b, e, fi, fj, ks>(GemmArgs);
+#define SS_GEMM_INST4(a, b, fi, fj, ks) \
+  SS_GEMM_INST(a, b, 0, fi, fj, ks) SS_GEMM_INST(a, b, 1, fi, fj, ks) SS_GEMM_INST(a, b, 2, fi, fj, ks) SS_GEMM_INST(a, b, 3, fi, fj, ks)
+#ifdef SS_FORCE_TILE
+SS_GEMM_INST4(false, false, SS_FORCE_TILE / 100, SS_FORCE_TILE / 10 % 10, SS_FORCE_TILE % 10)
+SS_GEMM_INST4(false, true, SS_FORCE_TILE / 100, SS_FORCE_TILE / 10 % 10, SS_FORCE_TILE % 10)
+SS_GEMM_INST4(true, false, SS_FORCE_TILE / 100, SS_FORCE_TILE / 10 % 10, SS_FORCE_TILE % 10)
+#else
+SS_GEMM_INST4(false, false, 4, 2, 4)
+SS_GEMM_INST4(false, true, 4, 2, 4)
+SS_GEMM_INST4(true, false, 4, 2, 2)
+#endif
+#undef SS_GEMM_INST4
+#undef SS_GEMM_INST
+
+template <bool AT, bool BT, int EPI, int FI, int FJ, int KS>
+hipError_t launch_one(const GemmArgs& g, hipStream_t st) {
+  const int tiles = ((g.M + 64 * FI - 1) / (64 * FI)) * ((g.N + 64 * FJ - 1) / (64 * FJ));
+  gemm_kernel<AT, BT, EPI, FI, FJ, KS><<<tiles, 256, 0, st>>>(g);
   return hipGetLastError();
 }
 
+// The tile shape depends on the operand layouts only, never on the sizes: every chunk of an
+// accumulated product must cut its fp32 partial result into the same tiles.
+template <bool AT, bool BT>
+hipError_t launch_epi(const GemmArgs& g, int epi, hipStream_t st) {
+#ifdef SS_FORCE_TILE
+  constexpr int FI = SS_FORCE_TILE / 100, FJ = SS_FORCE_TILE / 10 % 10, KS = SS_FORCE_TILE % 10;
+#else
+  constexpr int FI = 4, FJ = 2, KS = AT ? 2 : 4;
+#endif
+  switch (epi) {
+    case EPI_ACT: return launch_one<AT, BT, EPI_ACT, FI, FJ, KS>(g, st);
+    case EPI_MUL: return launch_one<AT, BT, EPI_MUL, FI, FJ, KS>(g, st);
+    case EPI_ACC: return launch_one<AT, BT, EPI_ACC, FI, FJ, KS>(g, st);
+    default: return launch_one<AT, BT, EPI_STORE, FI, FJ, KS>(g, st);
+  }
+}
+
 }  // namespace
+
+size_t gemm_acc_bytes(int M, int N) {
+  // whole tiles; no tile is larger than 256 x 256
+  return (size_t)((M + 255) / 256) * ((N + 255) / 256) * 256 * 256 * sizeof(float);
+}
 
 hipError_t launch_gemm(const GemmArgs& g, bool at, bool bt, int epi, hipStream_t st) {
   if (g.M <= 0 || g.N <= 0 || g.K <= 0) return hipErrorInvalidValue;
