@@ -97,26 +97,44 @@ class DeviceCase:
 class FfnCase:
     """One feed-forward operator resident on the GPU plus its output buffers (bf16)."""
 
-    def __init__(self, inputs: dict, *, act="gelu", device="cuda:0", fill=float("nan")):
+    def __init__(self, inputs: dict, *, act="gelu", device="cuda:0", fill=float("nan"), pad=(0, 0, 0)):
+        """pad = extra elements (multiples of 8) in the leading dimension of the [T, dm] matrices, of
+        W1 / dW1 and of W2 / dW2; the padding holds NaN, so any read of it shows in the results."""
         from . import ffn_binding as fb
         if not torch.cuda.is_available():
             raise RuntimeError("no GPU: the HIP path has no CPU fallback")
         self.fb = fb
         self.dev = torch.device(device)
-        up = lambda a: None if a is None else torch.from_numpy(np.ascontiguousarray(a)).to(self.dev).to(
-            torch.bfloat16).contiguous()
-        self.X, self.W1, self.b1, self.W2, self.b2, self.dY = (up(inputs.get(n)) for n in
-                                                              ("X", "W1", "b1", "W2", "b2", "dY"))
-        self.T, self.dm = self.X.shape
-        self.dh = self.W1.shape[1]
+        self.pad = tuple(pad)
+
+        def matrix(rows, cols, extra, values=None):
+            buf = torch.full((rows, cols + extra), float("nan") if values is not None else fill, dtype=torch.bfloat16,
+                             device=self.dev)
+            view = buf[:, :cols]
+            if values is not None:
+                view.copy_(torch.from_numpy(np.ascontiguousarray(values)).to(self.dev).to(torch.bfloat16))
+            elif extra:
+                buf[:, cols:] = float("nan")
+            return view
+
+        vec = lambda a: None if a is None else torch.from_numpy(np.ascontiguousarray(a)).to(self.dev).to(torch.bfloat16)
+        self.T, self.dm = inputs["X"].shape
+        self.dh = inputs["W1"].shape[1]
+        px, pw1, pw2 = self.pad
+        self.X = matrix(self.T, self.dm, px, inputs["X"])
+        self.dY = matrix(self.T, self.dm, px, inputs["dY"])
+        self.W1 = matrix(self.dm, self.dh, pw1, inputs["W1"])
+        self.W2 = matrix(self.dh, self.dm, pw2, inputs["W2"])
+        self.b1, self.b2 = vec(inputs.get("b1")), vec(inputs.get("b2"))
         self.act = fb.SS_ACT_GELU_TANH if act == "gelu" else fb.SS_ACT_RELU
-        mk = lambda t: torch.full_like(t, fill)
-        self.Y, self.dX, self.dW1, self.db1, self.dW2, self.db2 = (mk(self.X), mk(self.X), mk(self.W1), mk(self.b1),
-                                                                  mk(self.W2), mk(self.X[0]))
+        self.Y, self.dX = matrix(self.T, self.dm, px), matrix(self.T, self.dm, px)
+        self.dW1, self.dW2 = matrix(self.dm, self.dh, pw1), matrix(self.dh, self.dm, pw2)
+        self.db1, self.db2 = torch.full_like(self.b1, fill), torch.full((self.dm,), fill, dtype=torch.bfloat16, device=self.dev)
         self.ws = None
 
     def desc(self, lo, hi, k):
-        return self.fb.make_desc(self.T, self.dm, self.dh, lo, hi, k, act=self.act)
+        return self.fb.make_desc(self.T, self.dm, self.dh, lo, hi, k, act=self.act, ld_x=self.dm + self.pad[0],
+                                 ld_w1=self.dh + self.pad[1], ld_w2=self.dm + self.pad[2])
 
     def workspace(self, desc):
         f, b = self.fb.ss_ffn_workspace_bytes(desc)

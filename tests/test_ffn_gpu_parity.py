@@ -109,3 +109,30 @@ def test_full_size_gpt3_share_sampled():
         assert np.max(np.abs(got - ref)) <= TOL * float(np.max(np.abs(full))), n
     for n in ("Y", "dX", "dW1", "db1", "dW2", "db2"):
         assert np.all(np.isfinite(fc.host(n))), n
+
+
+def test_padded_leading_dimensions_are_never_read_or_written():
+    """Every matrix sits in a wider buffer whose padding holds NaN: a read past a row's end would
+    poison the results, a write past it would show in the padding."""
+    import torch
+    from paper_2301_08984_amd.runner import FfnCase
+    cfg = dict(seed=65, T=333, dm=200, dh=424, lo=8, hi=416, act="gelu")
+    inp = make_ffn_inputs(**cfg)
+    Y, g = _oracle(cfg, inp)
+    lo, hi = cfg["lo"], cfg["hi"]
+    for k in (1, 3):
+        print(f"ffn padded k={k}", flush=True)
+        fc = FfnCase(inp, act=cfg["act"], pad=(8, 16, 24))
+        d = fc.desc(lo, hi, k)
+        fc.fwd(d)
+        fc.bwd(d)
+        torch.cuda.synchronize()
+        errs = {"Y": rel_err(fc.host("Y"), Y), "dX": rel_err(fc.host("dX"), g["dX"]),
+                "dW1": rel_err(fc.host("dW1")[:, lo:hi], g["dW1"][:, lo:hi]),
+                "db1": rel_err(fc.host("db1")[lo:hi], g["db1"][lo:hi]),
+                "dW2": rel_err(fc.host("dW2")[lo:hi], g["dW2"][lo:hi]), "db2": rel_err(fc.host("db2"), g["db2"])}
+        for n, e in errs.items():
+            assert np.isfinite(e) and e <= TOL, (n, k, e)
+        for name, width in (("Y", cfg["dm"]), ("dX", cfg["dm"]), ("dW1", cfg["dh"]), ("dW2", cfg["dm"])):
+            base = getattr(fc, name)._base
+            assert bool(torch.isnan(base[:, width:].float()).all()), name
