@@ -16,8 +16,12 @@
  * [T, (hi-lo)/k] are alive at a time, and the backward recomputes them (Sections 2 and 6.3).
  *
  * All pointers are DEVICE pointers unless said otherwise; the descriptor and size outputs are HOST
- * memory.  The library allocates no device memory and never synchronises; everything is enqueued
- * on the caller's stream.  Error codes are those of ss_attn.h.
+ * memory.  The library allocates no device memory and never synchronises the host; the work is
+ * enqueued on the caller's stream, except that ss_ffn_bwd forks one product per chunk (dW2) onto a
+ * helper stream of the library's own (one per device, default priority, created on first use) and
+ * joins it back into the caller's stream with events before the call returns: to the caller the
+ * call is ordered on its stream like any other.  SS_FFN_ONE_STREAM=1 in the environment keeps
+ * everything on the caller's stream.  Error codes are those of ss_attn.h.
  */
 #ifndef SS_FFN_H
 #define SS_FFN_H

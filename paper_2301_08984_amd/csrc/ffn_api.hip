@@ -3,6 +3,7 @@
 #include "../../include/ss_ffn.h"
 
 #include <cstdio>
+#include <cstdlib>
 
 #include "ffn_kernels.h"
 
@@ -91,15 +92,42 @@ void drain() {
   g_npending = 0;
 }
 
-#define FF_LAUNCH(kind, expr, what)                  \
+#define FF_LAUNCH_ON(stream_, kind, expr, what)      \
   do {                                               \
     hipError_t e_;                                   \
     {                                                \
-      Prof ps_(st, kind);                            \
+      Prof ps_(stream_, kind);                       \
       e_ = (expr);                                   \
     }                                                \
     if (e_ != hipSuccess) return hip_fail(e_, what); \
   } while (0)
+#define FF_LAUNCH(kind, expr, what) FF_LAUNCH_ON(st, kind, expr, what)
+
+// A helper stream per device (default priority, created on first use, kept until the process ends):
+// dW2 = H^T dY needs only H, so it is forked onto the helper stream after the recompute, runs beside
+// dZ = (dY W2^T) act'(Z) -- whose T x chunk output has too few tiles to fill the chip -- and is joined
+// back into the caller's stream before anything overwrites H.
+struct Side {
+  hipStream_t s = nullptr;
+  hipEvent_t fork = nullptr, join = nullptr;
+  int state = 0;  // 0 not tried, 1 ready, -1 unavailable
+};
+Side g_side[64];
+Side* side_stream() {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
+  Side& sd = g_side[dev];
+  if (sd.state == 0) {
+    const char* off = std::getenv("SS_FFN_ONE_STREAM");
+    sd.state = -1;
+    if (!(off && off[0] == '1') && hipStreamCreateWithFlags(&sd.s, hipStreamNonBlocking) == hipSuccess &&
+        hipEventCreateWithFlags(&sd.fork, hipEventDisableTiming) == hipSuccess &&
+        hipEventCreateWithFlags(&sd.join, hipEventDisableTiming) == hipSuccess)
+      sd.state = 1;
+    (void)hipGetLastError();
+  }
+  return sd.state == 1 ? &sd : nullptr;
+}
 
 ssa::GemmArgs gemm(const void* A, int64_t lda, const void* B, int64_t ldb, int M, int N, int K) {
   ssa::GemmArgs g{};
@@ -173,6 +201,7 @@ int ss_ffn_bwd(const ss_ffn_desc* d, const void* X, const void* W1, const void* 
   const uint16_t* W2p = (const uint16_t*)W2;
   uint16_t* Hc = (uint16_t*)(ws + w.H);
   uint16_t* Dc = (uint16_t*)(ws + w.D);
+  Side* side = side_stream();
   if (db2) FF_LAUNCH(SS_FK_COLSUM, ssa::launch_colsum(dY, d->ld_x, d->T, d->dm, db2, st), "db2");
   for (int c = 0; c < d->k; ++c) {
     int a, b;
@@ -183,14 +212,24 @@ int ss_ffn_bwd(const ss_ffn_desc* d, const void* X, const void* W1, const void* 
     ssa::GemmArgs up = gemm(X, d->ld_x, W1p + a, d->ld_w1, d->T, nc, d->dm);
     up.bias = (const uint16_t*)b1 + a; up.out = Hc; up.out2 = Dc; up.ldo = w.ldh; up.act = d->act;
     FF_LAUNCH(SS_FK_UP, ssa::launch_gemm(up, false, false, ssa::EPI_ACT, st), "recompute H, act'(Z)");
+    // dW2[a:b, :] = H_c^T dY, beside the next product when the helper stream is there
+    ssa::GemmArgs gw2 = gemm(Hc, w.ldh, dY, d->ld_x, nc, d->dm, d->T);
+    gw2.out = (uint16_t*)dW2 + (int64_t)a * d->ld_w2; gw2.ldo = d->ld_w2;
+    const bool forked = side && hipEventRecord(side->fork, st) == hipSuccess &&
+                        hipStreamWaitEvent(side->s, side->fork, 0) == hipSuccess;
+    if (forked) {
+      FF_LAUNCH_ON(side->s, SS_FK_DW2, ssa::launch_gemm(gw2, true, false, ssa::EPI_STORE, side->s), "dW2 = H^T dY");
+      if (hipEventRecord(side->join, side->s) != hipSuccess) return hip_fail(hipGetLastError(), "join record");
+    }
     // dZ_c = (dY W2[a:b,:]^T) * D_c, in place over D_c
     ssa::GemmArgs dh = gemm(dY, d->ld_x, W2p + (int64_t)a * d->ld_w2, d->ld_w2, d->T, nc, d->dm);
     dh.mul = Dc; dh.ldm = w.ldh; dh.out = Dc; dh.ldo = w.ldh;
     FF_LAUNCH(SS_FK_DH, ssa::launch_gemm(dh, false, true, ssa::EPI_MUL, st), "dZ = (dY W2^T) act'(Z)");
-    // dW2[a:b, :] = H_c^T dY
-    ssa::GemmArgs gw2 = gemm(Hc, w.ldh, dY, d->ld_x, nc, d->dm, d->T);
-    gw2.out = (uint16_t*)dW2 + (int64_t)a * d->ld_w2; gw2.ldo = d->ld_w2;
-    FF_LAUNCH(SS_FK_DW2, ssa::launch_gemm(gw2, true, false, ssa::EPI_STORE, st), "dW2 = H^T dY");
+    if (forked) {
+      if (hipStreamWaitEvent(st, side->join, 0) != hipSuccess) return hip_fail(hipGetLastError(), "join wait");
+    } else {
+      FF_LAUNCH(SS_FK_DW2, ssa::launch_gemm(gw2, true, false, ssa::EPI_STORE, st), "dW2 = H^T dY");
+    }
     // dW1[:, a:b] = X^T dZ_c
     ssa::GemmArgs gw1 = gemm(X, d->ld_x, Dc, w.ldh, d->dm, nc, d->T);
     gw1.out = (uint16_t*)dW1 + a; gw1.ldo = d->ld_w1;

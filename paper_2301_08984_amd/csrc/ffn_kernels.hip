@@ -159,11 +159,6 @@ struct FragReader {
   }
   // fragment f (rho = 32 F wr + 32 f ..) of contraction step ks of the stage at `op`
   __device__ bf16x8 read(const char* op, int f, int ks) const {
-#ifdef SS_NO_DSREAD
-    union { u32x4 u; bf16x8 v; } z;
-    z.u = u32x4{a0, a0 + f, a0 + ks, a0};
-    return z.v;
-#endif
     if (!TR) {
       return *(const bf16x8*)(op + ((a0 ^ (uint32_t)(ks << 5)) + (uint32_t)f * (1024u * KS)));
     } else {
@@ -295,11 +290,6 @@ __global__ __launch_bounds__(256, (FI * FJ <= 8 && KS == 2) ? 2 : 1) void gemm_k
   // cores stall as soon as the instructions between two MFMAs take longer to issue than one MFMA
   // takes to run.
   auto stage = [&](const char* cur, const char* nxt, char* ldst) {
-#ifdef SS_NO_DMA
-    const bool dma = false;
-#else
-    const bool dma = true;
-#endif
     sa.begin_stage();
     sb.begin_stage();
 #pragma unroll
@@ -310,15 +300,13 @@ __global__ __launch_bounds__(256, (FI * FJ <= 8 && KS == 2) ? 2 : 1) void gemm_k
         // so are this wavefront's reads of `cur`.  A bare barrier: __syncthreads() would wait for
         // every load in flight.
         asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"((NS - 3) * NL + items_before(BAR, NL, SLOTS)) : "memory");
-#ifndef SS_NO_BARRIER
         __builtin_amdgcn_s_barrier();
-#endif
         asm volatile("" ::: "memory");
       }
       acc[j][i] = mfma(fb[ks & 1][j], fa[ks & 1][i], acc[j][i]);
 #pragma unroll
       for (int l = 0; l < NL; ++l)
-        if (dma && s == slot_of(l, NL, SLOTS)) {
+        if (s == slot_of(l, NL, SLOTS)) {
           if (l < LA) sa.issue(ldst, w, l);
           else sb.issue(ldst + A_BYTES, w, l - LA);
         }
