@@ -17,7 +17,7 @@
  *
  * All pointers are DEVICE pointers unless said otherwise; the descriptor and size outputs are HOST
  * memory.  The library allocates no device memory and never synchronises the host; the work is
- * enqueued on the caller's stream, except that ss_ffn_bwd forks one product per chunk (dW2) onto a
+ * enqueued on the caller's stream, except that ss_ffn_bwd forks dW2 and the bias gradients onto a
  * helper stream of the library's own (one per device, default priority, created on first use) and
  * joins it back into the caller's stream with events before the call returns: to the caller the
  * call is ordered on its stream like any other.  SS_FFN_ONE_STREAM=1 in the environment keeps
@@ -74,7 +74,8 @@ int ss_ffn_bwd(const ss_ffn_desc* desc, const void* X, const void* W1, const voi
                void* dX, void* dW1, void* db1, void* dW2, void* db2, void* workspace, size_t workspace_bytes,
                void* stream);
 
-/* Benchmark instrumentation as in ss_attn.h: kernels of the feed-forward path. */
+/* Benchmark instrumentation as in ss_attn.h: kernels of the feed-forward path.  While it is enabled
+ * the helper stream is not used, so that every kernel is timed running alone. */
 typedef enum {
   SS_FK_UP = 0,      /* H = act(X W1 + b1) (forward and recompute)   */
   SS_FK_DOWN = 1,    /* Y += H W2                                    */

@@ -104,9 +104,10 @@ void drain() {
 #define FF_LAUNCH(kind, expr, what) FF_LAUNCH_ON(st, kind, expr, what)
 
 // A helper stream per device (default priority, created on first use, kept until the process ends):
-// dW2 = H^T dY needs only H, so it is forked onto the helper stream after the recompute, runs beside
-// dZ = (dY W2^T) act'(Z) -- whose T x chunk output has too few tiles to fill the chip -- and is joined
-// back into the caller's stream before anything overwrites H.
+// dW2 = H^T dY needs only H, and the bias gradients only dY or dZ, so they are forked onto the helper
+// stream, run beside the products of the caller's stream -- dZ = (dY W2^T) act'(Z) has too few tiles
+// to fill the chip -- and are joined back before the next chunk overwrites H and dZ, and before the
+// call returns.
 struct Side {
   hipStream_t s = nullptr;
   hipEvent_t fork = nullptr, join = nullptr;
@@ -201,47 +202,68 @@ int ss_ffn_bwd(const ss_ffn_desc* d, const void* X, const void* W1, const void* 
   const uint16_t* W2p = (const uint16_t*)W2;
   uint16_t* Hc = (uint16_t*)(ws + w.H);
   uint16_t* Dc = (uint16_t*)(ws + w.D);
-  Side* side = side_stream();
-  if (db2) FF_LAUNCH(SS_FK_COLSUM, ssa::launch_colsum(dY, d->ld_x, d->T, d->dm, db2, st), "db2");
+  Side* side = g_on ? nullptr : side_stream();  // per-kernel timing wants the kernels one at a time
+  bool pending = false;  // work on the helper stream that the caller's stream has not waited for yet
+  // run `launch` on the helper stream after everything enqueued on the caller's stream so far
+  auto fork = [&]() {
+    return side && hipEventRecord(side->fork, st) == hipSuccess && hipStreamWaitEvent(side->s, side->fork, 0) == hipSuccess;
+  };
+  auto join = [&]() {
+    if (!pending) return hipSuccess;
+    pending = false;
+    const hipError_t e = hipEventRecord(side->join, side->s);
+    return e != hipSuccess ? e : hipStreamWaitEvent(st, side->join, 0);
+  };
+  if (db2) {
+    if (fork()) {
+      pending = true;
+      FF_LAUNCH_ON(side->s, SS_FK_COLSUM, ssa::launch_colsum(dY, d->ld_x, d->T, d->dm, db2, side->s), "db2");
+    } else {
+      FF_LAUNCH(SS_FK_COLSUM, ssa::launch_colsum(dY, d->ld_x, d->T, d->dm, db2, st), "db2");
+    }
+  }
   for (int c = 0; c < d->k; ++c) {
     int a, b;
     chunk(d, c, &a, &b);
     const int nc = b - a;
     if (nc <= 0) continue;
+    // the helper stream still reads H and dZ of the previous chunk
+    if (join() != hipSuccess) return hip_fail(hipGetLastError(), "join");
     // recompute: H_c = act(Z_c), D_c = act'(Z_c)
     ssa::GemmArgs up = gemm(X, d->ld_x, W1p + a, d->ld_w1, d->T, nc, d->dm);
     up.bias = (const uint16_t*)b1 + a; up.out = Hc; up.out2 = Dc; up.ldo = w.ldh; up.act = d->act;
     FF_LAUNCH(SS_FK_UP, ssa::launch_gemm(up, false, false, ssa::EPI_ACT, st), "recompute H, act'(Z)");
-    // dW2[a:b, :] = H_c^T dY, beside the next product when the helper stream is there
+    // dW2[a:b, :] = H_c^T dY, beside the products that follow when the helper stream is there
     ssa::GemmArgs gw2 = gemm(Hc, w.ldh, dY, d->ld_x, nc, d->dm, d->T);
     gw2.out = (uint16_t*)dW2 + (int64_t)a * d->ld_w2; gw2.ldo = d->ld_w2;
-    const bool forked = side && hipEventRecord(side->fork, st) == hipSuccess &&
-                        hipStreamWaitEvent(side->s, side->fork, 0) == hipSuccess;
-    if (forked) {
+    if (fork()) {
+      pending = true;
       FF_LAUNCH_ON(side->s, SS_FK_DW2, ssa::launch_gemm(gw2, true, false, ssa::EPI_STORE, side->s), "dW2 = H^T dY");
-      if (hipEventRecord(side->join, side->s) != hipSuccess) return hip_fail(hipGetLastError(), "join record");
+    } else {
+      FF_LAUNCH(SS_FK_DW2, ssa::launch_gemm(gw2, true, false, ssa::EPI_STORE, st), "dW2 = H^T dY");
     }
     // dZ_c = (dY W2[a:b,:]^T) * D_c, in place over D_c
     ssa::GemmArgs dh = gemm(dY, d->ld_x, W2p + (int64_t)a * d->ld_w2, d->ld_w2, d->T, nc, d->dm);
     dh.mul = Dc; dh.ldm = w.ldh; dh.out = Dc; dh.ldo = w.ldh;
     FF_LAUNCH(SS_FK_DH, ssa::launch_gemm(dh, false, true, ssa::EPI_MUL, st), "dZ = (dY W2^T) act'(Z)");
-    if (forked) {
-      if (hipStreamWaitEvent(st, side->join, 0) != hipSuccess) return hip_fail(hipGetLastError(), "join wait");
+    // db1[a:b] = column sums of dZ_c
+    if (fork()) {
+      pending = true;
+      FF_LAUNCH_ON(side->s, SS_FK_COLSUM, ssa::launch_colsum(Dc, w.ldh, d->T, nc, (uint16_t*)db1 + a, side->s), "db1");
     } else {
-      FF_LAUNCH(SS_FK_DW2, ssa::launch_gemm(gw2, true, false, ssa::EPI_STORE, st), "dW2 = H^T dY");
+      FF_LAUNCH(SS_FK_COLSUM, ssa::launch_colsum(Dc, w.ldh, d->T, nc, (uint16_t*)db1 + a, st), "db1");
     }
     // dW1[:, a:b] = X^T dZ_c
     ssa::GemmArgs gw1 = gemm(X, d->ld_x, Dc, w.ldh, d->dm, nc, d->T);
     gw1.out = (uint16_t*)dW1 + a; gw1.ldo = d->ld_w1;
     FF_LAUNCH(SS_FK_DW1, ssa::launch_gemm(gw1, true, false, ssa::EPI_STORE, st), "dW1 = X^T dZ");
-    // db1[a:b] = column sums of dZ_c
-    FF_LAUNCH(SS_FK_COLSUM, ssa::launch_colsum(Dc, w.ldh, d->T, nc, (uint16_t*)db1 + a, st), "db1");
     // dX += dZ_c W1[:, a:b]^T; the last chunk writes dX
     ssa::GemmArgs gx = gemm(Dc, w.ldh, W1p + a, d->ld_w1, d->T, d->dm, nc);
     gx.acc32 = (float*)(ws + w.acc); gx.accumulate = c > 0; gx.last = c == d->k - 1;
     gx.out = (uint16_t*)dX; gx.ldo = d->ld_x;
     FF_LAUNCH(SS_FK_DX, ssa::launch_gemm(gx, false, true, ssa::EPI_ACC, st), "dX += dZ W1^T");
   }
+  if (join() != hipSuccess) return hip_fail(hipGetLastError(), "join");
   return SS_OK;
 }
 
