@@ -136,3 +136,70 @@ def test_padded_leading_dimensions_are_never_read_or_written():
         for name, width in (("Y", cfg["dm"]), ("dX", cfg["dm"]), ("dW1", cfg["dh"]), ("dW2", cfg["dm"])):
             base = getattr(fc, name)._base
             assert bool(torch.isnan(base[:, width:].float()).all()), name
+
+
+def test_optional_output_bias_and_its_gradient():
+    """b2 = NULL (a tensor-parallel caller adds it after its all-reduce) and db2 = NULL (skipped)."""
+    import torch
+    from paper_2301_08984_amd.runner import FfnCase
+    cfg = SMALL["several_tiles"]
+    inp = make_ffn_inputs(**cfg)
+    kind = orc.ACT_GELU_TANH
+    p = orc.FfnProblem(inp["X"], inp["W1"], inp["b1"], inp["W2"], inp["b2"], kind)
+    Y = orc.ffn_forward(p, cfg["lo"], cfg["hi"], add_b2=False)
+    for k in (1, 2):
+        print(f"ffn no-b2 k={k}", flush=True)
+        fc = FfnCase(inp, act=cfg["act"])
+        fc.b2, fc.db2 = None, None
+        d = fc.desc(cfg["lo"], cfg["hi"], k)
+        fc.fwd(d)
+        fc.bwd(d)
+        torch.cuda.synchronize()
+        assert rel_err(fc.host("Y"), Y) <= TOL
+        assert np.all(np.isfinite(fc.host("dX")))
+
+
+def test_graph_capture_replays_match_eager():
+    """Forward + backward captured into a HIP graph (the helper stream is forked and joined inside
+    the capture) and replayed with eager work and synchronisations in between: every replay gives
+    the eager result, bit for bit."""
+    import torch
+    from paper_2301_08984_amd.runner import FfnCase
+    cfg = SMALL["several_tiles"]
+    inp = make_ffn_inputs(**cfg)
+    fc = FfnCase(inp, act=cfg["act"])
+    d = fc.desc(cfg["lo"], cfg["hi"], 3)
+    fc.fwd(d)
+    fc.bwd(d)
+    torch.cuda.synchronize()
+    names = ("Y", "dX", "dW1", "db1", "dW2", "db2")
+    eager = {n: getattr(fc, n).clone() for n in names}
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        fc.fwd(d)  # warm-up on the capturing stream
+        fc.bwd(d)
+        torch.cuda.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            fc.fwd(d)
+            fc.bwd(d)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    for rep in range(3):
+        print(f"ffn graph replay {rep}", flush=True)
+        for n in names:
+            getattr(fc, n).fill_(float("nan"))
+        scratch = torch.randn(1 << 20, device=fc.dev).sum()  # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for n in names:
+            a, b = getattr(fc, n), eager[n]
+            lo, hi = cfg["lo"], cfg["hi"]
+            if n == "dW1":
+                a, b = a[:, lo:hi], b[:, lo:hi]
+            if n in ("db1", "dW2"):
+                a, b = a[lo:hi], b[lo:hi]
+            assert torch.equal(a, b), (n, rep)
+        del scratch
