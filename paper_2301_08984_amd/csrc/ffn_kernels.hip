@@ -191,8 +191,8 @@ constexpr int items_before(int slot, int n, int slots) {
 //   FI = 4, FJ = 2, KS = 4, NS = 3: 144 KB of LDS, one work-group per compute unit, half as many
 //        barriers per MFMA.  For products with a contraction-contiguous operand (see Stager).
 //   FI = FJ = 4, KS = 2, NS = 4: 256 x 256 tile, 256 accumulation registers (half the LDS reads and
-//        loads per MFMA of the others); not used by the feed-forward shapes, which have too few
-//        such tiles to go round.
+//        loads per MFMA of the others); not instantiated: the feed-forward shapes have too few such
+//        tiles to go round.
 // Stages travel global -> LDS directly, NS - 1 stages ahead of the multiplication, the load
 // instructions spread evenly between the MFMAs (the compute unit's load path moves 64 bytes per
 // cycle, of which the kernel needs 32 to 48), and one barrier per stage, issued with half a step of
