@@ -203,3 +203,26 @@ def test_graph_capture_replays_match_eager():
                 a, b = a[lo:hi], b[lo:hi]
             assert torch.equal(a, b), (n, rep)
         del scratch
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_shapes_match_oracle(seed):
+    """Seeded random shapes: ragged token counts, model and hidden widths that are not multiples of
+    the 64-deep stage or of the 256 x 128 tile, sub-ranges, every k up to the limit."""
+    rng = np.random.default_rng(9000 + seed)
+    T = int(rng.integers(1, 700))
+    dm = 8 * int(rng.integers(1, 70))
+    dh = 8 * int(rng.integers(2, 90))
+    lo = 8 * int(rng.integers(0, dh // 16))
+    hi = min(dh, lo + 8 * int(rng.integers(1, (dh - lo) // 8 + 1)))
+    cfg = dict(seed=9100 + seed, T=T, dm=dm, dh=dh, lo=lo, hi=hi, act="gelu" if seed % 3 else "relu")
+    k = int(rng.integers(1, -(-(hi - lo) // 16) + 1))
+    print(f"ffn random case {cfg} k={k}", flush=True)
+    fc, inp = _run(cfg, k)
+    Y, g = _oracle(cfg, inp)
+    errs = {"Y": rel_err(fc.host("Y"), Y), "dX": rel_err(fc.host("dX"), g["dX"]),
+            "dW1": rel_err(fc.host("dW1")[:, lo:hi], g["dW1"][:, lo:hi]),
+            "db1": rel_err(fc.host("db1")[lo:hi], g["db1"][lo:hi]),
+            "dW2": rel_err(fc.host("dW2")[lo:hi], g["dW2"][lo:hi]), "db2": rel_err(fc.host("db2"), g["db2"])}
+    for n, e in errs.items():
+        assert np.isfinite(e) and e <= TOL, (n, cfg, k, e)
