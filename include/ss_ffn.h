@@ -42,7 +42,8 @@ typedef enum { SS_ACT_RELU = 0, SS_ACT_GELU_TANH = 1 } ss_act;
  *   X, Y, dY, dX : [T, dm], row stride ld_x
  *   W1, dW1      : [dm, dh], row stride ld_w1        b1, db1 : [dh]
  *   W2, dW2      : [dh, dm], row stride ld_w2        b2, db2 : [dm]
- * dm and dh multiples of 8.  lo and hi-lo need no alignment, but chunk boundaries fall on
+ * dm and dh multiples of 8; every operand smaller than 2 GiB and every leading dimension below
+ * 2^22 elements (SS_ERR_UNSUPPORTED otherwise).  lo and hi multiples of 8; chunk boundaries fall on
  * multiples of 16 hidden columns counted from lo (ss_ffn_chunk_range). */
 typedef struct {
   int32_t T, dm, dh;

@@ -23,7 +23,9 @@ int validate(const ss_ffn_desc* d) {
   if (d->lo < 0 || d->lo >= d->hi || d->hi > d->dh || (d->lo & 7) || (d->hi & 7)) return SS_ERR_BAD_RANGE;
   const int units = (d->hi - d->lo + UNIT - 1) / UNIT;
   if (d->k < 1 || d->k > units) return SS_ERR_BAD_K;
-  // 32-bit byte offsets inside one operand
+  // 32-bit byte offsets inside one operand, also for the rows of a ragged tile that lie past the
+  // end of the matrix (up to 255 of them): their offsets must not wrap back into the matrix
+  if (d->ld_x >= (1 << 22) || d->ld_w1 >= (1 << 22) || d->ld_w2 >= (1 << 22)) return SS_ERR_UNSUPPORTED;
   const int64_t lim = (int64_t)1 << 31;
   if ((int64_t)d->T * d->ld_x * 2 >= lim || (int64_t)d->dm * d->ld_w1 * 2 >= lim || (int64_t)d->dh * d->ld_w2 * 2 >= lim)
     return SS_ERR_UNSUPPORTED;

@@ -352,7 +352,7 @@ __global__ __launch_bounds__(256, (FI * FJ <= 8 && KS == 2) ? 2 : 1) void gemm_k
       stage(stage2, stage0, stage1);
     }
   }
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
   SS_MARK();
 
   if (EPI == EPI_ACC && !g.last) {

@@ -46,7 +46,8 @@ def test_validation_and_chunks():
     bad = [(dict(T=0), ss.SS_ERR_BAD_SHAPE), (dict(dm=60), ss.SS_ERR_BAD_SHAPE), (dict(ld_x=32), ss.SS_ERR_BAD_SHAPE),
            (dict(lo=4), ss.SS_ERR_BAD_RANGE), (dict(hi=300), ss.SS_ERR_BAD_RANGE), (dict(lo=256), ss.SS_ERR_BAD_RANGE),
            (dict(k=0), ss.SS_ERR_BAD_K), (dict(k=17), ss.SS_ERR_BAD_K), (dict(dtype=ss.SS_F32), ss.SS_ERR_UNSUPPORTED),
-           (dict(act=7), ss.SS_ERR_UNSUPPORTED)]
+           (dict(act=7), ss.SS_ERR_UNSUPPORTED), (dict(T=1, ld_x=1 << 22), ss.SS_ERR_UNSUPPORTED),
+           (dict(T=1 << 20, ld_x=2048), ss.SS_ERR_UNSUPPORTED)]
     for change, code in bad:
         d = fb.make_desc(100, 64, 256, 0, 256, 4)
         for f, v in change.items():
