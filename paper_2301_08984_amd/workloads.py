@@ -137,6 +137,8 @@ FFN_WORKLOADS = {
     # one GPU's tensor-parallel share of a GPT-3 175B feed-forward block: d_model 12288, hidden 49152
     # split 8 ways, 2048 tokens (the sequence of the attention share)
     "gpt3_ffn": dict(seed=9002, T=2048, dm=12288, dh=6144, lo=0, hi=6144, act="gelu", k=(1, 2, 4)),
+    # the same share with a micro-batch of four sequences: enough tiles in every product to fill the chip
+    "gpt3_ffn_mb4": dict(seed=9003, T=8192, dm=12288, dh=6144, lo=0, hi=6144, act="gelu", k=(1, 2, 4)),
 }
 
 
