@@ -161,3 +161,56 @@ def test_the_examples_cheaper_chain_under_the_link_model():
     assert [s[0] for s in steps] == [P.REDUCE_SCATTER, P.ALL_GATHER] and t_found < t_paper
     m = nbytes // 2
     assert t_paper == 2 * cm.alpha_ns + 2 * ((m // 2) * 1000 // cm.link_bytes_per_us) + (m // 2) * 1000 // cm.link_bytes_per_us
+
+
+# ---- the paper's printed examples as fixtures (tests/golden/, each with its citation)
+def _golden(name):
+    import json
+    import os
+    with open(os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", name)) as fh:
+        return json.load(fh)
+
+
+def test_golden_rvd_worked_example():
+    gold = _golden("rvd_worked_example.json")
+    names = {n: i for i, n in enumerate(P.PRIMITIVE_NAMES)}
+    state = tuple(gold["producer"])
+    assert state[0] * state[1] * P._prod(state[2:]) == gold["vtensors_represented"]
+    for step in gold["steps"]:
+        options = [ns for prim, a, b, g, ns in P.transitions(state)
+                   if prim == names[step["primitive"]] and g == step["over_every"] and ns == tuple(step["layout_after"])]
+        assert len(options) == 1, step
+        state = options[0]
+    assert state == tuple(gold["consumer"])
+
+
+def test_golden_materialization_example():
+    gold = _golden("materialization_example.json")
+    R, C = 10, 14
+    region = {"left half": ((0, 0), (R, C // 2)), "right half": ((0, C // 2), (R, C)), "top half": ((0, 0), (R // 2, C)),
+              "top-left part": ((0, 0), (R // 2, C // 2)), "top-right part": ((0, C // 2), (R // 2, C))}
+    ops = {}
+    for i, (name, where) in enumerate(list(gold["producers"].items()) + list(gold["consumer"].items())):
+        lo, hi = region[where]
+        ops[name] = P.VTensor(op=i, tensor=0, lo=lo, hi=hi)
+    for pair, where in gold["overlaps"].items():
+        a, b = pair.split(" and ")
+        assert P.intersect(ops[a], ops[b]) == region[where]
+
+
+def test_golden_microbenchmark_same_group_categories_take_one_primitive():
+    gold = _golden("rvd_microbenchmark_categories.json")
+    import re
+    expected = {("R", "R"): [], ("R", "D"): [P.SCHUNK], ("V", "R"): [P.ALL_REDUCE], ("V", "D"): [P.REDUCE_SCATTER],
+                ("D", "R"): [P.ALL_GATHER], ("D", "D"): []}
+    assert len(gold["categories"]) * len(gold["configurations"]) == 18
+    for cat in gold["categories"]:
+        which = lambda text, sym: [m.group(1) for m in re.finditer(r"([RVD])\((%s)\)" % sym, text)][0]
+        src_kind, dst_kind = which(cat["producers"], "i"), which(cat["consumers"], "j")
+        for i, j in gold["configurations"]:
+            layout = lambda kind, n: {"R": (n, 1, 1), "V": (1, n, 1), "D": (1, 1, n)}[kind]
+            found = P.rvd_search(layout(src_kind, i), layout(dst_kind, j), 1 << 24)
+            if i != j:
+                assert found is None  # different group sizes: not a same-group search
+            else:
+                assert [s[0] for s in found[1]] == expected[(src_kind, dst_kind)]
