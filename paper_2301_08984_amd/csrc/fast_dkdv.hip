@@ -17,7 +17,7 @@ namespace {
 // ---------------------------------------------------------------------------
 template <int D, bool BIAS, bool CAUSAL, int NW>
 __global__ __launch_bounds__(64 * NW) void dkdv_fast_kernel(KP p) {
-  constexpr int KS = D / 16, DB = D / 32, LD = D + 16, NT = 64 * NW, BK = 32 * NW;
+  constexpr int KS = D / 16, DB = D / 32, LD = D + 24, NT = 64 * NW, BK = 32 * NW;  // tiles read both ways
   constexpr int CPR = D / 8, CPT = BN * CPR / NT;
   __shared__ __attribute__((aligned(16))) uint16_t sQ[2][BN * LD];
   __shared__ __attribute__((aligned(16))) uint16_t sG[2][BN * LD];

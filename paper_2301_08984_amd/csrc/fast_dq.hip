@@ -15,7 +15,7 @@ namespace {
 template <int D, bool BIAS, bool CAUSAL, int QW, int NG>
 __global__ __launch_bounds__(64 * QW * NG) __attribute__((amdgpu_waves_per_eu(2, 2))) void dq_fast_kernel(KP p) {
   constexpr int KS = D / 16, DB = D / 32, NT = 64 * QW, BM = 32 * QW;
-  constexpr int LDK = D + 16, LDV = D + 8;
+  constexpr int LDK = D + 24, LDV = D + 8;  // K is read both ways: D + 24 is conflict-free for b128 and transposed reads
   constexpr int CPR = D / 8, CPT = BN * CPR / NT;
   constexpr int TILE_ELEMS = BN * LDK + BN * LDV;
   constexpr int MERGE_ELEMS = NT * (16 * DB) * 2 * (NG - 1);

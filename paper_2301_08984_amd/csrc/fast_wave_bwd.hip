@@ -13,13 +13,13 @@ namespace {
 // ---------------------------------------------------------------------------
 template <int D, int NG>
 constexpr int dq_wave_lds_elems() {
-  constexpr int SLOT = 2 * (32 * (D + 16) + 32 * (D + 8)), MERGE = NG * 64 * 4 * (D / 32) * 8;
+  constexpr int SLOT = 2 * (32 * (D + 24) + 32 * (D + 8)), MERGE = NG * 64 * 4 * (D / 32) * 8;
   return NG * SLOT > MERGE ? NG * SLOT : MERGE;
 }
 template <int D, bool BIAS, bool CAUSAL, int NG>
 __device__ __forceinline__ void dq_wave_block(const KP& p, uint16_t* smem, int rank, int by, int bz_) {
   constexpr int KS = D / 16, DB = D / 32, SUB = 32, CPT = D / 16;
-  constexpr int LDK = D + 16, LDV = D + 8;  // K is also read transposed
+  constexpr int LDK = D + 24, LDV = D + 8;  // K is also read transposed: D + 24 is conflict-free both ways
   constexpr int BUF = SUB * LDK + SUB * LDV;
   constexpr int SLOT = 2 * BUF;
   constexpr int MSLOT = 64 * 4 * DB;
@@ -232,12 +232,12 @@ __device__ __forceinline__ void dq_wave_block(const KP& p, uint16_t* smem, int r
 // ---------------------------------------------------------------------------
 template <int D, int QG>
 constexpr int dkdv_wave_lds_elems() {
-  constexpr int SLOT = 4 * 32 * (D + 16) + 2 * 2 * 2 * 32, MERGE = QG * 64 * 8 * (D / 32) * 8;
+  constexpr int SLOT = 4 * 32 * (D + 24) + 2 * 2 * 2 * 32, MERGE = QG * 64 * 8 * (D / 32) * 8;
   return QG * SLOT > MERGE ? QG * SLOT : MERGE;
 }
 template <int D, bool BIAS, bool CAUSAL, int QG>
 __device__ __forceinline__ void dkdv_wave_block(const KP& p, uint16_t* smem, int rank, int by, int bz_) {
-  constexpr int KS = D / 16, DB = D / 32, LD = D + 16, SUB = 32;
+  constexpr int KS = D / 16, DB = D / 32, LD = D + 24, SUB = 32;  // read both ways: conflict-free for b128 and transposed reads
   constexpr int CPR = D / 8, CPT = SUB * CPR / 64;
   constexpr int MAT = SUB * LD;                  // uint16 elements of one staged matrix
   constexpr int SLOT = 4 * MAT + 2 * 2 * 2 * SUB;  // two buffers of (Q, dO) + two of (lse, delta) as floats
