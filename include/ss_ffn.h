@@ -21,7 +21,9 @@
  * helper stream of the library's own (one per device, default priority, created on first use) and
  * joins it back into the caller's stream with events before the call returns: to the caller the
  * call is ordered on its stream like any other.  SS_FFN_ONE_STREAM=1 in the environment keeps
- * everything on the caller's stream.  Error codes are those of ss_attn.h.
+ * everything on the caller's stream.  The helper stream is shared by all calls on a device: calls
+ * from several host threads, or on several streams of one device at once, must be serialised by
+ * the caller.  Error codes are those of ss_attn.h.
  */
 #ifndef SS_FFN_H
 #define SS_FFN_H
