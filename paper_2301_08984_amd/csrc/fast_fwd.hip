@@ -141,10 +141,11 @@ __global__ __launch_bounds__(64 * QW * NG) __attribute__((amdgpu_waves_per_eu(2,
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
           const uint2 u = bz[4 * kb + g];
-          sa[kb][4 * g + 0] = fmaf(sa[kb][4 * g + 0], c1, __uint_as_float(u.x << 16) * LOG2E);
-          sa[kb][4 * g + 1] = fmaf(sa[kb][4 * g + 1], c1, __uint_as_float(u.x & 0xffff0000u) * LOG2E);
-          sa[kb][4 * g + 2] = fmaf(sa[kb][4 * g + 2], c1, __uint_as_float(u.y << 16) * LOG2E);
-          sa[kb][4 * g + 3] = fmaf(sa[kb][4 * g + 3], c1, __uint_as_float(u.y & 0xffff0000u) * LOG2E);
+          // natural units here; the change to base 2 rides on the subtraction of the maximum below
+          sa[kb][4 * g + 0] = fmaf(sa[kb][4 * g + 0], p.scale, __uint_as_float(u.x << 16));
+          sa[kb][4 * g + 1] = fmaf(sa[kb][4 * g + 1], p.scale, __uint_as_float(u.x & 0xffff0000u));
+          sa[kb][4 * g + 2] = fmaf(sa[kb][4 * g + 2], p.scale, __uint_as_float(u.y << 16));
+          sa[kb][4 * g + 3] = fmaf(sa[kb][4 * g + 3], p.scale, __uint_as_float(u.y & 0xffff0000u));
         }
     }
     if (edge) {
@@ -162,7 +163,7 @@ __global__ __launch_bounds__(64 * QW * NG) __attribute__((amdgpu_waves_per_eu(2,
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
       for (int v = 0; v < 16; ++v) rmax = fmaxf(rmax, sa[kb][v]);
-    if (!BIAS) rmax *= c1;  // scale > 0 on this path
+    rmax *= BIAS ? LOG2E : c1;  // the running maximum is kept in base-2 units; scale > 0 on this path
     rmax = half_max(rmax);
     // the running maximum is raised only when exceeded by more than 2^8, so the O rescale is
     // skipped on most tiles; probabilities stay below 2^8, harmless in fp32/bf16 range
@@ -181,7 +182,7 @@ __global__ __launch_bounds__(64 * QW * NG) __attribute__((amdgpu_waves_per_eu(2,
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
-        sa[kb][v] = BIAS ? fast_exp2(sa[kb][v] - m) : fast_exp2(fmaf(sa[kb][v], c1, -m));
+        sa[kb][v] = fast_exp2(fmaf(sa[kb][v], BIAS ? LOG2E : c1, -m));
         lsum += sa[kb][v];
       }
     l += lsum;
