@@ -28,12 +28,14 @@ __global__ __launch_bounds__(64 * QW * NG) __attribute__((amdgpu_waves_per_eu(2,
   constexpr int LDK = D + 8, LDV = D + 16;  // row pads chosen for conflict-free b128 / transpose reads
   constexpr int CPR = D / 8, CPT = BN * CPR / NT;
   constexpr int TILE_ELEMS = BN * LDK + BN * LDV;
+  constexpr bool DBUF = D <= 64;  // two tile buffers per group where LDS is plentiful
+  constexpr int NBUF = DBUF ? 2 : 1;
   constexpr int MERGE_ELEMS = NT * (16 * DB + 2) * 2 * (NG - 1);  // in uint16 units
-  constexpr int LDS_ELEMS = NG * TILE_ELEMS > MERGE_ELEMS ? NG * TILE_ELEMS : MERGE_ELEMS;
+  constexpr int LDS_ELEMS = NG * NBUF * TILE_ELEMS > MERGE_ELEMS ? NG * NBUF * TILE_ELEMS : MERGE_ELEMS;
   __shared__ __attribute__((aligned(16))) uint16_t smem[LDS_ELEMS];
   const int tid = threadIdx.x % NT, grp = threadIdx.x / NT;
   const int lane = tid & 63, w = tid >> 6, r = lane & 31, hl = lane >> 5;
-  uint16_t* sK = smem + grp * TILE_ELEMS;
+  uint16_t* sK = smem + grp * NBUF * TILE_ELEMS;
   uint16_t* sV = sK + BN * LDK;
   const BlockId blk = xcd_block_id();
   const int h = p.h0 + blk.y, b = p.b0 + blk.z;
@@ -85,30 +87,8 @@ __global__ __launch_bounds__(64 * QW * NG) __attribute__((amdgpu_waves_per_eu(2,
     gload(grp);
     if (BIAS) bload(grp);
   }
-  const int nit = (ntiles + NG - 1) / NG;
-  for (int it = 0; it < nit; ++it) {
-    const int kt = it * NG + grp;
-    const int k0 = kt * BN;
-    __syncthreads();
-    uint2 bz[8];
-    if (BIAS) {
-#pragma unroll
-      for (int j = 0; j < 8; ++j) bz[j] = bzn[j];
-    }
-    if (kt < ntiles) {
-#pragma unroll
-      for (int c = 0; c < CPT; ++c) {
-        const int idx = tid + c * NT, row = idx / CPR, col = (idx % CPR) * 8;
-        *(u32x4*)(sK + row * LDK + col) = pk[c];
-        *(u32x4*)(sV + row * LDV + col) = pv[c];
-      }
-      if (kt + NG < ntiles) {
-        gload(kt + NG);
-        if (BIAS) bload(kt + NG);
-      }
-    }
-    __syncthreads();
-    if (kt >= wtiles) continue;
+  // one key tile: scores, online softmax, value product (tile in LDS at sK / sV, bias slice bz)
+  auto tile = [&](const uint16_t* sK, const uint16_t* sV, int k0, const uint2* bz) {
     f32x16 sa[2];
     {
       // operand reads run ahead of the matrix cores; the two score blocks alternate so that
@@ -215,6 +195,71 @@ __global__ __launch_bounds__(64 * QW * NG) __attribute__((amdgpu_waves_per_eu(2,
         __builtin_amdgcn_sched_group_barrier(0x100, 2, 1);
       }
       __builtin_amdgcn_sched_group_barrier(0x008, DB, 1);
+    }
+  
+  };
+  auto stage = [&](uint16_t* dK, uint16_t* dV) {
+#pragma unroll
+    for (int c = 0; c < CPT; ++c) {
+      const int idx = tid + c * NT, row = idx / CPR, col = (idx % CPR) * 8;
+      *(u32x4*)(dK + row * LDK + col) = pk[c];
+      *(u32x4*)(dV + row * LDV + col) = pv[c];
+    }
+  };
+  const int nit = (ntiles + NG - 1) / NG;
+  if (DBUF) {
+    // two tile buffers per group and one barrier per tile: while a tile is multiplied the next one
+    // is already in registers; it is written to the other buffer after the multiplication, which
+    // every wavefront finished reading before the previous barrier
+    uint2 bz[8];
+    if (grp < ntiles) {
+      stage(sK, sV);
+      if (BIAS) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) bz[j] = bzn[j];
+      }
+      if (grp + NG < ntiles) {
+        gload(grp + NG);
+        if (BIAS) bload(grp + NG);
+      }
+    }
+    __syncthreads();
+    for (int it = 0; it < nit; ++it) {
+      const int kt = it * NG + grp;
+      uint16_t* cK = sK + (it & 1) * TILE_ELEMS;
+      uint16_t* nK = sK + ((it + 1) & 1) * TILE_ELEMS;
+      if (kt < wtiles) tile(cK, cK + BN * LDK, kt * BN, bz);
+      if (kt + NG < ntiles) {
+        stage(nK, nK + BN * LDK);
+        if (BIAS) {
+#pragma unroll
+          for (int j = 0; j < 8; ++j) bz[j] = bzn[j];
+        }
+        if (kt + 2 * NG < ntiles) {
+          gload(kt + 2 * NG);
+          if (BIAS) bload(kt + 2 * NG);
+        }
+      }
+      __syncthreads();
+    }
+  } else {
+    for (int it = 0; it < nit; ++it) {
+      const int kt = it * NG + grp;
+      __syncthreads();
+      uint2 bz[8];
+      if (BIAS) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) bz[j] = bzn[j];
+      }
+      if (kt < ntiles) {
+        stage(sK, sV);
+        if (kt + NG < ntiles) {
+          gload(kt + NG);
+          if (BIAS) bload(kt + NG);
+        }
+      }
+      __syncthreads();
+      if (kt < wtiles) tile(sK, sV, kt * BN, bz);
     }
   }
   if (NG > 1) {
