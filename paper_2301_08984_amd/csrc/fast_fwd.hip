@@ -23,7 +23,7 @@ namespace {
 // not depend on k.
 // ---------------------------------------------------------------------------
 template <int D, bool BIAS, bool CAUSAL, bool RECOMP, int QW, int NG>
-__global__ __launch_bounds__(64 * QW * NG) __attribute__((amdgpu_waves_per_eu(2, 2))) void fwd_fast_kernel(KP p) {
+__global__ __launch_bounds__(64 * QW * NG) __attribute__((amdgpu_waves_per_eu(D <= 32 ? (BIAS ? 3 : 4) : 2, D <= 32 ? (BIAS ? 3 : 4) : 2))) void fwd_fast_kernel(KP p) {
   constexpr int KS = D / 16, DB = D / 32, NT = 64 * QW, BM = 32 * QW;
   constexpr int LDK = D + 8, LDV = D + 16;  // row pads chosen for conflict-free b128 / transpose reads
   constexpr int CPR = D / 8, CPT = BN * CPR / NT;
@@ -31,7 +31,11 @@ __global__ __launch_bounds__(64 * QW * NG) __attribute__((amdgpu_waves_per_eu(2,
   constexpr bool DBUF = D <= 64;  // two tile buffers per group where LDS is plentiful
   constexpr int NBUF = DBUF ? 2 : 1;
   constexpr int MERGE_ELEMS = NT * (16 * DB + 2) * 2 * (NG - 1);  // in uint16 units
-  constexpr int LDS_ELEMS = NG * NBUF * TILE_ELEMS > MERGE_ELEMS ? NG * NBUF * TILE_ELEMS : MERGE_ELEMS;
+  // bias tiles pass through a wavefront-private LDS area (32 query rows of 64 keys, rows padded to
+  // 136 bytes so that the 8-byte reads of 32 rows fall into distinct banks)
+  constexpr int LDB = 68, BIAS_ELEMS = BIAS ? 32 * LDB * QW * NG : 0;
+  constexpr int KV_ELEMS = NG * NBUF * TILE_ELEMS;
+  constexpr int LDS_ELEMS = KV_ELEMS + BIAS_ELEMS > MERGE_ELEMS ? KV_ELEMS + BIAS_ELEMS : MERGE_ELEMS;
   __shared__ __attribute__((aligned(16))) uint16_t smem[LDS_ELEMS];
   const int tid = threadIdx.x % NT, grp = threadIdx.x / NT;
   const int lane = tid & 63, w = tid >> 6, r = lane & 31, hl = lane >> 5;
@@ -46,7 +50,18 @@ __global__ __launch_bounds__(64 * QW * NG) __attribute__((amdgpu_waves_per_eu(2,
   const uint16_t* Qb = (const uint16_t*)p.Q + base;
   const uint16_t* Kb = (const uint16_t*)p.K + base;
   const uint16_t* Vb = (const uint16_t*)p.V + base;
-  const uint16_t* bias_row = BIAS ? (const uint16_t*)p.bias + ((int64_t)h * p.S + qc) * p.S : nullptr;
+  // Bias: a lane of the score tile owns one query and needs 4 consecutive keys at a time, so
+  // direct loads would touch 64 rows per instruction.  Instead 16 lanes fetch 128 contiguous bytes
+  // of one row (4 rows per instruction, 8 instructions per 32 x 64 tile), the tile is parked in
+  // LDS and read back in the layout of the accumulator.
+  const int brow0 = BIAS ? __builtin_amdgcn_readfirstlane(min(q0, p.S - 1)) : 0;
+  const uint16_t* bias_w = BIAS ? (const uint16_t*)p.bias + ((int64_t)h * p.S + brow0) * p.S : nullptr;
+  uint16_t* sB = smem + KV_ELEMS + (threadIdx.x >> 6) * (32 * LDB);
+  int boff[8];
+  if (BIAS) {
+#pragma unroll
+    for (int c = 0; c < 8; ++c) boff[c] = (min(q0 + (lane >> 4) + 4 * c, p.S - 1) - brow0) * p.S;
+  }
 
   bf16x8 qf[KS];
 #pragma unroll
@@ -77,19 +92,23 @@ __global__ __launch_bounds__(64 * QW * NG) __attribute__((amdgpu_waves_per_eu(2,
   // the bias slice of the next tile travels with the next K/V tile
   uint2 bzn[8];
   auto bload = [&](int kt) {
+    const int col = min(kt * BN + 4 * (lane & 15), p.S - 4);  // S is a multiple of 4 on this path
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
+    for (int c = 0; c < 8; ++c) bzn[c] = *(const uint2*)(bias_w + boff[c] + col);
+  };
+  // park the fetched bias tile in the wavefront's LDS area (read back by the next tile())
+  auto bpark = [&]() {
 #pragma unroll
-      for (int g = 0; g < 4; ++g)
-        bzn[4 * kb + g] = *(const uint2*)(bias_row + min(kt * BN + 32 * kb + 8 * g + 4 * hl, p.S - 4));
+    for (int c = 0; c < 8; ++c) *(uint2*)(sB + ((lane >> 4) + 4 * c) * LDB + 4 * (lane & 15)) = bzn[c];
   };
   if (grp < ntiles) {
     gload(grp);
     if (BIAS) bload(grp);
   }
   // one key tile: scores, online softmax, value product (tile in LDS at sK / sV, bias slice bz)
-  auto tile = [&](const uint16_t* sK, const uint16_t* sV, int k0, const uint2* bz) {
+  auto tile = [&](const uint16_t* sK, const uint16_t* sV, int k0) {
     f32x16 sa[2];
+    uint2 bz[8];
     {
       // operand reads run ahead of the matrix cores; the two score blocks alternate so that
       // consecutive MFMAs never wait on each other's accumulator
@@ -113,6 +132,12 @@ __global__ __launch_bounds__(64 * QW * NG) __attribute__((amdgpu_waves_per_eu(2,
         __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
       }
       __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+    }
+    if (BIAS) {
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) bz[4 * kb + g] = *(const uint2*)(sB + r * LDB + 32 * kb + 8 * g + 4 * hl);
     }
     const bool edge = (k0 + BN > p.S) || (CAUSAL && k0 + BN - 1 > q0);
     if (BIAS) {
@@ -211,13 +236,9 @@ __global__ __launch_bounds__(64 * QW * NG) __attribute__((amdgpu_waves_per_eu(2,
     // two tile buffers per group and one barrier per tile: while a tile is multiplied the next one
     // is already in registers; it is written to the other buffer after the multiplication, which
     // every wavefront finished reading before the previous barrier
-    uint2 bz[8];
     if (grp < ntiles) {
       stage(sK, sV);
-      if (BIAS) {
-#pragma unroll
-        for (int j = 0; j < 8; ++j) bz[j] = bzn[j];
-      }
+      if (BIAS) bpark();
       if (grp + NG < ntiles) {
         gload(grp + NG);
         if (BIAS) bload(grp + NG);
@@ -228,13 +249,10 @@ __global__ __launch_bounds__(64 * QW * NG) __attribute__((amdgpu_waves_per_eu(2,
       const int kt = it * NG + grp;
       uint16_t* cK = sK + (it & 1) * TILE_ELEMS;
       uint16_t* nK = sK + ((it + 1) & 1) * TILE_ELEMS;
-      if (kt < wtiles) tile(cK, cK + BN * LDK, kt * BN, bz);
+      if (kt < wtiles) tile(cK, cK + BN * LDK, kt * BN);
       if (kt + NG < ntiles) {
         stage(nK, nK + BN * LDK);
-        if (BIAS) {
-#pragma unroll
-          for (int j = 0; j < 8; ++j) bz[j] = bzn[j];
-        }
+        if (BIAS) bpark();
         if (kt + 2 * NG < ntiles) {
           gload(kt + 2 * NG);
           if (BIAS) bload(kt + 2 * NG);
@@ -246,20 +264,16 @@ __global__ __launch_bounds__(64 * QW * NG) __attribute__((amdgpu_waves_per_eu(2,
     for (int it = 0; it < nit; ++it) {
       const int kt = it * NG + grp;
       __syncthreads();
-      uint2 bz[8];
-      if (BIAS) {
-#pragma unroll
-        for (int j = 0; j < 8; ++j) bz[j] = bzn[j];
-      }
       if (kt < ntiles) {
         stage(sK, sV);
+        if (BIAS) bpark();
         if (kt + NG < ntiles) {
           gload(kt + NG);
           if (BIAS) bload(kt + NG);
         }
       }
       __syncthreads();
-      if (kt < wtiles) tile(sK, sV, kt * BN, bz);
+      if (kt < wtiles) tile(sK, sV, kt * BN);
     }
   }
   if (NG > 1) {
