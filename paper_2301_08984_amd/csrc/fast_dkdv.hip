@@ -16,13 +16,14 @@ namespace {
 // tile travels global -> registers meanwhile.
 // ---------------------------------------------------------------------------
 template <int D, bool BIAS, bool CAUSAL, int NW>
-__global__ __launch_bounds__(64 * NW) void dkdv_fast_kernel(KP p) {
+__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(D <= 32 ? 2 : 1, D <= 32 ? 2 : 1))) void dkdv_fast_kernel(KP p) {
   constexpr int KS = D / 16, DB = D / 32, LD = D + 24, NT = 64 * NW, BK = 32 * NW;  // tiles read both ways
   constexpr int CPR = D / 8, CPT = BN * CPR / NT;
   __shared__ __attribute__((aligned(16))) uint16_t sQ[2][BN * LD];
   __shared__ __attribute__((aligned(16))) uint16_t sG[2][BN * LD];
   __shared__ __attribute__((aligned(16))) float sL[2][BN];
   __shared__ __attribute__((aligned(16))) float sD[2][BN];
+  __shared__ __attribute__((aligned(16))) uint16_t sBias[BIAS ? NW * BIAS_TILE_ELEMS : 8];  // one parked tile per wavefront
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, r = lane & 31, hl = lane >> 5;
   const BlockId blk = xcd_block_id();
   const int h = p.h0 + blk.y, b = p.b0 + blk.z;
@@ -36,8 +37,11 @@ __global__ __launch_bounds__(64 * NW) void dkdv_fast_kernel(KP p) {
   const uint16_t* dOb = (const uint16_t*)p.dO + (int64_t)b * p.do_sb + (int64_t)h * p.do_sh;
   const float* lse_b = p.lse + (int64_t)b * p.lse_sb + (int64_t)h * p.lse_sh;
   const float* dl_b = p.delta + (int64_t)b * p.dl_sb + (int64_t)h * p.dl_sh;
-  // transposed bias copy: biasT[h][key][query], four consecutive queries per 8-byte load
-  const uint16_t* biasT_row = BIAS ? (const uint16_t*)p.biasT + ((int64_t)h * p.S + kc) * p.S : nullptr;
+  // bias comes from the transposed copy biasT[h][key][query], so that a lane (= key) finds four
+  // consecutive queries in 8 bytes
+  BiasTile bt;
+  if (BIAS) bt.init((const uint16_t*)p.biasT + (int64_t)h * p.S * p.S, k0, p.S, sBias + w * BIAS_TILE_ELEMS);
+  auto bload = [&](int qt) { bt.load(qt, lane); };
 
   bf16x8 kf[KS], vf[KS];
 #pragma unroll
@@ -146,12 +150,17 @@ __global__ __launch_bounds__(64 * NW) void dkdv_fast_kernel(KP p) {
     gload(first);
     lstore(first & 1);
     if (first + 1 < ntiles) gload(first + 1);
+    if (BIAS) bload(first);
   }
   for (int qt = first; qt < ntiles; ++qt) {
     const int i0 = qt * BN;
     __syncthreads();
     if (qt + 1 < ntiles) lstore((qt + 1) & 1);
     if (qt + 2 < ntiles) gload(qt + 2);
+    if (BIAS) {
+      bt.park(lane);
+      if (qt + 1 < ntiles) bload(qt + 1);
+    }
     if (k0 >= p.S || (CAUSAL && i0 + BN - 1 < k0)) continue;  // no visible pair for this wavefront
     const uint16_t* tq = sQ[qt & 1];
     const uint16_t* tg = sG[qt & 1];
@@ -163,7 +172,7 @@ __global__ __launch_bounds__(64 * NW) void dkdv_fast_kernel(KP p) {
     uint2 bz[8];
     if (BIAS) {
 #pragma unroll
-      for (int j = 0; j < 8; ++j) bz[j] = *(const uint2*)(biasT_row + min(i0 + 8 * j + 4 * hl, p.S - 4));
+      for (int j = 0; j < 8; ++j) bz[j] = bt.read(r, 8 * j + 4 * hl);
     }
     auto tile = [&](auto edge_tag) {
       // D = 128: keeps the 32 operand reads inside this block; they are common to both variants of

@@ -19,7 +19,9 @@ __global__ __launch_bounds__(64 * QW * NG) __attribute__((amdgpu_waves_per_eu(2,
   constexpr int CPR = D / 8, CPT = BN * CPR / NT;
   constexpr int TILE_ELEMS = BN * LDK + BN * LDV;
   constexpr int MERGE_ELEMS = NT * (16 * DB) * 2 * (NG - 1);
-  constexpr int LDS_ELEMS = NG * TILE_ELEMS > MERGE_ELEMS ? NG * TILE_ELEMS : MERGE_ELEMS;
+  constexpr int BIAS_ELEMS = BIAS ? BIAS_TILE_ELEMS * QW * NG : 0;  // one parked bias tile per wavefront
+  constexpr int KV_ELEMS = NG * TILE_ELEMS;
+  constexpr int LDS_ELEMS = KV_ELEMS + BIAS_ELEMS > MERGE_ELEMS ? KV_ELEMS + BIAS_ELEMS : MERGE_ELEMS;
   __shared__ __attribute__((aligned(16))) uint16_t smem[LDS_ELEMS];
   const int tid = threadIdx.x % NT, grp = threadIdx.x / NT;
   const int lane = tid & 63, w = tid >> 6, r = lane & 31, hl = lane >> 5;
@@ -35,7 +37,10 @@ __global__ __launch_bounds__(64 * QW * NG) __attribute__((amdgpu_waves_per_eu(2,
   const uint16_t* Kb = (const uint16_t*)p.K + base;
   const uint16_t* Vb = (const uint16_t*)p.V + base;
   const uint16_t* dOb = (const uint16_t*)p.dO + (int64_t)b * p.do_sb + (int64_t)h * p.do_sh;
-  const uint16_t* bias_row = BIAS ? (const uint16_t*)p.bias + ((int64_t)h * p.S + qc) * p.S : nullptr;
+  BiasTile bt;
+  if (BIAS)
+    bt.init((const uint16_t*)p.bias + (int64_t)h * p.S * p.S, q0, p.S,
+            smem + KV_ELEMS + (threadIdx.x >> 6) * BIAS_TILE_ELEMS);
 
   bf16x8 qf[KS], gf[KS];
 #pragma unroll
@@ -68,14 +73,7 @@ __global__ __launch_bounds__(64 * QW * NG) __attribute__((amdgpu_waves_per_eu(2,
     }
   };
   // the bias slice of the next tile travels with the next K/V tile
-  uint2 bzn[8];
-  auto bload = [&](int kt) {
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int g = 0; g < 4; ++g)
-        bzn[4 * kb + g] = *(const uint2*)(bias_row + min(kt * BN + 32 * kb + 8 * g + 4 * hl, p.S - 4));
-  };
+  auto bload = [&](int kt) { bt.load(kt, lane); };
   if (grp < ntiles) {
     gload(grp);
     if (BIAS) bload(grp);
@@ -85,12 +83,8 @@ __global__ __launch_bounds__(64 * QW * NG) __attribute__((amdgpu_waves_per_eu(2,
     const int kt = it * NG + grp;
     const int k0 = kt * BN;
     __syncthreads();
-    uint2 bzc[8];
-    if (BIAS) {
-#pragma unroll
-      for (int j = 0; j < 8; ++j) bzc[j] = bzn[j];
-    }
     if (kt < ntiles) {
+      if (BIAS) bt.park(lane);
 #pragma unroll
       for (int c = 0; c < CPT; ++c) {
         const int idx = tid + c * NT, row = idx / CPR, col = (idx % CPR) * 8;
@@ -108,10 +102,6 @@ __global__ __launch_bounds__(64 * QW * NG) __attribute__((amdgpu_waves_per_eu(2,
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb) {
       uint2 bz[4];
-      if (BIAS) {
-#pragma unroll
-        for (int g = 0; g < 4; ++g) bz[g] = bzc[4 * kb + g];
-      }
       f32x16 sa, pa;
       {
         bf16x8 fk[KS], fv[KS];
@@ -127,6 +117,10 @@ __global__ __launch_bounds__(64 * QW * NG) __attribute__((amdgpu_waves_per_eu(2,
           sa = mfma(fk[ks], qf[ks], sa);
           pa = mfma(fv[ks], gf[ks], pa);
         }
+      }
+      if (BIAS) {
+#pragma unroll
+        for (int g = 0; g < 4; ++g) bz[g] = bt.read(r, 32 * kb + 8 * g + 4 * hl);
       }
       float ds[16];
 #pragma unroll

@@ -31,9 +31,7 @@ __global__ __launch_bounds__(64 * QW * NG) __attribute__((amdgpu_waves_per_eu(D 
   constexpr bool DBUF = D <= 64;  // two tile buffers per group where LDS is plentiful
   constexpr int NBUF = DBUF ? 2 : 1;
   constexpr int MERGE_ELEMS = NT * (16 * DB + 2) * 2 * (NG - 1);  // in uint16 units
-  // bias tiles pass through a wavefront-private LDS area (32 query rows of 64 keys, rows padded to
-  // 136 bytes so that the 8-byte reads of 32 rows fall into distinct banks)
-  constexpr int LDB = 68, BIAS_ELEMS = BIAS ? 32 * LDB * QW * NG : 0;
+  constexpr int BIAS_ELEMS = BIAS ? BIAS_TILE_ELEMS * QW * NG : 0;  // one parked bias tile per wavefront
   constexpr int KV_ELEMS = NG * NBUF * TILE_ELEMS;
   constexpr int LDS_ELEMS = KV_ELEMS + BIAS_ELEMS > MERGE_ELEMS ? KV_ELEMS + BIAS_ELEMS : MERGE_ELEMS;
   __shared__ __attribute__((aligned(16))) uint16_t smem[LDS_ELEMS];
@@ -50,18 +48,10 @@ __global__ __launch_bounds__(64 * QW * NG) __attribute__((amdgpu_waves_per_eu(D 
   const uint16_t* Qb = (const uint16_t*)p.Q + base;
   const uint16_t* Kb = (const uint16_t*)p.K + base;
   const uint16_t* Vb = (const uint16_t*)p.V + base;
-  // Bias: a lane of the score tile owns one query and needs 4 consecutive keys at a time, so
-  // direct loads would touch 64 rows per instruction.  Instead 16 lanes fetch 128 contiguous bytes
-  // of one row (4 rows per instruction, 8 instructions per 32 x 64 tile), the tile is parked in
-  // LDS and read back in the layout of the accumulator.
-  const int brow0 = BIAS ? __builtin_amdgcn_readfirstlane(min(q0, p.S - 1)) : 0;
-  const uint16_t* bias_w = BIAS ? (const uint16_t*)p.bias + ((int64_t)h * p.S + brow0) * p.S : nullptr;
-  uint16_t* sB = smem + KV_ELEMS + (threadIdx.x >> 6) * (32 * LDB);
-  int boff[8];
-  if (BIAS) {
-#pragma unroll
-    for (int c = 0; c < 8; ++c) boff[c] = (min(q0 + (lane >> 4) + 4 * c, p.S - 1) - brow0) * p.S;
-  }
+  BiasTile bt;
+  if (BIAS)
+    bt.init((const uint16_t*)p.bias + (int64_t)h * p.S * p.S, q0, p.S,
+            smem + KV_ELEMS + (threadIdx.x >> 6) * BIAS_TILE_ELEMS);
 
   bf16x8 qf[KS];
 #pragma unroll
@@ -90,17 +80,8 @@ __global__ __launch_bounds__(64 * QW * NG) __attribute__((amdgpu_waves_per_eu(D 
     }
   };
   // the bias slice of the next tile travels with the next K/V tile
-  uint2 bzn[8];
-  auto bload = [&](int kt) {
-    const int col = min(kt * BN + 4 * (lane & 15), p.S - 4);  // S is a multiple of 4 on this path
-#pragma unroll
-    for (int c = 0; c < 8; ++c) bzn[c] = *(const uint2*)(bias_w + boff[c] + col);
-  };
-  // park the fetched bias tile in the wavefront's LDS area (read back by the next tile())
-  auto bpark = [&]() {
-#pragma unroll
-    for (int c = 0; c < 8; ++c) *(uint2*)(sB + ((lane >> 4) + 4 * c) * LDB + 4 * (lane & 15)) = bzn[c];
-  };
+  auto bload = [&](int kt) { bt.load(kt, lane); };
+  auto bpark = [&]() { bt.park(lane); };  // read back by the next tile()
   if (grp < ntiles) {
     gload(grp);
     if (BIAS) bload(grp);
@@ -137,7 +118,7 @@ __global__ __launch_bounds__(64 * QW * NG) __attribute__((amdgpu_waves_per_eu(D 
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-        for (int g = 0; g < 4; ++g) bz[4 * kb + g] = *(const uint2*)(sB + r * LDB + 32 * kb + 8 * g + 4 * hl);
+        for (int g = 0; g < 4; ++g) bz[4 * kb + g] = bt.read(r, 32 * kb + 8 * g + 4 * hl);
     }
     const bool edge = (k0 + BN > p.S) || (CAUSAL && k0 + BN - 1 > q0);
     if (BIAS) {

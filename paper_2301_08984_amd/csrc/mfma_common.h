@@ -95,6 +95,39 @@ __device__ inline BlockId xcd_block_id() {
   return b;
 }
 
+// Dense bias tile of one wavefront: 32 rows (queries, or keys of the transposed copy) by 64 columns.
+// A lane of the score tile owns one row and needs 4 consecutive columns at a time, so direct loads
+// would touch 64 rows per instruction.  Instead 16 lanes fetch 128 contiguous bytes of one row (4
+// rows per instruction, 8 instructions per tile, issued one tile ahead), the tile is parked in a
+// wavefront-private LDS area and read back in the layout of the accumulator.  LDS rows are padded to
+// 136 bytes so that the 8-byte reads of 32 rows fall into distinct banks.  Rows past S are replaced
+// by in-bounds addresses (their scores are masked or never stored); S is a multiple of 4.
+constexpr int BIAS_LD = 68, BIAS_TILE_ELEMS = 32 * BIAS_LD;
+struct BiasTile {
+  const uint16_t* base;  // first row of the wavefront (uniform)
+  uint16_t* lds;         // the wavefront's area, BIAS_TILE_ELEMS elements
+  int S, lim;            // lim: largest offset that keeps an 8-byte load inside the head's matrix
+  uint2 nxt[8];
+  __device__ void init(const uint16_t* head, int row0, int S_, uint16_t* area) {
+    S = S_;
+    const int first = __builtin_amdgcn_readfirstlane(min(row0, S - 1));
+    base = head + (int64_t)first * S;
+    lim = (S - 1 - first) * S + S - 4;
+    lds = area;
+  }
+  __device__ void load(int tile, int lane) {
+    const int off = (lane >> 4) * S + min(tile * 64 + 4 * (lane & 15), S - 4);
+#pragma unroll
+    for (int c = 0; c < 8; ++c) nxt[c] = *(const uint2*)(base + min(off + 4 * c * S, lim));
+  }
+  __device__ void park(int lane) {
+#pragma unroll
+    for (int c = 0; c < 8; ++c) *(uint2*)(lds + ((lane >> 4) + 4 * c) * BIAS_LD + 4 * (lane & 15)) = nxt[c];
+  }
+  // columns col .. col + 3 (col a multiple of 4) of row r of the parked tile
+  __device__ uint2 read(int r, int col) const { return *(const uint2*)(lds + r * BIAS_LD + col); }
+};
+
 __device__ inline int key_of(int v, int hl) { return 8 * (v >> 2) + 4 * hl + (v & 3); }
 
 // forward epilogue: normalise, gate, store Y (and LSE); recompute mode: gate gradient,
