@@ -348,12 +348,15 @@ __global__ __launch_bounds__(256) void dbias_fast_kernel(KP p) {
 // group, and the groups are summed in index order afterwards, so the result never depends
 // on k.  With a single group the sum continues directly in the output.
 // ---------------------------------------------------------------------------
+// At D = 32 four work-groups fill a compute unit exactly (4 x 40 KB of LDS, 128 registers per lane),
+// which is also what a 1024 x 1024 head needs for all its tiles to be resident at once; the per-row
+// statistics therefore live in the padding of the Q tile's rows instead of arrays of their own.
 template <int D, bool CAUSAL>
-__global__ __launch_bounds__(256) void dbias_tile_kernel(KP p) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D <= 32 ? 4 : 1, D <= 32 ? 4 : (D <= 64 ? 2 : 1))))
+void dbias_tile_kernel(KP p) {
   constexpr int KS = D / 16, LD = D + 8, CPR = D / 8;
   constexpr int CPT = 64 * CPR / 256;  // 16-byte chunks per thread per tensor tile
   __shared__ __attribute__((aligned(16))) uint16_t sT[2][4][64 * LD];  // Q, dO, K, V
-  __shared__ float sL[2][64], sD[2][64];
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, r = lane & 31, hl = lane >> 5;
   const int Hc = p.h1 - p.h0;
   const int h = p.h0 + (int)blockIdx.z % Hc;
@@ -413,8 +416,9 @@ __global__ __launch_bounds__(256) void dbias_tile_kernel(KP p) {
 #pragma unroll
         for (int t = 0; t < 4; ++t) *(u32x4*)(&sT[buf][t][row * LD + col]) = pre[t][c];
       }
-      if (tid < 64) sL[buf][tid] = pstat * LOG2E;
-      else if (tid < 128) sD[buf][tid - 64] = pstat;
+      // LSE (base 2) and Delta of query i: the two floats after the D elements of row i of the Q tile
+      if (tid < 64) *(float*)(&sT[buf][0][tid * LD + D]) = pstat * LOG2E;
+      else if (tid < 128) *(float*)(&sT[buf][0][(tid - 64) * LD + D + 2]) = pstat;
     };
     gload(bfirst);
     lstore(bfirst & 1);
@@ -432,7 +436,8 @@ __global__ __launch_bounds__(256) void dbias_tile_kernel(KP p) {
         sa = mfma(lds_nat<LD>(sT[buf][2], 32 * wk + r, ks, hl), lds_nat<LD>(sT[buf][0], 32 * wq + r, ks, hl), sa);
         pa = mfma(lds_nat<LD>(sT[buf][3], 32 * wk + r, ks, hl), lds_nat<LD>(sT[buf][1], 32 * wq + r, ks, hl), pa);
       }
-      const float lse2 = sL[buf][32 * wq + r], dlt = sD[buf][32 * wq + r];
+      const float2 st2 = *(const float2*)(&sT[buf][0][(32 * wq + r) * LD + D]);
+      const float lse2 = st2.x, dlt = st2.y;
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
         const float e = fast_exp2(fmaf(sa[v], c1, bz[v] - lse2));
