@@ -359,8 +359,11 @@ void dbias_tile_kernel(KP p) {
   __shared__ __attribute__((aligned(16))) uint16_t sT[2][4][64 * LD];  // Q, dO, K, V
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, r = lane & 31, hl = lane >> 5;
   const int Hc = p.h1 - p.h0;
-  const int h = p.h0 + (int)blockIdx.z % Hc;
-  const int q0t = blockIdx.y * 64, k0t = blockIdx.x * 64;
+  // consecutive tiles (same head, neighbouring query tiles, all key tiles) run on one XCD, so a
+  // row's Q/dO/K/V slices are fetched into few L2s instead of all eight
+  const BlockId blk = xcd_block_id();
+  const int h = p.h0 + blk.z % Hc;
+  const int q0t = blk.y * 64, k0t = blk.x * 64;
   const int wq = w >> 1, wk = w & 1;
   const int q0 = q0t + 32 * wq, k0 = k0t + 32 * wk;
   const int q = q0 + r, qc = min(q, p.S - 1);
@@ -369,7 +372,7 @@ void dbias_tile_kernel(KP p) {
   float* dst;
   bool resume;
   if (p.sm_partial) {
-    const int g = p.b0 / p.sm_gw + (int)blockIdx.z / Hc;
+    const int g = p.b0 / p.sm_gw + blk.z / Hc;
     bfirst = max(g * p.sm_gw, p.b0);
     blast = min((g + 1) * p.sm_gw, p.b1);
     dst = p.sm_partial + ((int64_t)(g - p.sm_g0) * p.H + h) * p.S * p.S + (int64_t)qc * p.S;
