@@ -26,6 +26,10 @@ constexpr int SLD = SD + 8;   // LDS row stride of the per-wave tiles (elements)
 constexpr int BLD = 68;       // LDS row stride of the bias tile (elements)
 constexpr int FWD_ROWS_PER_WAVE = 8;
 
+struct WaveLdsFwd {
+  uint16_t t0[64 * SLD];  // V
+  int rid[64];
+};
 struct WaveLds {
   uint16_t t0[64 * SLD];  // forward: V ; backward: K
   uint16_t t1[64 * SLD];  // backward: dO
@@ -84,10 +88,11 @@ __device__ inline void wave_lds_sync() {
 }
 
 // scores of query block qb against both key blocks, lane = query: x = s*c1 + bias*log2e, masked -> -inf
+template <bool REGION>
 __device__ inline void scores_by_query(const KP& p, const bf16x8 (&kf)[2][2], const bf16x8 (&qf)[2][2], int qb,
                                        const uint16_t* bias_tile, const int* rid, int q, int hl, float c1,
                                        float (&x)[2][16]) {
-  const int my_rid = p.mask_kind == 2 ? rid[q] : 0;
+  const int my_rid = REGION ? rid[q] : 0;
 #pragma unroll
   for (int kb = 0; kb < 2; ++kb) {
     f32x16 sa;
@@ -102,12 +107,12 @@ __device__ inline void scores_by_query(const KP& p, const bf16x8 (&kf)[2][2], co
       const float bl[4] = {__uint_as_float(u.x << 16), __uint_as_float(u.x & 0xffff0000u),
                            __uint_as_float(u.y << 16), __uint_as_float(u.y & 0xffff0000u)};
       int4 rk = {0, 0, 0, 0};
-      if (p.mask_kind == 2) rk = *(const int4*)(rid + kbase);
+      if (REGION) rk = *(const int4*)(rid + kbase);
       const int rks[4] = {rk.x, rk.y, rk.z, rk.w};
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
         float t = fmaf(sa[4 * g + e], c1, bl[e] * LOG2E);
-        if (p.mask_kind == 2) t = rks[e] != my_rid ? -INFINITY : t;
+        if (REGION) t = rks[e] != my_rid ? -INFINITY : t;
         x[kb][4 * g + e] = t;
       }
     }
@@ -115,33 +120,51 @@ __device__ inline void scores_by_query(const KP& p, const bf16x8 (&kf)[2][2], co
 }
 
 // ---------------------------------------------------------------------------
-// forward: grid (ceil(rows/32), heads); each wavefront takes 8 consecutive rows
+// forward: each wavefront takes 8 consecutive rows of one head.  A work-group covers HPW
+// neighbouring heads (wavefront w: head w % HPW, row block w / HPW): the heads of one row sit side
+// by side in memory, 64 bytes each, so wavefronts that run together then read whole cache lines
+// and DRAM pages between them instead of one 64-byte piece per line.
+// grid (ceil(rows / (8 * 4 / HPW)), heads / HPW)
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void small_fwd_kernel(KP p) {
-  __shared__ __attribute__((aligned(16))) uint16_t bias_tile[64 * BLD];
-  __shared__ __attribute__((aligned(16))) WaveLds wl[4];
+template <bool REGION, int HPW>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void small_fwd_kernel(KP p) {
+  __shared__ __attribute__((aligned(16))) uint16_t bias_tiles[HPW][64 * BLD];
+  __shared__ __attribute__((aligned(16))) WaveLdsFwd wl[4];
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, r = lane & 31, hl = lane >> 5;
-  const int h = p.h0 + blockIdx.y;
-  build_bias_tile(p, h, bias_tile, tid, 256);
+  const int h = p.h0 + blockIdx.y * HPW + w % HPW;
+#pragma unroll
+  for (int i = 0; i < HPW; ++i) build_bias_tile(p, p.h0 + blockIdx.y * HPW + i, bias_tiles[i], tid, 256);
   __syncthreads();
-  WaveLds& L = wl[w];
+  const uint16_t* bias_tile = bias_tiles[w % HPW];
+  WaveLdsFwd& L = wl[w];
   const float c1 = p.scale * LOG2E;
-  const int bfirst = p.b0 + (blockIdx.x * 4 + w) * FWD_ROWS_PER_WAVE;
+  const int bfirst = p.b0 + (blockIdx.x * (4 / HPW) + w / HPW) * FWD_ROWS_PER_WAVE;
   const int blast = min(bfirst + FWD_ROWS_PER_WAVE, p.b1);
+  // the operands of row b + 1 are fetched while row b is computed
+  bf16x8 qn[2][2], kn[2][2], vn[2][2];
+  auto fetch = [&](int b) {
+    const int64_t base = (int64_t)b * p.sb + (int64_t)h * p.sh;
+    load_nat((const uint16_t*)p.Q + base, p.ss, p.S, r, hl, qn);
+    load_nat((const uint16_t*)p.K + base, p.ss, p.S, r, hl, kn);
+    load_nat((const uint16_t*)p.V + base, p.ss, p.S, r, hl, vn);
+  };
+  if (bfirst < blast) fetch(bfirst);
   for (int b = bfirst; b < blast; ++b) {
     const int64_t base = (int64_t)b * p.sb + (int64_t)h * p.sh;
     bf16x8 qf[2][2], kf[2][2], vf[2][2];
-    load_nat((const uint16_t*)p.Q + base, p.ss, p.S, r, hl, qf);
-    load_nat((const uint16_t*)p.K + base, p.ss, p.S, r, hl, kf);
-    load_nat((const uint16_t*)p.V + base, p.ss, p.S, r, hl, vf);
-    if (p.mask_kind == 2) L.rid[lane] = p.region[(int64_t)(b % p.mask_period) * p.S + min(lane, p.S - 1)];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j) { qf[i][j] = qn[i][j]; kf[i][j] = kn[i][j]; vf[i][j] = vn[i][j]; }
+    fetch(min(b + 1, blast - 1));
+    if (REGION) L.rid[lane] = p.region[(int64_t)(b % p.mask_period) * p.S + min(lane, p.S - 1)];
     store_tile(L.t0, r, hl, vf);
     wave_lds_sync();
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
       const int q = 32 * qb + r;
       float x[2][16];
-      scores_by_query(p, kf, qf, qb, bias_tile, L.rid, q, hl, c1, x);
+      scores_by_query<REGION>(p, kf, qf, qb, bias_tile, L.rid, q, hl, c1, x);
       float m = -1e30f;
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
@@ -173,6 +196,7 @@ __global__ __launch_bounds__(256) void small_fwd_kernel(KP p) {
 // ---------------------------------------------------------------------------
 // backward: grid (ceil(groups/4), heads); each wavefront takes one group of rows
 // ---------------------------------------------------------------------------
+template <bool REGION>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void small_bwd_kernel(KP p) {
   __shared__ __attribute__((aligned(16))) uint16_t bias_tile[64 * BLD];
   __shared__ __attribute__((aligned(16))) WaveLds wl[4];
@@ -216,7 +240,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
       store_tile(L.t2, r, hl, tmp);
     }
     load_nat((const uint16_t*)p.V + base, p.ss, p.S, r, hl, vf);
-    if (p.mask_kind == 2) L.rid[lane] = p.region[(int64_t)(b % p.mask_period) * p.S + min(lane, p.S - 1)];
+    if (REGION) L.rid[lane] = p.region[(int64_t)(b % p.mask_period) * p.S + min(lane, p.S - 1)];
     wave_lds_sync();
     // ---- pass 1, lane = query: exact softmax, Delta, dQ
 #pragma unroll
@@ -233,7 +257,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
           qf[qb][ks] = tile_nat(L.t2, qb, ks, r, hl);
           gq_[ks] = tile_nat(L.t1, qb, ks, r, hl);
         }
-        scores_by_query(p, kf, qf, qb, bias_tile, L.rid, q, hl, c1, x);
+        scores_by_query<REGION>(p, kf, qf, qb, bias_tile, L.rid, q, hl, c1, x);
       }
       float m = -1e30f;
 #pragma unroll
@@ -300,7 +324,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb) {
       const int key = 32 * kb + r;
-      const int my_rid = p.mask_kind == 2 ? L.rid[key] : 0;
+      const int my_rid = REGION ? L.rid[key] : 0;
       f32x16 dk, dv;
 #pragma unroll
       for (int v = 0; v < 16; ++v) { dk[v] = 0.f; dv[v] = 0.f; }
@@ -322,13 +346,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
           const f32x4 l4 = *(const f32x4*)(L.lse2 + qbase);
           const f32x4 d4 = *(const f32x4*)(L.delta + qbase);
           int4 rq = {0, 0, 0, 0};
-          if (p.mask_kind == 2) rq = *(const int4*)(L.rid + qbase);
+          if (REGION) rq = *(const int4*)(L.rid + qbase);
           const int rqs[4] = {rq.x, rq.y, rq.z, rq.w};
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
             const float bl = bf2f(bias_tile[(qbase + e) * BLD + key]) * LOG2E;
             float t = fmaf(sa[4 * gq + e], c1, bl) - l4[e];
-            if (p.mask_kind == 2) t = rqs[e] != my_rid ? -INFINITY : t;
+            if (REGION) t = rqs[e] != my_rid ? -INFINITY : t;
             const float pe = fast_exp2(t);
             pr[4 * gq + e] = pe;
             ds[4 * gq + e] = pe * (pa[4 * gq + e] - d4[e]);
@@ -406,15 +430,30 @@ bool small_supported(const KP& p, bool bf16) {
 
 hipError_t launch_small_fwd(const KP& p, hipStream_t st) {
   const int rows = p.b1 - p.b0;
-  dim3 g((rows + 4 * FWD_ROWS_PER_WAVE - 1) / (4 * FWD_ROWS_PER_WAVE), p.h1 - p.h0);
-  small_fwd_kernel<<<g, 256, 0, st>>>(p);
+  const int heads = p.h1 - p.h0;
+  // heads per work-group; the order of the arithmetic of a (row, head) does not depend on it
+  const int hpw = heads % 4 == 0 ? 4 : heads % 2 == 0 ? 2 : 1;
+  const int rpw = (4 / hpw) * FWD_ROWS_PER_WAVE;
+  dim3 g((rows + rpw - 1) / rpw, heads / hpw);
+  const bool region = p.mask_kind == 2;
+  if (hpw == 4) {
+    if (region) small_fwd_kernel<true, 4><<<g, 256, 0, st>>>(p);
+    else small_fwd_kernel<false, 4><<<g, 256, 0, st>>>(p);
+  } else if (hpw == 2) {
+    if (region) small_fwd_kernel<true, 2><<<g, 256, 0, st>>>(p);
+    else small_fwd_kernel<false, 2><<<g, 256, 0, st>>>(p);
+  } else {
+    if (region) small_fwd_kernel<true, 1><<<g, 256, 0, st>>>(p);
+    else small_fwd_kernel<false, 1><<<g, 256, 0, st>>>(p);
+  }
   return hipGetLastError();
 }
 
 hipError_t launch_small_bwd(const KP& p, hipStream_t st) {
   const int ng = (p.b1 - 1) / p.sm_gw - p.b0 / p.sm_gw + 1;
   dim3 g((ng + 3) / 4, p.h1 - p.h0);
-  small_bwd_kernel<<<g, 256, 0, st>>>(p);
+  if (p.mask_kind == 2) small_bwd_kernel<true><<<g, 256, 0, st>>>(p);
+  else small_bwd_kernel<false><<<g, 256, 0, st>>>(p);
   return hipGetLastError();
 }
 

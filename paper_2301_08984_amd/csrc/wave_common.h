@@ -97,7 +97,7 @@ __device__ inline float fwd_epilogue_block(const KP& p, const f32x16& o16, int d
     if (!RECOMP) {
       if (p.gated) {
 #pragma unroll
-        for (int e = 0; e < 4; ++e) o[e] *= 1.f / (1.f + fast_exp2(-gl[e] * LOG2E));
+        for (int e = 0; e < 4; ++e) o[e] *= fast_rcp(1.f + fast_exp2(-gl[e] * LOG2E));
       }
       uint2 out;
       out.x = (uint32_t)f2bf(o[0]) | ((uint32_t)f2bf(o[1]) << 16);
@@ -111,7 +111,7 @@ __device__ inline float fwd_epilogue_block(const KP& p, const f32x16& o16, int d
         uint16_t dg[4], dor[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          const float gt = 1.f / (1.f + fast_exp2(-gl[e] * LOG2E));
+          const float gt = fast_rcp(1.f + fast_exp2(-gl[e] * LOG2E));
           dg[e] = f2bf(go[e] * o[e] * gt * (1.f - gt));
           dor[e] = f2bf(go[e] * gt);
           go[e] = bf2f(dor[e]);  // the later kernels read the rounded copy
