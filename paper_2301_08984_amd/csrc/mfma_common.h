@@ -42,6 +42,19 @@ __device__ inline float half_sum(float x) {
   auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
   return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
+// Stores one row of 32 bf16 columns held as "lane = row, group g = columns 8g + 4*hl .. +3" (the
+// layout of a 32x32 accumulator block, packed to 8 bytes per group): the two half-waves exchange
+// pieces so that every lane writes 16 contiguous bytes twice (columns 8*(2j + hl) .. +7) instead of
+// 8 bytes four times, which halves the cache-line lookups of the store.  All 64 lanes must call it;
+// `live` masks the stores only.
+__device__ inline void store_row32(uint16_t* row_ptr, const uint2 (&a)[4], int hl, bool live) {
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    auto s = __builtin_amdgcn_permlane32_swap(a[2 * j].x, a[2 * j + 1].x, false, false);
+    auto t = __builtin_amdgcn_permlane32_swap(a[2 * j].y, a[2 * j + 1].y, false, false);
+    if (live) *(u32x4*)(row_ptr + 8 * (2 * j + hl)) = u32x4{s[0], t[0], s[1], t[1]};
+  }
+}
 __device__ inline f32x16 mfma(bf16x8 a, bf16x8 b, f32x16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }

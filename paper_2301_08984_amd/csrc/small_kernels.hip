@@ -26,14 +26,10 @@ constexpr int SLD = SD + 8;   // LDS row stride of the per-wave tiles (elements)
 constexpr int BLD = 68;       // LDS row stride of the bias tile (elements)
 constexpr int FWD_ROWS_PER_WAVE = 8;
 
-struct WaveLdsFwd {
-  uint16_t t0[64 * SLD];  // V
-  int rid[64];
-};
 struct WaveLds {
   uint16_t t0[64 * SLD];  // forward: V ; backward: K
-  uint16_t t1[64 * SLD];  // backward: dO
-  uint16_t t2[64 * SLD];  // backward: Q
+  uint16_t t1[64 * SLD];  // forward: K ; backward: dO
+  uint16_t t2[64 * SLD];  // Q (forward: then the output block)
   float lse2[64];
   float delta[64];
   int rid[64];
@@ -69,6 +65,20 @@ __device__ inline void load_nat(const uint16_t* base, int64_t row_stride, int S,
 #pragma unroll
     for (int ks = 0; ks < 2; ++ks) f[blk][ks] = *(const bf16x8*)(base + (int64_t)row * row_stride + 16 * ks + 8 * hl);
   }
+}
+// a [<=64 x 32] activation slice in whole row segments: lane l takes the 16-byte chunk l % 4 of rows
+// l / 4 + 16 c (rows past S - 1 repeat the last row; their scores are masked by the bias tile)
+__device__ inline void load_rows(const uint16_t* base, int64_t row_stride, int S, int lane, u32x4 (&f)[4]) {
+#pragma unroll
+  for (int c = 0; c < 4; ++c) {
+    const int row = min((lane >> 2) + 16 * c, S - 1);
+    f[c] = *(const u32x4*)(base + (int64_t)row * row_stride + 8 * (lane & 3));
+  }
+}
+// ... into a per-wave LDS tile
+__device__ inline void store_rows(uint16_t* t, int lane, const u32x4 (&f)[4]) {
+#pragma unroll
+  for (int c = 0; c < 4; ++c) *(u32x4*)(t + ((lane >> 2) + 16 * c) * SLD + 8 * (lane & 3)) = f[c];
 }
 // natural-layout fragment of rows 32*blk.. of a per-wave LDS tile
 __device__ inline bf16x8 tile_nat(const uint16_t* t, int blk, int ks, int r, int hl) {
@@ -120,46 +130,51 @@ __device__ inline void scores_by_query(const KP& p, const bf16x8 (&kf)[2][2], co
 }
 
 // ---------------------------------------------------------------------------
-// forward: each wavefront takes 8 consecutive rows of one head.  A work-group covers HPW
-// neighbouring heads (wavefront w: head w % HPW, row block w / HPW): the heads of one row sit side
-// by side in memory, 64 bytes each, so wavefronts that run together then read whole cache lines
-// and DRAM pages between them instead of one 64-byte piece per line.
-// grid (ceil(rows / (8 * 4 / HPW)), heads / HPW)
+// forward: grid (ceil(rows/32), heads); each wavefront takes 8 consecutive rows of one head.
+// Global memory is touched only in whole 64-byte row segments (four lanes per segment, 16 rows per
+// instruction): the operands pass through the wavefront's LDS tiles on their way into operand
+// layout, and the output block goes back through a tile on its way out.  Loading in operand layout
+// (one lane = one row, 16 bytes) costs four cache-line lookups per four lanes instead of one, and the
+// short-sequence kernels are bound by exactly that.
 // ---------------------------------------------------------------------------
-template <bool REGION, int HPW>
+template <bool REGION>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void small_fwd_kernel(KP p) {
-  __shared__ __attribute__((aligned(16))) uint16_t bias_tiles[HPW][64 * BLD];
-  __shared__ __attribute__((aligned(16))) WaveLdsFwd wl[4];
+  __shared__ __attribute__((aligned(16))) uint16_t bias_tile[64 * BLD];
+  __shared__ __attribute__((aligned(16))) WaveLds wl[4];
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, r = lane & 31, hl = lane >> 5;
-  const int h = p.h0 + blockIdx.y * HPW + w % HPW;
-#pragma unroll
-  for (int i = 0; i < HPW; ++i) build_bias_tile(p, p.h0 + blockIdx.y * HPW + i, bias_tiles[i], tid, 256);
+  const int h = p.h0 + blockIdx.y;
+  build_bias_tile(p, h, bias_tile, tid, 256);
   __syncthreads();
-  const uint16_t* bias_tile = bias_tiles[w % HPW];
-  WaveLdsFwd& L = wl[w];
+  WaveLds& L = wl[w];
   const float c1 = p.scale * LOG2E;
-  const int bfirst = p.b0 + (blockIdx.x * (4 / HPW) + w / HPW) * FWD_ROWS_PER_WAVE;
+  const int bfirst = p.b0 + (blockIdx.x * 4 + w) * FWD_ROWS_PER_WAVE;
   const int blast = min(bfirst + FWD_ROWS_PER_WAVE, p.b1);
   // the operands of row b + 1 are fetched while row b is computed
-  bf16x8 qn[2][2], kn[2][2], vn[2][2];
+  u32x4 qn[4], kn[4], vn[4];
   auto fetch = [&](int b) {
     const int64_t base = (int64_t)b * p.sb + (int64_t)h * p.sh;
-    load_nat((const uint16_t*)p.Q + base, p.ss, p.S, r, hl, qn);
-    load_nat((const uint16_t*)p.K + base, p.ss, p.S, r, hl, kn);
-    load_nat((const uint16_t*)p.V + base, p.ss, p.S, r, hl, vn);
+    load_rows((const uint16_t*)p.Q + base, p.ss, p.S, lane, qn);
+    load_rows((const uint16_t*)p.K + base, p.ss, p.S, lane, kn);
+    load_rows((const uint16_t*)p.V + base, p.ss, p.S, lane, vn);
   };
   if (bfirst < blast) fetch(bfirst);
   for (int b = bfirst; b < blast; ++b) {
     const int64_t base = (int64_t)b * p.sb + (int64_t)h * p.sh;
-    bf16x8 qf[2][2], kf[2][2], vf[2][2];
-#pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-      for (int j = 0; j < 2; ++j) { qf[i][j] = qn[i][j]; kf[i][j] = kn[i][j]; vf[i][j] = vn[i][j]; }
+    store_rows(L.t2, lane, qn);
+    store_rows(L.t1, lane, kn);
+    store_rows(L.t0, lane, vn);
     fetch(min(b + 1, blast - 1));
     if (REGION) L.rid[lane] = p.region[(int64_t)(b % p.mask_period) * p.S + min(lane, p.S - 1)];
-    store_tile(L.t0, r, hl, vf);
     wave_lds_sync();
+    bf16x8 qf[2][2], kf[2][2];
+#pragma unroll
+    for (int blk = 0; blk < 2; ++blk)
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks) {
+        qf[blk][ks] = tile_nat(L.t2, blk, ks, r, hl);
+        kf[blk][ks] = tile_nat(L.t1, blk, ks, r, hl);
+      }
+    wave_lds_sync();  // the Q tile is reused for the output below
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
       const int q = 32 * qb + r;
@@ -179,17 +194,39 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
           x[kb][v] = fast_exp2(x[kb][v] - m);
           l += x[kb][v];
         }
-      f32x16 oacc[1];
+      f32x16 oacc;
 #pragma unroll
-      for (int v = 0; v < 16; ++v) oacc[0][v] = 0.f;
+      for (int v = 0; v < 16; ++v) oacc[v] = 0.f;
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
         for (int hb = 0; hb < 2; ++hb)
-          oacc[0] = mfma(lds_tr<SLD>(L.t0, 32 * kb + 16 * hb, 0, lane), pack8(&x[kb][8 * hb]), oacc[0]);
-      if (q < p.S) fwd_epilogue<1, false>(p, oacc, m, l, b, h, q, hl, base);
+          oacc = mfma(lds_tr<SLD>(L.t0, 32 * kb + 16 * hb, 0, lane), pack8(&x[kb][8 * hb]), oacc);
+      // normalise; the block's output row goes to the (consumed) Q tile, LSE straight to memory
+      l = half_sum(l);
+      const float inv = 1.f / l;
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        uint2 o;
+        o.x = (uint32_t)f2bf(oacc[4 * g] * inv) | ((uint32_t)f2bf(oacc[4 * g + 1] * inv) << 16);
+        o.y = (uint32_t)f2bf(oacc[4 * g + 2] * inv) | ((uint32_t)f2bf(oacc[4 * g + 3] * inv) << 16);
+        *(uint2*)(L.t2 + q * SLD + 8 * g + 4 * hl) = o;
+      }
+      if (q < p.S && hl == 0 && p.lse_out)
+        p.lse_out[(int64_t)b * p.lse_sb + (int64_t)h * p.lse_sh + q] = (m + log2f(l)) * LN2;
     }
-    wave_lds_sync();  // the next row's tile stores must not overtake this row's transpose reads
+    wave_lds_sync();
+    // Y rows leave as whole 64-byte segments
+    {
+      uint16_t* Yb = (uint16_t*)p.Y + base;
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const int row = (lane >> 2) + 16 * c;
+        const u32x4 o = *(const u32x4*)(L.t2 + row * SLD + 8 * (lane & 3));
+        if (row < p.S) *(u32x4*)(Yb + (int64_t)row * p.ss + 8 * (lane & 3)) = o;
+      }
+    }
+    wave_lds_sync();  // the next row's tile stores must not overtake this row's reads
   }
 }
 
@@ -228,18 +265,19 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   }
   for (int b = bfirst; b < blast; ++b) {
     const int64_t base = (int64_t)b * p.sb + (int64_t)h * p.sh;
-    // K, dO and Q go to this wavefront's LDS tiles (read back both ways); V stays in registers
+    // K, dO and Q go to this wavefront's LDS tiles (read back both ways), fetched in whole 64-byte
+    // row segments; V stays in registers, in operand layout
     bf16x8 vf[2][2];
     {
-      bf16x8 tmp[2][2];
-      load_nat((const uint16_t*)p.K + base, p.ss, p.S, r, hl, tmp);
-      store_tile(L.t0, r, hl, tmp);
-      load_nat((const uint16_t*)p.dO + (int64_t)b * p.do_sb + (int64_t)h * p.do_sh, p.do_ss, p.S, r, hl, tmp);
-      store_tile(L.t1, r, hl, tmp);
-      load_nat((const uint16_t*)p.Q + base, p.ss, p.S, r, hl, tmp);
-      store_tile(L.t2, r, hl, tmp);
+      u32x4 tk[4], tg[4], tq[4];
+      load_rows((const uint16_t*)p.K + base, p.ss, p.S, lane, tk);
+      load_rows((const uint16_t*)p.dO + (int64_t)b * p.do_sb + (int64_t)h * p.do_sh, p.do_ss, p.S, lane, tg);
+      load_rows((const uint16_t*)p.Q + base, p.ss, p.S, lane, tq);
+      load_nat((const uint16_t*)p.V + base, p.ss, p.S, r, hl, vf);
+      store_rows(L.t0, lane, tk);
+      store_rows(L.t1, lane, tg);
+      store_rows(L.t2, lane, tq);
     }
-    load_nat((const uint16_t*)p.V + base, p.ss, p.S, r, hl, vf);
     if (REGION) L.rid[lane] = p.region[(int64_t)(b % p.mask_period) * p.S + min(lane, p.S - 1)];
     wave_lds_sync();
     // ---- pass 1, lane = query: exact softmax, Delta, dQ
@@ -308,15 +346,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
         for (int hb = 0; hb < 2; ++hb)
           dq = mfma(lds_tr<SLD>(L.t0, 32 * kb + 16 * hb, 0, lane), pack8(&x[kb][8 * hb]), dq);
       }
-      if (q < p.S) {
-        uint16_t* out = (uint16_t*)p.dQ + base + (int64_t)q * p.ss;
+      {
+        uint2 o[4];
 #pragma unroll
         for (int gq = 0; gq < 4; ++gq) {
-          uint2 o;
-          o.x = (uint32_t)f2bf(dq[4 * gq] * p.scale) | ((uint32_t)f2bf(dq[4 * gq + 1] * p.scale) << 16);
-          o.y = (uint32_t)f2bf(dq[4 * gq + 2] * p.scale) | ((uint32_t)f2bf(dq[4 * gq + 3] * p.scale) << 16);
-          *(uint2*)(out + 8 * gq + 4 * hl) = o;
+          o[gq].x = (uint32_t)f2bf(dq[4 * gq] * p.scale) | ((uint32_t)f2bf(dq[4 * gq + 1] * p.scale) << 16);
+          o[gq].y = (uint32_t)f2bf(dq[4 * gq + 2] * p.scale) | ((uint32_t)f2bf(dq[4 * gq + 3] * p.scale) << 16);
         }
+        store_row32((uint16_t*)p.dQ + base + (int64_t)min(q, p.S - 1) * p.ss, o, hl, q < p.S);
       }
     }
     wave_lds_sync();  // LSE / Delta written by half of the lanes, read by all
@@ -368,19 +405,18 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
           dk = mfma(lds_tr<SLD>(L.t2, 32 * qb + 16 * hb, 0, lane), pack8(&ds[8 * hb]), dk);
         }
       }
-      if (key < p.S) {
-        uint16_t* oK = (uint16_t*)p.dK + base + (int64_t)key * p.ss;
-        uint16_t* oV = (uint16_t*)p.dV + base + (int64_t)key * p.ss;
+      {
+        uint2 a[4], c[4];
 #pragma unroll
         for (int gd = 0; gd < 4; ++gd) {
-          uint2 a, c;
-          a.x = (uint32_t)f2bf(dk[4 * gd] * p.scale) | ((uint32_t)f2bf(dk[4 * gd + 1] * p.scale) << 16);
-          a.y = (uint32_t)f2bf(dk[4 * gd + 2] * p.scale) | ((uint32_t)f2bf(dk[4 * gd + 3] * p.scale) << 16);
-          c.x = (uint32_t)f2bf(dv[4 * gd]) | ((uint32_t)f2bf(dv[4 * gd + 1]) << 16);
-          c.y = (uint32_t)f2bf(dv[4 * gd + 2]) | ((uint32_t)f2bf(dv[4 * gd + 3]) << 16);
-          *(uint2*)(oK + 8 * gd + 4 * hl) = a;
-          *(uint2*)(oV + 8 * gd + 4 * hl) = c;
+          a[gd].x = (uint32_t)f2bf(dk[4 * gd] * p.scale) | ((uint32_t)f2bf(dk[4 * gd + 1] * p.scale) << 16);
+          a[gd].y = (uint32_t)f2bf(dk[4 * gd + 2] * p.scale) | ((uint32_t)f2bf(dk[4 * gd + 3] * p.scale) << 16);
+          c[gd].x = (uint32_t)f2bf(dv[4 * gd]) | ((uint32_t)f2bf(dv[4 * gd + 1]) << 16);
+          c[gd].y = (uint32_t)f2bf(dv[4 * gd + 2]) | ((uint32_t)f2bf(dv[4 * gd + 3]) << 16);
         }
+        const int64_t krow = base + (int64_t)min(key, p.S - 1) * p.ss;
+        store_row32((uint16_t*)p.dK + krow, a, hl, key < p.S);
+        store_row32((uint16_t*)p.dV + krow, c, hl, key < p.S);
       }
     }
     wave_lds_sync();  // next row's tile stores after this row's reads
@@ -430,22 +466,9 @@ bool small_supported(const KP& p, bool bf16) {
 
 hipError_t launch_small_fwd(const KP& p, hipStream_t st) {
   const int rows = p.b1 - p.b0;
-  const int heads = p.h1 - p.h0;
-  // heads per work-group; the order of the arithmetic of a (row, head) does not depend on it
-  const int hpw = heads % 4 == 0 ? 4 : heads % 2 == 0 ? 2 : 1;
-  const int rpw = (4 / hpw) * FWD_ROWS_PER_WAVE;
-  dim3 g((rows + rpw - 1) / rpw, heads / hpw);
-  const bool region = p.mask_kind == 2;
-  if (hpw == 4) {
-    if (region) small_fwd_kernel<true, 4><<<g, 256, 0, st>>>(p);
-    else small_fwd_kernel<false, 4><<<g, 256, 0, st>>>(p);
-  } else if (hpw == 2) {
-    if (region) small_fwd_kernel<true, 2><<<g, 256, 0, st>>>(p);
-    else small_fwd_kernel<false, 2><<<g, 256, 0, st>>>(p);
-  } else {
-    if (region) small_fwd_kernel<true, 1><<<g, 256, 0, st>>>(p);
-    else small_fwd_kernel<false, 1><<<g, 256, 0, st>>>(p);
-  }
+  dim3 g((rows + 4 * FWD_ROWS_PER_WAVE - 1) / (4 * FWD_ROWS_PER_WAVE), p.h1 - p.h0);
+  if (p.mask_kind == 2) small_fwd_kernel<true><<<g, 256, 0, st>>>(p);
+  else small_fwd_kernel<false><<<g, 256, 0, st>>>(p);
   return hipGetLastError();
 }
 
