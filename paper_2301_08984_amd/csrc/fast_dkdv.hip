@@ -223,18 +223,16 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(D <= 32
   uint16_t* oK = (uint16_t*)p.dK + base + (int64_t)key * p.ss;
   uint16_t* oV = (uint16_t*)p.dV + base + (int64_t)key * p.ss;
 #pragma unroll
-  for (int db = 0; db < DB; ++db)
+  for (int db = 0; db < DB; ++db) {
+    uint2 a[4], c[4];
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
-      const int d0 = 32 * db + 8 * g + 4 * hl;
-      uint2 a, c;
-      a.x = (uint32_t)f2bf(dk[db][4 * g] * p.scale) | ((uint32_t)f2bf(dk[db][4 * g + 1] * p.scale) << 16);
-      a.y = (uint32_t)f2bf(dk[db][4 * g + 2] * p.scale) | ((uint32_t)f2bf(dk[db][4 * g + 3] * p.scale) << 16);
-      c.x = (uint32_t)f2bf(dv[db][4 * g]) | ((uint32_t)f2bf(dv[db][4 * g + 1]) << 16);
-      c.y = (uint32_t)f2bf(dv[db][4 * g + 2]) | ((uint32_t)f2bf(dv[db][4 * g + 3]) << 16);
-      *(uint2*)(oK + d0) = a;
-      *(uint2*)(oV + d0) = c;
+      a[g] = pack4_bf16(dk[db][4 * g], dk[db][4 * g + 1], dk[db][4 * g + 2], dk[db][4 * g + 3], p.scale);
+      c[g] = pack4_bf16(dv[db][4 * g], dv[db][4 * g + 1], dv[db][4 * g + 2], dv[db][4 * g + 3], 1.f);
     }
+    store_row32(oK + 32 * db, a, hl, true);
+    store_row32(oV + 32 * db, c, hl, true);
+  }
 }
 
 // ---------------------------------------------------------------------------

@@ -176,15 +176,13 @@ __global__ __launch_bounds__(64 * QW * NG) __attribute__((amdgpu_waves_per_eu(2,
   if (q >= p.S) return;
   uint16_t* out = (uint16_t*)p.dQ + base + (int64_t)q * p.ss;
 #pragma unroll
-  for (int db = 0; db < DB; ++db)
+  for (int db = 0; db < DB; ++db) {
+    uint2 o[4];
 #pragma unroll
-    for (int g = 0; g < 4; ++g) {
-      const int d0 = 32 * db + 8 * g + 4 * hl;
-      uint2 o;
-      o.x = (uint32_t)f2bf(acc[db][4 * g] * p.scale) | ((uint32_t)f2bf(acc[db][4 * g + 1] * p.scale) << 16);
-      o.y = (uint32_t)f2bf(acc[db][4 * g + 2] * p.scale) | ((uint32_t)f2bf(acc[db][4 * g + 3] * p.scale) << 16);
-      *(uint2*)(out + d0) = o;
-    }
+    for (int g = 0; g < 4; ++g)
+      o[g] = pack4_bf16(acc[db][4 * g], acc[db][4 * g + 1], acc[db][4 * g + 2], acc[db][4 * g + 3], p.scale);
+    store_row32(out + 32 * db, o, hl, true);
+  }
 }
 
 template <int D, int QW, int NG>

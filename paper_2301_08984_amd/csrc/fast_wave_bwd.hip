@@ -174,12 +174,9 @@ __device__ __forceinline__ void dq_wave_block(const KP& p, uint16_t* smem, int r
     }
   }
 
-  auto store_q = [&](int db, int g, const f32x4& x) {
-    const int d0 = 32 * db + 8 * g + 4 * hl;
-    uint2 o;
-    o.x = (uint32_t)f2bf(x[0] * p.scale) | ((uint32_t)f2bf(x[1] * p.scale) << 16);
-    o.y = (uint32_t)f2bf(x[2] * p.scale) | ((uint32_t)f2bf(x[3] * p.scale) << 16);
-    *(uint2*)((uint16_t*)p.dQ + base + (int64_t)q * p.ss + d0) = o;
+  // one 32-column block of the row, 16 bytes per lane and store (both lanes of a row are active)
+  auto store_q = [&](int db, const uint2 (&o)[4]) {
+    store_row32((uint16_t*)p.dQ + base + (int64_t)q * p.ss + 32 * db, o, hl, true);
   };
   if (NG > 1) {
     // every wavefront hands over its partial sums through LDS; wavefront w then folds and stores
@@ -195,7 +192,8 @@ __device__ __forceinline__ void dq_wave_block(const KP& p, uint16_t* smem, int r
         my[(4 * db + g) * 64] = f32x4{acc[db][4 * g], acc[db][4 * g + 1], acc[db][4 * g + 2], acc[db][4 * g + 3]};
     __syncthreads();
     if (q >= p.S) return;
-    for (int db = grp; db < DB; db += NG)
+    for (int db = grp; db < DB; db += NG) {
+      uint2 o[4];
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         f32x4 x[NG];
@@ -205,16 +203,21 @@ __device__ __forceinline__ void dq_wave_block(const KP& p, uint16_t* smem, int r
         for (int st = NG / 2; st >= 1; st >>= 1)
 #pragma unroll
           for (int w = 0; w < st; ++w) x[w] += x[w + st];
-        store_q(db, g, x[0]);
+        o[g] = pack4_bf16(x[0][0], x[0][1], x[0][2], x[0][3], p.scale);
       }
+      store_q(db, o);
+    }
     return;
   }
   if (q >= p.S) return;
 #pragma unroll
-  for (int db = 0; db < DB; ++db)
+  for (int db = 0; db < DB; ++db) {
+    uint2 o[4];
 #pragma unroll
     for (int g = 0; g < 4; ++g)
-      store_q(db, g, f32x4{acc[db][4 * g], acc[db][4 * g + 1], acc[db][4 * g + 2], acc[db][4 * g + 3]});
+      o[g] = pack4_bf16(acc[db][4 * g], acc[db][4 * g + 1], acc[db][4 * g + 2], acc[db][4 * g + 3], p.scale);
+    store_q(db, o);
+  }
 }
 
 // ---------------------------------------------------------------------------
@@ -410,15 +413,10 @@ __device__ __forceinline__ void dkdv_wave_block(const KP& p, uint16_t* smem, int
     }
   }
 
-  auto store_kv = [&](int db, int g, const f32x4& k4, const f32x4& v4) {
-    const int d0 = 32 * db + 8 * g + 4 * hl;
-    uint2 a, c;
-    a.x = (uint32_t)f2bf(k4[0] * p.scale) | ((uint32_t)f2bf(k4[1] * p.scale) << 16);
-    a.y = (uint32_t)f2bf(k4[2] * p.scale) | ((uint32_t)f2bf(k4[3] * p.scale) << 16);
-    c.x = (uint32_t)f2bf(v4[0]) | ((uint32_t)f2bf(v4[1]) << 16);
-    c.y = (uint32_t)f2bf(v4[2]) | ((uint32_t)f2bf(v4[3]) << 16);
-    *(uint2*)((uint16_t*)p.dK + base + (int64_t)key * p.ss + d0) = a;
-    *(uint2*)((uint16_t*)p.dV + base + (int64_t)key * p.ss + d0) = c;
+  // one 32-column block of the row, 16 bytes per lane and store (both lanes of a row are active)
+  auto store_kv = [&](int db, const uint2 (&a)[4], const uint2 (&c)[4]) {
+    store_row32((uint16_t*)p.dK + base + (int64_t)key * p.ss + 32 * db, a, hl, true);
+    store_row32((uint16_t*)p.dV + base + (int64_t)key * p.ss + 32 * db, c, hl, true);
   };
   if (QG > 1) {
     // every wavefront hands over its partial sums through LDS; wavefront w then folds and stores
@@ -437,7 +435,8 @@ __device__ __forceinline__ void dkdv_wave_block(const KP& p, uint16_t* smem, int
       }
     __syncthreads();
     if (key >= p.S) return;
-    for (int db = grp; db < DB; db += QG)
+    for (int db = grp; db < DB; db += QG) {
+      uint2 a[4], c[4];
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         f32x4 xk[QG], xv[QG];
@@ -450,17 +449,24 @@ __device__ __forceinline__ void dkdv_wave_block(const KP& p, uint16_t* smem, int
         for (int st = QG / 2; st >= 1; st >>= 1)
 #pragma unroll
           for (int w = 0; w < st; ++w) { xk[w] += xk[w + st]; xv[w] += xv[w + st]; }
-        store_kv(db, g, xk[0], xv[0]);
+        a[g] = pack4_bf16(xk[0][0], xk[0][1], xk[0][2], xk[0][3], p.scale);
+        c[g] = pack4_bf16(xv[0][0], xv[0][1], xv[0][2], xv[0][3], 1.f);
       }
+      store_kv(db, a, c);
+    }
     return;
   }
   if (key >= p.S) return;
 #pragma unroll
-  for (int db = 0; db < DB; ++db)
+  for (int db = 0; db < DB; ++db) {
+    uint2 a[4], c[4];
 #pragma unroll
-    for (int g = 0; g < 4; ++g)
-      store_kv(db, g, f32x4{dk[db][4 * g], dk[db][4 * g + 1], dk[db][4 * g + 2], dk[db][4 * g + 3]},
-               f32x4{dv[db][4 * g], dv[db][4 * g + 1], dv[db][4 * g + 2], dv[db][4 * g + 3]});
+    for (int g = 0; g < 4; ++g) {
+      a[g] = pack4_bf16(dk[db][4 * g], dk[db][4 * g + 1], dk[db][4 * g + 2], dk[db][4 * g + 3], p.scale);
+      c[g] = pack4_bf16(dv[db][4 * g], dv[db][4 * g + 1], dv[db][4 * g + 2], dv[db][4 * g + 3], 1.f);
+    }
+    store_kv(db, a, c);
+  }
 }
 
 // ---------------------------------------------------------------------------

@@ -244,7 +244,7 @@ __global__ __launch_bounds__(64 * NG) __attribute__((amdgpu_waves_per_eu(2, 2)))
 #pragma unroll
         for (int e = 0; e < 4; ++e) o[4 * g + e] = x[0][e];
       }
-      if (q < p.S) part += fwd_epilogue_block<RECOMP>(p, o, db, inv, b, h, q, hl, base);
+      if (q < p.S) part += fwd_epilogue_block<RECOMP>(p, o, db, inv, b, h, q, hl, base, 0.f);
     }
     const float lse = (m + log2f(l)) * LN2;
     if (!RECOMP) {

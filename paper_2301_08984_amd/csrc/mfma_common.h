@@ -45,14 +45,34 @@ __device__ inline float half_sum(float x) {
 // Stores one row of 32 bf16 columns held as "lane = row, group g = columns 8g + 4*hl .. +3" (the
 // layout of a 32x32 accumulator block, packed to 8 bytes per group): the two half-waves exchange
 // pieces so that every lane writes 16 contiguous bytes twice (columns 8*(2j + hl) .. +7) instead of
-// 8 bytes four times, which halves the cache-line lookups of the store.  All 64 lanes must call it;
-// `live` masks the stores only.
+// 8 bytes four times, which halves the cache-line lookups of the store.  Both lanes of a row (l and
+// l + 32) must be active; `live` masks the stores only.
 __device__ inline void store_row32(uint16_t* row_ptr, const uint2 (&a)[4], int hl, bool live) {
 #pragma unroll
   for (int j = 0; j < 2; ++j) {
     auto s = __builtin_amdgcn_permlane32_swap(a[2 * j].x, a[2 * j + 1].x, false, false);
     auto t = __builtin_amdgcn_permlane32_swap(a[2 * j].y, a[2 * j + 1].y, false, false);
     if (live) *(u32x4*)(row_ptr + 8 * (2 * j + hl)) = u32x4{s[0], t[0], s[1], t[1]};
+  }
+}
+// four scaled values as packed bf16
+__device__ inline uint2 pack4_bf16(float a, float b, float c, float d, float s) {
+  uint2 o;
+  o.x = (uint32_t)f2bf(a * s) | ((uint32_t)f2bf(b * s) << 16);
+  o.y = (uint32_t)f2bf(c * s) | ((uint32_t)f2bf(d * s) << 16);
+  return o;
+}
+// The matching load: every lane fetches 16 contiguous bytes twice and the half-waves exchange pieces,
+// so that a[g] ends up holding columns 8g + 4*hl .. +3 of the lane's row.  Both lanes of a row (l and
+// l + 32) must be active.
+__device__ inline void load_row32(const uint16_t* row_ptr, uint2 (&a)[4], int hl) {
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const u32x4 v = *(const u32x4*)(row_ptr + 8 * (2 * j + hl));
+    auto s = __builtin_amdgcn_permlane32_swap(v[0], v[2], false, false);
+    auto t = __builtin_amdgcn_permlane32_swap(v[1], v[3], false, false);
+    a[2 * j].x = s[0]; a[2 * j].y = t[0];
+    a[2 * j + 1].x = s[1]; a[2 * j + 1].y = t[1];
   }
 }
 __device__ inline f32x16 mfma(bf16x8 a, bf16x8 b, f32x16 c) {
@@ -146,6 +166,75 @@ struct BiasTile {
 
 __device__ inline int key_of(int v, int hl) { return 8 * (v >> 2) + 4 * hl + (v & 3); }
 
+// Forward epilogue for one 32-column block `db` of a query's output (lane = query, registers =
+// columns 8g + 4*hl + e, not yet normalised): normalise by `inv`, gate, store Y; recompute
+// mode: gate gradient and pre-gated dO copy, and `part` continues this lane's part of
+// Delta = rowsum(dO * O).  Rows are read and written 16 bytes per lane (load_row32 / store_row32).
+// Both lanes of the row must be active.
+template <bool RECOMP>
+__device__ inline float fwd_epilogue_block(const KP& p, const f32x16& o16, int db, float inv, int b, int h, int q, int hl,
+                                           int64_t base, float part) {
+  const int64_t row = base + (int64_t)q * p.ss + 32 * db;
+  float o[16], gt[16];
+#pragma unroll
+  for (int v = 0; v < 16; ++v) o[v] = o16[v] * inv;
+  if (p.gated) {
+    uint2 gu[4];
+    load_row32((const uint16_t*)p.G + row, gu, hl);
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const float gl[4] = {__uint_as_float(gu[g].x << 16), __uint_as_float(gu[g].x & 0xffff0000u),
+                           __uint_as_float(gu[g].y << 16), __uint_as_float(gu[g].y & 0xffff0000u)};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) gt[4 * g + e] = fast_rcp(1.f + fast_exp2(-gl[e] * LOG2E));
+    }
+  }
+  if (!RECOMP) {
+    if (p.gated) {
+#pragma unroll
+      for (int v = 0; v < 16; ++v) o[v] *= gt[v];
+    }
+    uint2 out[4];
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      out[g].x = (uint32_t)f2bf(o[4 * g]) | ((uint32_t)f2bf(o[4 * g + 1]) << 16);
+      out[g].y = (uint32_t)f2bf(o[4 * g + 2]) | ((uint32_t)f2bf(o[4 * g + 3]) << 16);
+    }
+    store_row32((uint16_t*)p.Y + row, out, hl, true);
+  } else {
+    uint2 du[4];
+    load_row32((const uint16_t*)p.dY + row, du, hl);
+    float go[16];
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      go[4 * g] = __uint_as_float(du[g].x << 16); go[4 * g + 1] = __uint_as_float(du[g].x & 0xffff0000u);
+      go[4 * g + 2] = __uint_as_float(du[g].y << 16); go[4 * g + 3] = __uint_as_float(du[g].y & 0xffff0000u);
+    }
+    if (p.gated) {
+      uint2 o1[4], o2[4];
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        uint16_t dg[4], dor[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int v = 4 * g + e;
+          dg[e] = f2bf(go[v] * o[v] * gt[v] * (1.f - gt[v]));
+          dor[e] = f2bf(go[v] * gt[v]);
+          go[v] = bf2f(dor[e]);  // the later kernels read the rounded copy
+        }
+        o1[g].x = (uint32_t)dg[0] | ((uint32_t)dg[1] << 16); o1[g].y = (uint32_t)dg[2] | ((uint32_t)dg[3] << 16);
+        o2[g].x = (uint32_t)dor[0] | ((uint32_t)dor[1] << 16); o2[g].y = (uint32_t)dor[2] | ((uint32_t)dor[3] << 16);
+      }
+      store_row32((uint16_t*)p.dG + row, o1, hl, true);
+      store_row32((uint16_t*)p.dO_out + (int64_t)b * p.do_sb + (int64_t)q * p.do_ss + (int64_t)h * p.do_sh + 32 * db, o2, hl,
+                  true);
+    }
+#pragma unroll
+    for (int v = 0; v < 16; ++v) part = fmaf(go[v], o[v], part);
+  }
+  return part;
+}
+
 // forward epilogue: normalise, gate, store Y (and LSE); recompute mode: gate gradient,
 // pre-gated dO copy, Delta = rowsum(dO*O) and LSE into the workspace
 template <int DB, bool RECOMP>
@@ -155,69 +244,12 @@ __device__ inline void fwd_epilogue(const KP& p, f32x16 (&oacc)[DB], float m, fl
   l = half_sum(l);
   const float inv = 1.f / l;
   const float lse = (m + log2f(l)) * LN2;
-  const int64_t row = base + (int64_t)q * p.ss;
+  float part = 0.f;
+#pragma unroll
+  for (int db = 0; db < DB; ++db) part = fwd_epilogue_block<RECOMP>(p, oacc[db], db, inv, b, h, q, hl, base, part);
   if (!RECOMP) {
-    uint16_t* Yr = (uint16_t*)p.Y + row;
-    const uint16_t* Gr = (const uint16_t*)p.G + row;
-#pragma unroll
-    for (int db = 0; db < DB; ++db)
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const int d0 = 32 * db + 8 * g + 4 * hl;
-        float o[4];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) o[e] = oacc[db][4 * g + e] * inv;
-        if (p.gated) {
-          const uint2 gu = *(const uint2*)(Gr + d0);
-          const float gl[4] = {__uint_as_float(gu.x << 16), __uint_as_float(gu.x & 0xffff0000u),
-                               __uint_as_float(gu.y << 16), __uint_as_float(gu.y & 0xffff0000u)};
-#pragma unroll
-          for (int e = 0; e < 4; ++e) o[e] *= fast_rcp(1.f + fast_exp2(-gl[e] * LOG2E));
-        }
-        uint2 out;
-        out.x = (uint32_t)f2bf(o[0]) | ((uint32_t)f2bf(o[1]) << 16);
-        out.y = (uint32_t)f2bf(o[2]) | ((uint32_t)f2bf(o[3]) << 16);
-        *(uint2*)(Yr + d0) = out;
-      }
     if (p.lse_out && hl == 0) p.lse_out[(int64_t)b * p.lse_sb + (int64_t)h * p.lse_sh + q] = lse;
   } else {
-    const uint16_t* dYr = (const uint16_t*)p.dY + row;
-    const uint16_t* Gr = (const uint16_t*)p.G + row;
-    uint16_t* dGr = (uint16_t*)p.dG + row;
-    uint16_t* dOr = (uint16_t*)p.dO_out + (int64_t)b * p.do_sb + (int64_t)q * p.do_ss + (int64_t)h * p.do_sh;
-    float part = 0.f;
-#pragma unroll
-    for (int db = 0; db < DB; ++db)
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const int d0 = 32 * db + 8 * g + 4 * hl;
-        const uint2 du = *(const uint2*)(dYr + d0);
-        float go[4] = {__uint_as_float(du.x << 16), __uint_as_float(du.x & 0xffff0000u),
-                       __uint_as_float(du.y << 16), __uint_as_float(du.y & 0xffff0000u)};
-        float o[4];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) o[e] = oacc[db][4 * g + e] * inv;
-        if (p.gated) {
-          const uint2 gu = *(const uint2*)(Gr + d0);
-          const float gl[4] = {__uint_as_float(gu.x << 16), __uint_as_float(gu.x & 0xffff0000u),
-                               __uint_as_float(gu.y << 16), __uint_as_float(gu.y & 0xffff0000u)};
-          uint16_t dg[4], dor[4];
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const float gt = fast_rcp(1.f + fast_exp2(-gl[e] * LOG2E));
-            dg[e] = f2bf(go[e] * o[e] * gt * (1.f - gt));
-            dor[e] = f2bf(go[e] * gt);
-            go[e] = bf2f(dor[e]);  // the later kernels read the rounded copy
-          }
-          uint2 o1, o2;
-          o1.x = (uint32_t)dg[0] | ((uint32_t)dg[1] << 16); o1.y = (uint32_t)dg[2] | ((uint32_t)dg[3] << 16);
-          o2.x = (uint32_t)dor[0] | ((uint32_t)dor[1] << 16); o2.y = (uint32_t)dor[2] | ((uint32_t)dor[3] << 16);
-          *(uint2*)(dGr + d0) = o1;
-          *(uint2*)(dOr + d0) = o2;
-        }
-#pragma unroll
-        for (int e = 0; e < 4; ++e) part = fmaf(go[e], o[e], part);
-      }
     part = half_sum(part);
     if (hl == 0) {
       p.delta[(int64_t)b * p.dl_sb + (int64_t)h * p.dl_sh + q] = part;

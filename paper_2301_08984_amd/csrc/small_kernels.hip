@@ -266,14 +266,23 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   for (int b = bfirst; b < blast; ++b) {
     const int64_t base = (int64_t)b * p.sb + (int64_t)h * p.sh;
     // K, dO and Q go to this wavefront's LDS tiles (read back both ways), fetched in whole 64-byte
-    // row segments; V stays in registers, in operand layout
+    // row segments; V ends up in registers, in operand layout
     bf16x8 vf[2][2];
     {
       u32x4 tk[4], tg[4], tq[4];
       load_rows((const uint16_t*)p.K + base, p.ss, p.S, lane, tk);
       load_rows((const uint16_t*)p.dO + (int64_t)b * p.do_sb + (int64_t)h * p.do_sh, p.do_ss, p.S, lane, tg);
       load_rows((const uint16_t*)p.Q + base, p.ss, p.S, lane, tq);
-      load_nat((const uint16_t*)p.V + base, p.ss, p.S, r, hl, vf);
+      u32x4 tv[4];
+      load_rows((const uint16_t*)p.V + base, p.ss, p.S, lane, tv);
+      // V passes through the Q tile on its way into operand layout
+      store_rows(L.t2, lane, tv);
+      wave_lds_sync();
+#pragma unroll
+      for (int blk = 0; blk < 2; ++blk)
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) vf[blk][ks] = tile_nat(L.t2, blk, ks, r, hl);
+      wave_lds_sync();
       store_rows(L.t0, lane, tk);
       store_rows(L.t1, lane, tg);
       store_rows(L.t2, lane, tq);

@@ -73,61 +73,6 @@ __device__ inline void sub_store(uint16_t* t, const u32x4 (&src)[D / 16], int la
   }
 }
 
-// Forward epilogue for one 32-column block `db` of a 32-query block whose (already folded) output is
-// in `o` (lane = query, registers = columns): normalise by `inv`, gate, store Y; recompute mode:
-// gate gradient and pre-gated dO copy, and the return value is this lane's part of
-// Delta = rowsum(dO * O) over its columns of the block.
-template <bool RECOMP>
-__device__ inline float fwd_epilogue_block(const KP& p, const f32x16& o16, int db, float inv, int b, int h, int q, int hl,
-                                           int64_t base) {
-  const int64_t row = base + (int64_t)q * p.ss;
-  float part = 0.f;
-#pragma unroll
-  for (int g = 0; g < 4; ++g) {
-    const int d0 = 32 * db + 8 * g + 4 * hl;
-    float o[4];
-#pragma unroll
-    for (int e = 0; e < 4; ++e) o[e] = o16[4 * g + e] * inv;
-    float gl[4] = {0.f, 0.f, 0.f, 0.f};
-    if (p.gated) {
-      const uint2 gu = *(const uint2*)((const uint16_t*)p.G + row + d0);
-      gl[0] = __uint_as_float(gu.x << 16); gl[1] = __uint_as_float(gu.x & 0xffff0000u);
-      gl[2] = __uint_as_float(gu.y << 16); gl[3] = __uint_as_float(gu.y & 0xffff0000u);
-    }
-    if (!RECOMP) {
-      if (p.gated) {
-#pragma unroll
-        for (int e = 0; e < 4; ++e) o[e] *= fast_rcp(1.f + fast_exp2(-gl[e] * LOG2E));
-      }
-      uint2 out;
-      out.x = (uint32_t)f2bf(o[0]) | ((uint32_t)f2bf(o[1]) << 16);
-      out.y = (uint32_t)f2bf(o[2]) | ((uint32_t)f2bf(o[3]) << 16);
-      *(uint2*)((uint16_t*)p.Y + row + d0) = out;
-    } else {
-      const uint2 du = *(const uint2*)((const uint16_t*)p.dY + row + d0);
-      float go[4] = {__uint_as_float(du.x << 16), __uint_as_float(du.x & 0xffff0000u), __uint_as_float(du.y << 16),
-                     __uint_as_float(du.y & 0xffff0000u)};
-      if (p.gated) {
-        uint16_t dg[4], dor[4];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const float gt = fast_rcp(1.f + fast_exp2(-gl[e] * LOG2E));
-          dg[e] = f2bf(go[e] * o[e] * gt * (1.f - gt));
-          dor[e] = f2bf(go[e] * gt);
-          go[e] = bf2f(dor[e]);  // the later kernels read the rounded copy
-        }
-        uint2 o1, o2;
-        o1.x = (uint32_t)dg[0] | ((uint32_t)dg[1] << 16); o1.y = (uint32_t)dg[2] | ((uint32_t)dg[3] << 16);
-        o2.x = (uint32_t)dor[0] | ((uint32_t)dor[1] << 16); o2.y = (uint32_t)dor[2] | ((uint32_t)dor[3] << 16);
-        *(uint2*)((uint16_t*)p.dG + row + d0) = o1;
-        *(uint2*)((uint16_t*)p.dO_out + (int64_t)b * p.do_sb + (int64_t)q * p.do_ss + (int64_t)h * p.do_sh + d0) = o2;
-      }
-#pragma unroll
-      for (int e = 0; e < 4; ++e) part = fmaf(go[e], o[e], part);
-    }
-  }
-  return part;
-}
 
 }  // namespace
 }  // namespace ssa
