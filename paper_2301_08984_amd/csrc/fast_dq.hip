@@ -13,7 +13,9 @@ namespace {
 // tile transposed.
 // ---------------------------------------------------------------------------
 template <int D, bool BIAS, bool CAUSAL, int QW, int NG>
-__global__ __launch_bounds__(64 * QW * NG) __attribute__((amdgpu_waves_per_eu(2, 2))) void dq_fast_kernel(KP p) {
+// D = 32 needs 100 - 140 registers: three (with a bias) or four wavefronts per SIMD instead of two
+__global__ __launch_bounds__(64 * QW * NG)
+__attribute__((amdgpu_waves_per_eu(D <= 32 ? (BIAS ? 3 : 4) : 2, D <= 32 ? (BIAS ? 3 : 4) : 2))) void dq_fast_kernel(KP p) {
   constexpr int KS = D / 16, DB = D / 32, NT = 64 * QW, BM = 32 * QW;
   constexpr int LDK = D + 24, LDV = D + 8;  // K is read both ways: D + 24 is conflict-free for b128 and transposed reads
   constexpr int CPR = D / 8, CPT = BN * CPR / NT;
