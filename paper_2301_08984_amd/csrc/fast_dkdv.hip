@@ -25,7 +25,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(D <= 32
   __shared__ __attribute__((aligned(16))) float sD[2][BN];
   __shared__ __attribute__((aligned(16))) uint16_t sBias[BIAS ? NW * BIAS_TILE_ELEMS : 8];  // one parked tile per wavefront
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, r = lane & 31, hl = lane >> 5;
-  const BlockId blk = xcd_block_id();
+  const BlockId blk = xcd_block_id(BIAS && bias_rows_first(gridDim.y, p.S));
   const int h = p.h0 + blk.y, b = p.b0 + blk.z;
   const int kblk = blk.x * BK;  // early key blocks see the most queries under a causal mask
   const int k0 = kblk + 32 * w, key = k0 + r;

@@ -29,7 +29,7 @@ __attribute__((amdgpu_waves_per_eu(D <= 32 ? (BIAS ? 3 : 4) : 2, D <= 32 ? (BIAS
   const int lane = tid & 63, w = tid >> 6, r = lane & 31, hl = lane >> 5;
   uint16_t* sK = smem + grp * TILE_ELEMS;
   uint16_t* sV = sK + BN * LDK;
-  const BlockId blk = xcd_block_id();
+  const BlockId blk = xcd_block_id(BIAS && bias_rows_first(gridDim.y, p.S));
   const int h = p.h0 + blk.y, b = p.b0 + blk.z;
   const int qblk = (gridDim.x - 1 - blk.x) * BM;
   const int q0 = qblk + 32 * w, q = q0 + r;

@@ -39,7 +39,7 @@ __global__ __launch_bounds__(64 * QW * NG) __attribute__((amdgpu_waves_per_eu(D 
   const int lane = tid & 63, w = tid >> 6, r = lane & 31, hl = lane >> 5;
   uint16_t* sK = smem + grp * NBUF * TILE_ELEMS;
   uint16_t* sV = sK + BN * LDK;
-  const BlockId blk = xcd_block_id();
+  const BlockId blk = xcd_block_id(BIAS && bias_rows_first(gridDim.y, p.S));
   const int h = p.h0 + blk.y, b = p.b0 + blk.z;
   const int qblk = (gridDim.x - 1 - blk.x) * BM;  // long (late) causal blocks first
   const int q0 = qblk + 32 * w, q = q0 + r;

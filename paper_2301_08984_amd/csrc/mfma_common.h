@@ -115,8 +115,13 @@ __device__ inline bf16x8 lds_tr(const uint16_t* t, int rbase, int cbase, int lan
 // This maps the hardware block id to a logical (x, y, z) such that blocks with consecutive
 // logical ids (same head and row, neighbouring tiles: the ones that re-read the same K/V or
 // Q/dO) run on the same XCD.  A bijection on [0, gridDim.x*gridDim.y*gridDim.z).
+// `z_fast`: z (the row) varies before y (the head), so that the work-groups an XCD runs at one time
+// belong to one head and a handful of rows: for kernels with a dense bias whose heads together do
+// not fit one L2 (see bias_rows_first), the head's bias then stays in that L2 instead of being
+// fetched again for every row, while a row's K/V (or Q/dO) are still shared by neighbouring tiles.
 struct BlockId { int x, y, z; };
-__device__ inline BlockId xcd_block_id() {
+__device__ inline bool bias_rows_first(int heads, int S) { return (int64_t)heads * S * S * 2 > (4 << 20); }
+__device__ inline BlockId xcd_block_id(bool z_fast = false) {
   constexpr int NX = 8;
   const int gx = gridDim.x, gy = gridDim.y;
   const int n = gx * gy * gridDim.z;
@@ -126,8 +131,13 @@ __device__ inline BlockId xcd_block_id() {
   BlockId b;
   b.x = v % gx;
   const int yz = v / gx;
-  b.y = yz % gy;
-  b.z = yz / gy;
+  if (z_fast) {
+    b.z = yz % (int)gridDim.z;
+    b.y = yz / (int)gridDim.z;
+  } else {
+    b.y = yz % gy;
+    b.z = yz / gy;
+  }
   return b;
 }
 
