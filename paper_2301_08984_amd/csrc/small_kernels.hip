@@ -57,15 +57,6 @@ __device__ inline void build_bias_tile(const KP& p, int h, uint16_t* tile, int t
   }
 }
 
-// natural-layout operand fragments of a [<=64 x 32] activation slice: frag[blk][ks]
-__device__ inline void load_nat(const uint16_t* base, int64_t row_stride, int S, int r, int hl, bf16x8 (&f)[2][2]) {
-#pragma unroll
-  for (int blk = 0; blk < 2; ++blk) {
-    const int row = min(32 * blk + r, S - 1);
-#pragma unroll
-    for (int ks = 0; ks < 2; ++ks) f[blk][ks] = *(const bf16x8*)(base + (int64_t)row * row_stride + 16 * ks + 8 * hl);
-  }
-}
 // a [<=64 x 32] activation slice in whole row segments: lane l takes the 16-byte chunk l % 4 of rows
 // l / 4 + 16 c (rows past S - 1 repeat the last row; their scores are masked by the bias tile)
 __device__ inline void load_rows(const uint16_t* base, int64_t row_stride, int S, int lane, u32x4 (&f)[4]) {
@@ -83,12 +74,6 @@ __device__ inline void store_rows(uint16_t* t, int lane, const u32x4 (&f)[4]) {
 // natural-layout fragment of rows 32*blk.. of a per-wave LDS tile
 __device__ inline bf16x8 tile_nat(const uint16_t* t, int blk, int ks, int r, int hl) {
   return *(const bf16x8*)(t + (32 * blk + r) * SLD + 16 * ks + 8 * hl);
-}
-__device__ inline void store_tile(uint16_t* t, int r, int hl, const bf16x8 (&f)[2][2]) {
-#pragma unroll
-  for (int blk = 0; blk < 2; ++blk)
-#pragma unroll
-    for (int ks = 0; ks < 2; ++ks) *(bf16x8*)(t + (32 * blk + r) * SLD + 16 * ks + 8 * hl) = f[blk][ks];
 }
 // orders this wavefront's LDS writes before its following LDS reads
 __device__ inline void wave_lds_sync() {
