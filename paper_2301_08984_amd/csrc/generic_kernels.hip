@@ -323,24 +323,28 @@ __global__ __launch_bounds__(256) void generic_dbias_kernel(KP p) {
   if (live) *dst = acc;
 }
 
+// table[h][r] = sum of dense[h][i][j] over the (i, j) pairs of the window whose relative position is
+// r.  One wavefront per table entry: lane l takes the pairs l, l + 64, ... (numbered in (y, x) order
+// of the query) and the lanes are summed with a fixed butterfly, so the result does not depend on
+// anything but the values.
 __global__ __launch_bounds__(256) void relpos_reduce_kernel(const float* dense, float* table, int h0,
                                                             int nh, int S, int win_h, int win_w) {
   const int R = (2 * win_h - 1) * (2 * win_w - 1);
-  const int t = blockIdx.x * 256 + threadIdx.x;
-  if (t >= nh * R) return;
+  const int t = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (t >= nh * R) return;  // uniform over the wavefront
   const int h = h0 + t / R, r = t % R;
   const int dy = r / (2 * win_w - 1) - (win_h - 1), dx = r % (2 * win_w - 1) - (win_w - 1);
-  float acc = 0.f;
-  for (int yi = 0; yi < win_h; ++yi) {
-    const int yj = yi - dy;
-    if (yj < 0 || yj >= win_h) continue;
-    for (int xi = 0; xi < win_w; ++xi) {
-      const int xj = xi - dx;
-      if (xj < 0 || xj >= win_w) continue;
-      acc += dense[((int64_t)h * S + (yi * win_w + xi)) * S + (yj * win_w + xj)];
-    }
+  // queries (yi, xi) with a partner inside the window: yi in [ylo, yhi), xi in [xlo, xhi)
+  const int ylo = max(dy, 0), yhi = min(win_h + dy, win_h), xlo = max(dx, 0), xhi = min(win_w + dx, win_w);
+  const int nx = xhi - xlo, n = (yhi - ylo) * nx;
+  float v = 0.f;
+  for (int i = lane; i < n; i += 64) {  // one pass for windows of up to 64 positions
+    const int yi = ylo + i / nx, xi = xlo + i % nx;
+    v += dense[((int64_t)h * S + (yi * win_w + xi)) * S + ((yi - dy) * win_w + (xi - dx))];
   }
-  table[(int64_t)h * R + r] = acc;
+#pragma unroll
+  for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, 64);
+  if (lane == 0) table[(int64_t)h * R + r] = v;
 }
 
 __global__ __launch_bounds__(256) void fill_zero_kernel(float* p, size_t n) {
@@ -388,7 +392,7 @@ hipError_t launch_relpos_reduce(const float* dense, float* table, int h0, int h1
                                 int win_w, hipStream_t st) {
   const int R = (2 * win_h - 1) * (2 * win_w - 1);
   const int n = (h1 - h0) * R;
-  relpos_reduce_kernel<<<(n + 255) / 256, 256, 0, st>>>(dense, table, h0, h1 - h0, S, win_h, win_w);
+  relpos_reduce_kernel<<<(n + 3) / 4, 256, 0, st>>>(dense, table, h0, h1 - h0, S, win_h, win_w);
   return hipGetLastError();
 }
 hipError_t launch_fill_zero(float* ptr, size_t n, hipStream_t st) {
