@@ -432,15 +432,32 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 // into the slice's first group (in place, ascending order); level 2 adds the slice sums in
 // ascending order into dense[h][i][j].  The tree depends only on the group count.
 constexpr int SLICE = 32;
+typedef f32x4 f32x4_u __attribute__((aligned(4)));
+// The heads [h0, h0 + nh) of one group are one contiguous run of nh * SS floats: a thread takes four
+// consecutive ones (16-byte loads need 4-byte alignment only), each summed over the groups in order.
 __global__ __launch_bounds__(256) void small_group_fold_kernel(float* partial, int ngroups, int H, int h0, int nh,
                                                                int SS) {
-  const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (t >= (int64_t)nh * SS) return;
-  const int h = h0 + (int)(t / SS), ij = (int)(t % SS);
+  const int64_t n = (int64_t)nh * SS, t = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
+  if (t >= n) return;
   const int g0 = blockIdx.y * SLICE, g1 = min(g0 + SLICE, ngroups);
-  float a = 0.f;
-  for (int g = g0; g < g1; ++g) a += partial[((int64_t)g * H + h) * SS + ij];
-  partial[((int64_t)g0 * H + h) * SS + ij] = a;
+  const int64_t gs = (int64_t)H * SS;
+  float* p0 = partial + (int64_t)h0 * SS + t;
+  if (t + 4 <= n) {
+    f32x4 a = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll 8
+    for (int g = g0; g < g1; ++g) {
+      const f32x4 v = *(const f32x4_u*)(p0 + g * gs);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) a[e] += v[e];
+    }
+    *(f32x4_u*)(p0 + g0 * gs) = a;
+  } else {
+    for (int e = 0; t + e < n; ++e) {
+      float a = 0.f;
+      for (int g = g0; g < g1; ++g) a += p0[g * gs + e];
+      p0[g0 * gs + e] = a;
+    }
+  }
 }
 __global__ __launch_bounds__(256) void small_group_reduce_kernel(const float* partial, float* dense, int ngroups,
                                                                  int H, int h0, int nh, int SS) {
@@ -478,8 +495,8 @@ hipError_t launch_small_group_reduce(float* partial, float* dense, int ngroups, 
                                      hipStream_t st) {
   const int64_t n = (int64_t)(h1 - h0) * S * S;
   const unsigned bx = (unsigned)((n + 255) / 256);
-  small_group_fold_kernel<<<dim3(bx, (ngroups + SLICE - 1) / SLICE), 256, 0, st>>>(partial, ngroups, H, h0, h1 - h0,
-                                                                                  S * S);
+  small_group_fold_kernel<<<dim3((unsigned)((n + 1023) / 1024), (ngroups + SLICE - 1) / SLICE), 256, 0, st>>>(
+      partial, ngroups, H, h0, h1 - h0, S * S);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   small_group_reduce_kernel<<<bx, 256, 0, st>>>(partial, dense, ngroups, H, h0, h1 - h0, S * S);
