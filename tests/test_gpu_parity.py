@@ -39,6 +39,7 @@ SMALL = {
     "short_gated": dict(seed=45, B=5, H=2, S=33, D=32, dtype="bf16", bias="dense", gated=True, axis="head"),
     "long_rows_many_groups": dict(seed=46, B=150, H=1, S=64, D=32, dtype="bf16", bias="dense", axis="row"),
     "d128_bias": dict(seed=47, B=2, H=2, S=128, D=128, dtype="bf16", bias="dense", axis="row"),
+    "d128_gated": dict(seed=57, B=2, H=2, S=200, D=128, dtype="bf16", gated=True, axis="head"),
     # long rows in a small share: work-groups split the keys (forward, dQ) / the queries (dK, dV)
     "long_seq_few_heads": dict(seed=48, B=1, H=2, S=600, D=128, dtype="bf16", mask="causal", axis="head"),
     "long_seq_bias_d64": dict(seed=49, B=2, H=1, S=516, D=64, dtype="bf16", bias="dense", gated=True, axis="row"),
