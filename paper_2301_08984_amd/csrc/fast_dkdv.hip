@@ -40,8 +40,8 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(D <= 32
   // bias comes from the transposed copy biasT[h][key][query], so that a lane (= key) finds four
   // consecutive queries in 8 bytes
   BiasTile bt;
-  if (BIAS) bt.init((const uint16_t*)p.biasT + (int64_t)h * p.S * p.S, k0, p.S, sBias + w * BIAS_TILE_ELEMS);
-  auto bload = [&](int qt) { bt.load(qt, lane); };
+  if (BIAS) bt.init((const uint16_t*)p.biasT + (int64_t)h * p.S * p.S, k0, p.S, sBias + w * BIAS_TILE_ELEMS, lane);
+  auto bload = [&](int qt) { bt.load(qt); };
 
   bf16x8 kf[KS], vf[KS];
 #pragma unroll

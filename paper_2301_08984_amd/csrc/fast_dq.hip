@@ -42,7 +42,7 @@ __attribute__((amdgpu_waves_per_eu(D <= 32 ? (BIAS ? 3 : 4) : 2, D <= 32 ? (BIAS
   BiasTile bt;
   if (BIAS)
     bt.init((const uint16_t*)p.bias + (int64_t)h * p.S * p.S, q0, p.S,
-            smem + KV_ELEMS + (threadIdx.x >> 6) * BIAS_TILE_ELEMS);
+            smem + KV_ELEMS + (threadIdx.x >> 6) * BIAS_TILE_ELEMS, lane);
 
   bf16x8 qf[KS], gf[KS];
 #pragma unroll
@@ -75,7 +75,7 @@ __attribute__((amdgpu_waves_per_eu(D <= 32 ? (BIAS ? 3 : 4) : 2, D <= 32 ? (BIAS
     }
   };
   // the bias slice of the next tile travels with the next K/V tile
-  auto bload = [&](int kt) { bt.load(kt, lane); };
+  auto bload = [&](int kt) { bt.load(kt); };
   if (grp < ntiles) {
     gload(grp);
     if (BIAS) bload(grp);

@@ -51,7 +51,7 @@ __global__ __launch_bounds__(64 * QW * NG) __attribute__((amdgpu_waves_per_eu(D 
   BiasTile bt;
   if (BIAS)
     bt.init((const uint16_t*)p.bias + (int64_t)h * p.S * p.S, q0, p.S,
-            smem + KV_ELEMS + (threadIdx.x >> 6) * BIAS_TILE_ELEMS);
+            smem + KV_ELEMS + (threadIdx.x >> 6) * BIAS_TILE_ELEMS, lane);
 
   bf16x8 qf[KS];
 #pragma unroll
@@ -80,7 +80,7 @@ __global__ __launch_bounds__(64 * QW * NG) __attribute__((amdgpu_waves_per_eu(D 
     }
   };
   // the bias slice of the next tile travels with the next K/V tile
-  auto bload = [&](int kt) { bt.load(kt, lane); };
+  auto bload = [&](int kt) { bt.load(kt); };
   auto bpark = [&]() { bt.park(lane); };  // read back by the next tile()
   if (grp < ntiles) {
     gload(grp);

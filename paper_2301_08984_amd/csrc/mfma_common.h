@@ -143,32 +143,38 @@ __device__ inline BlockId xcd_block_id(bool z_fast = false) {
 
 // Dense bias tile of one wavefront: 32 rows (queries, or keys of the transposed copy) by 64 columns.
 // A lane of the score tile owns one row and needs 4 consecutive columns at a time, so direct loads
-// would touch 64 rows per instruction.  Instead 16 lanes fetch 128 contiguous bytes of one row (4
-// rows per instruction, 8 instructions per tile, issued one tile ahead), the tile is parked in a
-// wavefront-private LDS area and read back in the layout of the accumulator.  LDS rows are padded to
-// 136 bytes so that the 8-byte reads of 32 rows fall into distinct banks.  Rows past S are replaced
-// by in-bounds addresses (their scores are masked or never stored); S is a multiple of 4.
+// would touch 64 rows per instruction.  Instead 8 lanes fetch 128 contiguous bytes of one row, 16
+// bytes each (8 rows per instruction, 4 instructions per tile, issued one tile ahead: 8-byte loads
+// move half as many bytes per cycle through a compute unit's load path, and the bias is two thirds
+// of these kernels' load traffic), the tile is parked in a wavefront-private LDS area and read back
+// in the layout of the accumulator.  LDS rows are padded to 136 bytes so that the 8-byte reads of 32
+// rows fall into distinct banks.  The loads are buffer loads over the head's S x S matrix: a row past
+// S - 1 lies past the end and reads as zeros, columns past S - 1 read the next row; both belong to
+// scores that are masked or never stored.  S is a multiple of 4 and S * S * 2 bytes at most 2 GiB.
 constexpr int BIAS_LD = 68, BIAS_TILE_ELEMS = 32 * BIAS_LD;
 struct BiasTile {
-  const uint16_t* base;  // first row of the wavefront (uniform)
-  uint16_t* lds;         // the wavefront's area, BIAS_TILE_ELEMS elements
-  int S, lim;            // lim: largest offset that keeps an 8-byte load inside the head's matrix
-  uint2 nxt[8];
-  __device__ void init(const uint16_t* head, int row0, int S_, uint16_t* area) {
-    S = S_;
+  __amdgpu_buffer_rsrc_t rs;  // the head's matrix
+  uint16_t* lds;              // the wavefront's area, BIAS_TILE_ELEMS elements
+  uint32_t off, rstep;        // byte offset of this lane's chunk in tile 0; bytes between its rows
+  u32x4 nxt[4];
+  __device__ void init(const uint16_t* head, int row0, int S, uint16_t* area, int lane) {
+    rs = __builtin_amdgcn_make_buffer_rsrc((void*)head, 0, (int)((int64_t)S * S * 2), 0x00020000);
     const int first = __builtin_amdgcn_readfirstlane(min(row0, S - 1));
-    base = head + (int64_t)first * S;
-    lim = (S - 1 - first) * S + S - 4;
+    off = ((uint32_t)(first + (lane >> 3)) * (uint32_t)S + 8u * (lane & 7)) * 2u;
+    rstep = 16u * (uint32_t)S;  // 8 rows
     lds = area;
   }
-  __device__ void load(int tile, int lane) {
-    const int off = (lane >> 4) * S + min(tile * 64 + 4 * (lane & 15), S - 4);
+  __device__ void load(int tile) {
 #pragma unroll
-    for (int c = 0; c < 8; ++c) nxt[c] = *(const uint2*)(base + min(off + 4 * c * S, lim));
+    for (int c = 0; c < 4; ++c) nxt[c] = __builtin_amdgcn_raw_buffer_load_b128(rs, off + tile * 128 + c * rstep, 0, 0);
   }
   __device__ void park(int lane) {
 #pragma unroll
-    for (int c = 0; c < 8; ++c) *(uint2*)(lds + ((lane >> 4) + 4 * c) * BIAS_LD + 4 * (lane & 15)) = nxt[c];
+    for (int c = 0; c < 4; ++c) {
+      uint16_t* d = lds + ((lane >> 3) + 8 * c) * BIAS_LD + 8 * (lane & 7);
+      *(uint2*)d = uint2{nxt[c][0], nxt[c][1]};
+      *(uint2*)(d + 4) = uint2{nxt[c][2], nxt[c][3]};
+    }
   }
   // columns col .. col + 3 (col a multiple of 4) of row r of the parked tile
   __device__ uint2 read(int r, int col) const { return *(const uint2*)(lds + r * BIAS_LD + col); }
@@ -272,7 +278,7 @@ __device__ inline void fwd_epilogue(const KP& p, f32x16 (&oacc)[DB], float m, fl
 // causal mask; a positive scale; more than one 64-key tile's worth of rows
 inline bool fast_ok(const KP& p) {
   if (p.S <= 64 || !(p.scale > 0.f) || p.mask_kind == 2 || p.bias_kind == 2) return false;
-  if (p.bias_kind == 1 && (!p.bias_bf16 || (p.S & 3))) return false;
+  if (p.bias_kind == 1 && (!p.bias_bf16 || (p.S & 3) || p.S > 32768)) return false;
   return true;
 }
 
