@@ -349,18 +349,24 @@ __global__ __launch_bounds__(256) void dbias_fast_kernel(KP p) {
 // At D = 32 four work-groups fill a compute unit exactly (4 x 40 KB of LDS, 128 registers per lane),
 // which is also what a 1024 x 1024 head needs for all its tiles to be resident at once; the per-row
 // statistics therefore live in the padding of the Q tile's rows instead of arrays of their own.
-template <int D, bool CAUSAL>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D <= 32 ? 4 : 1, D <= 32 ? 4 : (D <= 64 ? 2 : 1))))
+// HP = 2 (D = 32, heads side by side in memory): eight wavefronts cover the same tile of two
+// neighbouring heads, whose row slices are fetched together as 128 contiguous bytes: whole cache
+// lines instead of halves, at twice the bytes per cycle through the load path.
+template <int D, bool CAUSAL, int HP>
+__global__ __launch_bounds__(256 * HP)
+__attribute__((amdgpu_waves_per_eu(D <= 32 ? 4 : 1, D <= 32 ? 4 : (D <= 64 ? 2 : 1))))
 void dbias_tile_kernel(KP p) {
   constexpr int KS = D / 16, LD = D + 8, CPR = D / 8;
   constexpr int CPT = 64 * CPR / 256;  // 16-byte chunks per thread per tensor tile
-  __shared__ __attribute__((aligned(16))) uint16_t sT[2][4][64 * LD];  // Q, dO, K, V
-  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, r = lane & 31, hl = lane >> 5;
-  const int Hc = p.h1 - p.h0;
+  static_assert(HP == 1 || CPT == 1, "two heads per work-group: D = 32 only");
+  __shared__ __attribute__((aligned(16))) uint16_t sT[2][4][HP][64 * LD];  // Q, dO, K, V
+  const int tid = threadIdx.x, lane = tid & 63, w = (tid >> 6) & 3, hsel = tid >> 8, r = lane & 31, hl = lane >> 5;
+  const int Hc = (p.h1 - p.h0) / HP;  // head groups
   // consecutive tiles (same head, neighbouring query tiles, all key tiles) run on one XCD, so a
   // row's Q/dO/K/V slices are fetched into few L2s instead of all eight
   const BlockId blk = xcd_block_id();
-  const int h = p.h0 + blk.z % Hc;
+  const int hA = p.h0 + (blk.z % Hc) * HP;  // first head of the work-group
+  const int h = hA + hsel;
   const int q0t = blk.y * 64, k0t = blk.x * 64;
   const int wq = w >> 1, wk = w & 1;
   const int q0 = q0t + 32 * wq, k0 = k0t + 32 * wk;
@@ -393,33 +399,47 @@ void dbias_tile_kernel(KP p) {
     // staging: thread -> (tensor-tile row, 16-byte chunk); Q/dO rows q0t.., K/V rows k0t..
     u32x4 pre[4][CPT];
     float pstat = 0.f;
+    // HP = 1: thread t takes the chunks t, t + 256, ... of its head's tile rows.  HP = 2: the two heads'
+    // slices of a row are 2 * CPR consecutive chunks (stride_h == D); thread t takes chunk t of them.
+    auto chunk = [&](int c, int& hh, int& row, int& col) {
+      const int idx = HP == 1 ? tid + c * 256 : tid;
+      row = idx / (CPR * HP);
+      hh = HP == 1 ? 0 : (idx % (CPR * HP)) / CPR;
+      col = (idx % CPR) * 8;
+    };
     auto gload = [&](int b) {
 #pragma unroll
       for (int c = 0; c < CPT; ++c) {
-        const int idx = tid + c * 256, row = idx / CPR, col = (idx % CPR) * 8;
+        int hh, row, col;
+        chunk(c, hh, row, col);
         const int rq = min(q0t + row, p.S - 1), rk = min(k0t + row, p.S - 1);
-        const int64_t ba = (int64_t)b * p.sb + (int64_t)h * p.sh;
-        pre[0][c] = *(const u32x4*)((const uint16_t*)p.Q + ba + (int64_t)rq * p.ss + col);
-        pre[1][c] = *(const u32x4*)((const uint16_t*)p.dO + (int64_t)b * p.do_sb + (int64_t)h * p.do_sh + (int64_t)rq * p.do_ss + col);
-        pre[2][c] = *(const u32x4*)((const uint16_t*)p.K + ba + (int64_t)rk * p.ss + col);
-        pre[3][c] = *(const u32x4*)((const uint16_t*)p.V + ba + (int64_t)rk * p.ss + col);
+        const int hc = HP == 1 ? h : hA;  // HP = 2: addressed from the first head, hh * D columns on
+        const int64_t ba = (int64_t)b * p.sb + (int64_t)hc * p.sh + hh * D + col;
+        pre[0][c] = *(const u32x4*)((const uint16_t*)p.Q + ba + (int64_t)rq * p.ss);
+        pre[1][c] = *(const u32x4*)((const uint16_t*)p.dO + (int64_t)b * p.do_sb + (int64_t)hc * p.do_sh + (int64_t)rq * p.do_ss + hh * D + col);
+        pre[2][c] = *(const u32x4*)((const uint16_t*)p.K + ba + (int64_t)rk * p.ss);
+        pre[3][c] = *(const u32x4*)((const uint16_t*)p.V + ba + (int64_t)rk * p.ss);
       }
-      if (tid < 128) {
-        const int i = min(q0t + (tid & 63), p.S - 1);
-        pstat = tid < 64 ? p.lse[(int64_t)b * p.lse_sb + (int64_t)h * p.lse_sh + i]
-                         : p.delta[(int64_t)b * p.dl_sb + (int64_t)h * p.dl_sh + i];
+      if (tid < 128 * HP) {
+        const int hs = hA + tid / 128, i = min(q0t + (tid & 63), p.S - 1);
+        pstat = (tid & 64) == 0 ? p.lse[(int64_t)b * p.lse_sb + (int64_t)hs * p.lse_sh + i]
+                                : p.delta[(int64_t)b * p.dl_sb + (int64_t)hs * p.dl_sh + i];
       }
     };
     auto lstore = [&](int buf) {
 #pragma unroll
       for (int c = 0; c < CPT; ++c) {
-        const int idx = tid + c * 256, row = idx / CPR, col = (idx % CPR) * 8;
+        int hh, row, col;
+        chunk(c, hh, row, col);
 #pragma unroll
-        for (int t = 0; t < 4; ++t) *(u32x4*)(&sT[buf][t][row * LD + col]) = pre[t][c];
+        for (int t = 0; t < 4; ++t) *(u32x4*)(&sT[buf][t][hh][row * LD + col]) = pre[t][c];
       }
       // LSE (base 2) and Delta of query i: the two floats after the D elements of row i of the Q tile
-      if (tid < 64) *(float*)(&sT[buf][0][tid * LD + D]) = pstat * LOG2E;
-      else if (tid < 128) *(float*)(&sT[buf][0][(tid - 64) * LD + D + 2]) = pstat;
+      if (tid < 128 * HP) {
+        float* st = (float*)(&sT[buf][0][tid / 128][(tid & 63) * LD + D]);
+        if ((tid & 64) == 0) st[0] = pstat * LOG2E;
+        else st[1] = pstat;
+      }
     };
     gload(bfirst);
     lstore(bfirst & 1);
@@ -434,10 +454,10 @@ void dbias_tile_kernel(KP p) {
       for (int v = 0; v < 16; ++v) { sa[v] = 0.f; pa[v] = 0.f; }
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
-        sa = mfma(lds_nat<LD>(sT[buf][2], 32 * wk + r, ks, hl), lds_nat<LD>(sT[buf][0], 32 * wq + r, ks, hl), sa);
-        pa = mfma(lds_nat<LD>(sT[buf][3], 32 * wk + r, ks, hl), lds_nat<LD>(sT[buf][1], 32 * wq + r, ks, hl), pa);
+        sa = mfma(lds_nat<LD>(sT[buf][2][hsel], 32 * wk + r, ks, hl), lds_nat<LD>(sT[buf][0][hsel], 32 * wq + r, ks, hl), sa);
+        pa = mfma(lds_nat<LD>(sT[buf][3][hsel], 32 * wk + r, ks, hl), lds_nat<LD>(sT[buf][1][hsel], 32 * wq + r, ks, hl), pa);
       }
-      const float2 st2 = *(const float2*)(&sT[buf][0][(32 * wq + r) * LD + D]);
+      const float2 st2 = *(const float2*)(&sT[buf][0][hsel][(32 * wq + r) * LD + D]);
       const float lse2 = st2.x, dlt = st2.y;
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
@@ -490,9 +510,19 @@ hipError_t dbias_d(const KP& p, hipStream_t st) {
   if (p.S % 4 == 0 && p.S >= 64) {
     int ng = 1;
     if (p.sm_partial) ng = (p.b1 - 1) / p.sm_gw - p.b0 / p.sm_gw + 1;
-    dim3 g((p.S + 63) / 64, (p.S + 63) / 64, (p.h1 - p.h0) * ng);
-    if (p.mask_kind == 1) dbias_tile_kernel<D, true><<<g, 256, 0, st>>>(p);
-    else dbias_tile_kernel<D, false><<<g, 256, 0, st>>>(p);
+    const int heads = p.h1 - p.h0;
+    const int64_t tiles = (int64_t)((p.S + 63) / 64) * ((p.S + 63) / 64);
+    if (D == 32 && heads % 2 == 0 && p.sh == D && p.do_sh == D && tiles * (heads / 2) * ng >= 512) {
+      // neighbouring heads are 64 bytes apart: two per work-group, if that still leaves two
+      // work-groups per compute unit
+      dim3 g((p.S + 63) / 64, (p.S + 63) / 64, heads / 2 * ng);
+      if (p.mask_kind == 1) dbias_tile_kernel<D <= 32 ? D : 32, true, 2><<<g, 512, 0, st>>>(p);
+      else dbias_tile_kernel<D <= 32 ? D : 32, false, 2><<<g, 512, 0, st>>>(p);
+      return hipGetLastError();
+    }
+    dim3 g((p.S + 63) / 64, (p.S + 63) / 64, heads * ng);
+    if (p.mask_kind == 1) dbias_tile_kernel<D, true, 1><<<g, 256, 0, st>>>(p);
+    else dbias_tile_kernel<D, false, 1><<<g, 256, 0, st>>>(p);
     return hipGetLastError();
   }
   dim3 g((p.S + 127) / 128, (p.S + 31) / 32, p.h1 - p.h0);

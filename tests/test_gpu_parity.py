@@ -40,6 +40,8 @@ SMALL = {
     "long_rows_many_groups": dict(seed=46, B=150, H=1, S=64, D=32, dtype="bf16", bias="dense", axis="row"),
     "d128_bias": dict(seed=47, B=2, H=2, S=128, D=128, dtype="bf16", bias="dense", axis="row"),
     "d128_gated": dict(seed=57, B=2, H=2, S=200, D=128, dtype="bf16", gated=True, axis="head"),
+    # enough bias-gradient tiles for the variant that covers two neighbouring heads per work-group
+    "dbias_two_heads": dict(seed=58, B=3, H=16, S=512, D=32, dtype="bf16", bias="dense", axis="row"),
     # long rows in a small share: work-groups split the keys (forward, dQ) / the queries (dK, dV)
     "long_seq_few_heads": dict(seed=48, B=1, H=2, S=600, D=128, dtype="bf16", mask="causal", axis="head"),
     "long_seq_bias_d64": dict(seed=49, B=2, H=1, S=516, D=64, dtype="bf16", bias="dense", gated=True, axis="row"),
@@ -86,7 +88,7 @@ def test_sub_range_and_saved_lse(name):
 
 @pytest.mark.parametrize("name", ["gpt_like", "swin_like", "msa_like", "tiny_mha", "bias_causal_d64",
                                   "short_dense_causal", "long_rows_many_groups", "long_seq_few_heads",
-                                  "long_seq_bias_d64", "swin_head_axis", "tri_end_like"])
+                                  "long_seq_bias_d64", "swin_head_axis", "tri_end_like", "dbias_two_heads"])
 def test_results_identical_across_k(name):
     cfg = SMALL[name]
     ref = None
