@@ -18,6 +18,8 @@
 // gathered per table entry in a fixed order.
 #include "mfma_common.h"
 
+#include <type_traits>
+
 namespace ssa {
 namespace {
 
@@ -149,7 +151,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     store_rows(L.t1, lane, kn);
     store_rows(L.t0, lane, vn);
     fetch(min(b + 1, blast - 1));
-    if (REGION) L.rid[lane] = p.region[(int64_t)(b % p.mask_period) * p.S + min(lane, p.S - 1)];
+    // most windows of a shifted-window map lie inside one region: their mask masks nothing, and the
+    // row takes the copy of the code without the compare and select per score (uniform branch)
+    bool masked = false;
+    if (REGION) {
+      const int my = p.region[(int64_t)(b % p.mask_period) * p.S + min(lane, p.S - 1)];
+      L.rid[lane] = my;
+      masked = __builtin_amdgcn_ballot_w64(my != __builtin_amdgcn_readfirstlane(my)) != 0;
+    }
     wave_lds_sync();
     bf16x8 qf[2][2], kf[2][2];
 #pragma unroll
@@ -164,7 +173,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     for (int qb = 0; qb < 2; ++qb) {
       const int q = 32 * qb + r;
       float x[2][16];
-      scores_by_query<REGION>(p, kf, qf, qb, bias_tile, L.rid, q, hl, c1, x);
+      if (masked) scores_by_query<true>(p, kf, qf, qb, bias_tile, L.rid, q, hl, c1, x);
+      else scores_by_query<false>(p, kf, qf, qb, bias_tile, L.rid, q, hl, c1, x);
       float m = -1e30f;
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
@@ -272,7 +282,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
       store_rows(L.t1, lane, tg);
       store_rows(L.t2, lane, tq);
     }
-    if (REGION) L.rid[lane] = p.region[(int64_t)(b % p.mask_period) * p.S + min(lane, p.S - 1)];
+    // most windows of a shifted-window map lie inside one region: their mask masks nothing, and the
+    // row takes the copy of the code without the compare and select per score (uniform branch)
+    bool masked = false;
+    if (REGION) {
+      const int my = p.region[(int64_t)(b % p.mask_period) * p.S + min(lane, p.S - 1)];
+      L.rid[lane] = my;
+      masked = __builtin_amdgcn_ballot_w64(my != __builtin_amdgcn_readfirstlane(my)) != 0;
+    }
     wave_lds_sync();
     // ---- pass 1, lane = query: exact softmax, Delta, dQ
 #pragma unroll
@@ -289,7 +306,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
           qf[qb][ks] = tile_nat(L.t2, qb, ks, r, hl);
           gq_[ks] = tile_nat(L.t1, qb, ks, r, hl);
         }
-        scores_by_query<REGION>(p, kf, qf, qb, bias_tile, L.rid, q, hl, c1, x);
+        if (masked) scores_by_query<true>(p, kf, qf, qb, bias_tile, L.rid, q, hl, c1, x);
+        else scores_by_query<false>(p, kf, qf, qb, bias_tile, L.rid, q, hl, c1, x);
       }
       float m = -1e30f;
 #pragma unroll
@@ -371,24 +389,29 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
           pa = mfma(tile_nat(L.t1, qb, ks, r, hl), vf[kb][ks], pa);
         }
         float pr[16], ds[16];
+        auto probs = [&](auto masked_tag) {
+          constexpr bool MASKED = decltype(masked_tag)::value;
 #pragma unroll
-        for (int gq = 0; gq < 4; ++gq) {
-          const int qbase = 32 * qb + 8 * gq + 4 * hl;
-          const f32x4 l4 = *(const f32x4*)(L.lse2 + qbase);
-          const f32x4 d4 = *(const f32x4*)(L.delta + qbase);
-          int4 rq = {0, 0, 0, 0};
-          if (REGION) rq = *(const int4*)(L.rid + qbase);
-          const int rqs[4] = {rq.x, rq.y, rq.z, rq.w};
+          for (int gq = 0; gq < 4; ++gq) {
+            const int qbase = 32 * qb + 8 * gq + 4 * hl;
+            const f32x4 l4 = *(const f32x4*)(L.lse2 + qbase);
+            const f32x4 d4 = *(const f32x4*)(L.delta + qbase);
+            int4 rq = {0, 0, 0, 0};
+            if (MASKED) rq = *(const int4*)(L.rid + qbase);
+            const int rqs[4] = {rq.x, rq.y, rq.z, rq.w};
 #pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const float bl = bf2f(bias_tile[(qbase + e) * BLD + key]) * LOG2E;
-            float t = fmaf(sa[4 * gq + e], c1, bl) - l4[e];
-            if (REGION) t = rqs[e] != my_rid ? -INFINITY : t;
-            const float pe = fast_exp2(t);
-            pr[4 * gq + e] = pe;
-            ds[4 * gq + e] = pe * (pa[4 * gq + e] - d4[e]);
+            for (int e = 0; e < 4; ++e) {
+              const float bl = bf2f(bias_tile[(qbase + e) * BLD + key]) * LOG2E;
+              float t = fmaf(sa[4 * gq + e], c1, bl) - l4[e];
+              if (MASKED) t = rqs[e] != my_rid ? -INFINITY : t;
+              const float pe = fast_exp2(t);
+              pr[4 * gq + e] = pe;
+              ds[4 * gq + e] = pe * (pa[4 * gq + e] - d4[e]);
+            }
           }
-        }
+        };
+        if (masked) probs(std::true_type{});
+        else probs(std::false_type{});
         if (part) {
 #pragma unroll
           for (int v = 0; v < 16; ++v) acc[qb][kb][v] += ds[v];
