@@ -38,24 +38,32 @@ struct WaveLds {
 };
 
 // builds bias[q][k] (raw bf16 value; -inf where the pair can never be attended: padding,
-// causal) for head h; caller syncs
-__device__ inline void build_bias_tile(const KP& p, int h, uint16_t* tile, int tid, int nt) {
+// causal) for head h with 256 threads; caller syncs.  The 16 entries of a thread are fetched first
+// and stored afterwards, so that the gathers are in flight together (one after the other they cost
+// every work-group several microseconds before its first row).
+__device__ inline void build_bias_tile(const KP& p, int h, uint16_t* tile, int tid) {
   const int R = (2 * p.win_h - 1) * (2 * p.win_w - 1);
-  for (int idx = tid; idx < 64 * 64; idx += nt) {
-    const int q = idx >> 6, k = idx & 63;
-    uint16_t v = 0;
-    if (q >= p.S || k >= p.S || (p.mask_kind == 1 && k > q)) {
-      v = 0xff80;  // -inf
-    } else if (p.bias_kind == 1) {
-      const int64_t off = ((int64_t)h * p.S + q) * p.S + k;
-      v = p.bias_bf16 ? ((const uint16_t*)p.bias)[off] : f2bf(((const float*)p.bias)[off]);
+  uint16_t v[16];
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    const int idx = tid + i * 256, q = idx >> 6, k = idx & 63;
+    const bool dead = q >= p.S || k >= p.S || (p.mask_kind == 1 && k > q);
+    int64_t off = 0;
+    if (p.bias_kind == 1) {
+      off = ((int64_t)h * p.S + min(q, p.S - 1)) * p.S + min(k, p.S - 1);
     } else if (p.bias_kind == 2) {
-      const int yq = q / p.win_w, xq = q - yq * p.win_w, yk = k / p.win_w, xk = k - yk * p.win_w;
-      const int r = (yq - yk + p.win_h - 1) * (2 * p.win_w - 1) + (xq - xk + p.win_w - 1);
-      const int64_t off = (int64_t)h * R + r;
-      v = p.bias_bf16 ? ((const uint16_t*)p.bias)[off] : f2bf(((const float*)p.bias)[off]);
+      const int qq = min(q, p.S - 1), kk = min(k, p.S - 1);
+      const int yq = qq / p.win_w, xq = qq - yq * p.win_w, yk = kk / p.win_w, xk = kk - yk * p.win_w;
+      off = (int64_t)h * R + (yq - yk + p.win_h - 1) * (2 * p.win_w - 1) + (xq - xk + p.win_w - 1);
     }
-    tile[q * BLD + k] = v;
+    uint16_t x = 0;
+    if (p.bias_kind != 0) x = p.bias_bf16 ? ((const uint16_t*)p.bias)[off] : f2bf(((const float*)p.bias)[off]);
+    v[i] = dead ? (uint16_t)0xff80 : x;  // -inf
+  }
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    const int idx = tid + i * 256;
+    tile[(idx >> 6) * BLD + (idx & 63)] = v[i];
   }
 }
 
@@ -130,7 +138,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   __shared__ __attribute__((aligned(16))) WaveLds wl[4];
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, r = lane & 31, hl = lane >> 5;
   const int h = p.h0 + blockIdx.y;
-  build_bias_tile(p, h, bias_tile, tid, 256);
+  build_bias_tile(p, h, bias_tile, tid);
   __syncthreads();
   WaveLds& L = wl[w];
   const float c1 = p.scale * LOG2E;
@@ -234,7 +242,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   __shared__ __attribute__((aligned(16))) WaveLds wl[4];
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, r = lane & 31, hl = lane >> 5;
   const int h = p.h0 + blockIdx.y;
-  build_bias_tile(p, h, bias_tile, tid, 256);
+  build_bias_tile(p, h, bias_tile, tid);
   __syncthreads();
   WaveLds& L = wl[w];
   const float c1 = p.scale * LOG2E;
