@@ -471,6 +471,10 @@ SS_GEMM_INST4(true, false, SS_FORCE_TILE / 100, SS_FORCE_TILE / 10 % 10, SS_FORC
 SS_GEMM_INST4(false, false, 4, 2, 4)
 SS_GEMM_INST4(false, true, 4, 2, 4)
 SS_GEMM_INST4(true, false, 4, 2, 2)
+// 128 x 128 tiles for products that are not accumulated over chunks, when the large tiles are few
+SS_GEMM_INST(false, false, 0, 2, 2, 4) SS_GEMM_INST(false, false, 1, 2, 2, 4) SS_GEMM_INST(false, false, 3, 2, 2, 4)
+SS_GEMM_INST(false, true, 0, 2, 2, 4) SS_GEMM_INST(false, true, 1, 2, 2, 4) SS_GEMM_INST(false, true, 3, 2, 2, 4)
+SS_GEMM_INST(true, false, 0, 2, 2, 4) SS_GEMM_INST(true, false, 1, 2, 2, 4) SS_GEMM_INST(true, false, 3, 2, 2, 4)
 #endif
 #undef SS_GEMM_INST4
 #undef SS_GEMM_INST
@@ -482,14 +486,24 @@ hipError_t launch_one(const GemmArgs& g, hipStream_t st) {
   return hipGetLastError();
 }
 
-// The tile shape depends on the operand layouts only, never on the sizes: every chunk of an
-// accumulated product must cut its fp32 partial result into the same tiles.
+// For an accumulated product the tile shape depends on the operand layouts only, never on the
+// sizes: every chunk must cut its fp32 partial result into the same tiles.  The other products may
+// choose: an output element is the same chain of MFMA steps whatever tile it falls into, so when
+// fewer than 160 of the 256 x 128 tiles exist (k = 4 on the GPT-3 share: 96) they take 128 x 128
+// tiles, twice as many work-groups at 4/3 of the operand traffic per flop.
 template <bool AT, bool BT>
 hipError_t launch_epi(const GemmArgs& g, int epi, hipStream_t st) {
 #ifdef SS_FORCE_TILE
   constexpr int FI = SS_FORCE_TILE / 100, FJ = SS_FORCE_TILE / 10 % 10, KS = SS_FORCE_TILE % 10;
 #else
   constexpr int FI = 4, FJ = 2, KS = AT ? 2 : 4;
+  if (epi != EPI_ACC && (int64_t)((g.M + 255) / 256) * ((g.N + 127) / 128) < 160) {
+    switch (epi) {
+      case EPI_ACT: return launch_one<AT, BT, EPI_ACT, 2, 2, 4>(g, st);
+      case EPI_MUL: return launch_one<AT, BT, EPI_MUL, 2, 2, 4>(g, st);
+      default: return launch_one<AT, BT, EPI_STORE, 2, 2, 4>(g, st);
+    }
+  }
 #endif
   switch (epi) {
     case EPI_ACT: return launch_one<AT, BT, EPI_ACT, FI, FJ, KS>(g, st);
