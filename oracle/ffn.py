@@ -46,11 +46,13 @@ _C0 = 0.7978845608028654  # sqrt(2/pi)
 _C1 = 0.044715
 
 
-def chunk_ranges(lo: int, hi: int, k: int, unit: int = 16):
-    """Split the hidden range [lo,hi) into k consecutive chunks, balanced in units of `unit`
-    columns counted from lo (reading: the paper assumes even partitions, Section 4; a boundary
-    granularity keeps every chunk a whole number of contraction steps).  Chunks may be empty only
-    if k exceeds the number of units."""
+def chunk_ranges(lo: int, hi: int, k: int, unit: int = 1):
+    """Split the hidden range [lo,hi) into k consecutive chunks, as even as possible (Section 4
+    assumes even partitions; the balanced floor split extends that to k not dividing the range).
+    `unit` is an interface parameter, not part of the method: an implementation may promise chunk
+    boundaries at multiples of `unit` columns counted from lo, and the split is then balanced in
+    whole units.  The default is the plain split.  Chunks may be empty only if k exceeds the
+    number of units."""
     n = hi - lo
     units = -(-n // unit)
     out = []
@@ -113,7 +115,7 @@ def ffn_backward(p: FfnProblem, dY, lo=0, hi=None):
     return out
 
 
-def coshard_forward(p: FfnProblem, lo, hi, k, unit=16):
+def coshard_forward(p: FfnProblem, lo, hi, k, unit=1):
     """The k sub-operators one after another; their outputs are partial sums and are added."""
     Y = np.zeros((p.T, p.dm))
     for a, b in chunk_ranges(lo, hi, k, unit):
@@ -124,7 +126,7 @@ def coshard_forward(p: FfnProblem, lo, hi, k, unit=16):
     return Y
 
 
-def coshard_backward(p: FfnProblem, dY, lo, hi, k, unit=16):
+def coshard_backward(p: FfnProblem, dY, lo, hi, k, unit=1):
     tot = None
     for a, b in chunk_ranges(lo, hi, k, unit):
         if b <= a:

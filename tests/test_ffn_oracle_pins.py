@@ -101,21 +101,27 @@ def test_closed_forms():
 
 
 def test_chunk_ranges_and_invariant():
-    for lo, hi, k in ((0, 64, 4), (16, 200, 3), (0, 40, 7), (32, 48, 2), (0, 16, 3)):
-        r = orc.chunk_ranges(lo, hi, k)
-        assert len(r) == k and r[0][0] == lo and r[-1][1] == hi
-        assert all(a <= b for a, b in r) and all(r[i][1] == r[i + 1][0] for i in range(k - 1))
-        assert all((a - lo) % 16 == 0 for a, _ in r)
-        sizes = [b - a for a, b in r]
-        assert max(sizes) - min(sizes) <= 16 + (16 - (hi - lo) % 16) % 16
+    # literal values: the plain balanced split, and the same split in whole units of 16 columns
+    assert orc.chunk_ranges(0, 10, 3) == [(0, 3), (3, 6), (6, 10)]
+    assert orc.chunk_ranges(5, 9, 4) == [(5, 6), (6, 7), (7, 8), (8, 9)]
+    assert orc.chunk_ranges(0, 40, 3, unit=16) == [(0, 16), (16, 32), (32, 40)]
+    assert orc.chunk_ranges(16, 200, 3, unit=16) == [(16, 80), (80, 144), (144, 200)]
+    for unit in (1, 16):
+        for lo, hi, k in ((0, 64, 4), (16, 200, 3), (0, 40, 7), (32, 48, 2), (0, 16, 3)):
+            r = orc.chunk_ranges(lo, hi, k, unit)
+            assert len(r) == k and r[0][0] == lo and r[-1][1] == hi
+            assert all(a <= b for a, b in r) and all(r[i][1] == r[i + 1][0] for i in range(k - 1))
+            assert all((a - lo) % unit == 0 for a, _ in r)
+            sizes = [b - a for a, b in r]
+            assert max(sizes) - min(sizes) <= unit + (unit - (hi - lo) % unit) % unit
     p, dY = _problem(6, T=6, dm=8, dh=112)
     for lo, hi in ((0, 112), (16, 100)):
         Y1 = orc.coshard_forward(p, lo, hi, 1)
         assert np.allclose(Y1, orc.ffn_forward(p, lo, hi))
         g1 = orc.coshard_backward(p, dY, lo, hi, 1)
-        for k in (2, 3, 5):
-            assert np.allclose(orc.coshard_forward(p, lo, hi, k), Y1, rtol=1e-12, atol=1e-12)
-            gk = orc.coshard_backward(p, dY, lo, hi, k)
+        for k, unit in ((2, 1), (3, 1), (5, 1), (3, 16), (5, 16)):
+            assert np.allclose(orc.coshard_forward(p, lo, hi, k, unit), Y1, rtol=1e-12, atol=1e-12)
+            gk = orc.coshard_backward(p, dY, lo, hi, k, unit)
             for n in g1:
                 assert np.allclose(gk[n], g1[n], rtol=1e-12, atol=1e-12), (n, k)
 
@@ -128,7 +134,7 @@ def test_planted_mistakes_are_caught():
     H = orc.act(Z, p.kind)
     dH = dY @ p.W2.T
     wrong = {
-        "dW2 with operands swapped": (H.T @ dY).T.shape != g["dW2"].shape or True,
+        "dW2 from the pre-activations instead of the activations": not np.allclose(Z.T @ dY, g["dW2"]),
         "dZ without the activation derivative": not np.allclose(dH @ p.W1.T, g["dX"]),
         "derivative of the erf form instead of the tanh form": not np.allclose(
             (dH * (0.5 * (1 + np.vectorize(__import__("math").erf)(Z / np.sqrt(2)))
