@@ -75,8 +75,12 @@ class DeviceCase:
         ss.ss_attn_fwd(desc, self.Q, self.K, self.V, self.bias, self.region, self.G, self.Y,
                        self.lse if want_lse else None, None, 0, st)
 
-    def bwd(self, desc, use_lse=False, stream=None):
+    def bwd(self, desc, use_lse=False, stream=None, poison=False):
+        """`poison`: fill the workspace with 0xFF bytes (NaN in every float format) first, so that a
+        kernel that reads scratch it has not written in this call shows up in the results."""
         need = self.workspace(desc)
+        if poison:
+            self.ws.fill_(0xFF)
         st = torch.cuda.current_stream(self.dev).cuda_stream if stream is None else stream
         ss.ss_attn_bwd(desc, self.Q, self.K, self.V, self.bias, self.region, self.G, self.dY,
                        self.lse if use_lse else None, self.dQ, self.dK, self.dV, self.dBias, self.dG,
@@ -143,13 +147,17 @@ class FfnCase:
             self.ws = torch.empty(need, dtype=torch.uint8, device=self.dev)
         return f, b
 
-    def fwd(self, desc):
+    def fwd(self, desc, poison=False):
         self.workspace(desc)
+        if poison:
+            self.ws.fill_(0xFF)
         st = torch.cuda.current_stream(self.dev).cuda_stream
         self.fb.ss_ffn_fwd(desc, self.X, self.W1, self.b1, self.W2, self.b2, self.Y, self.ws, self.ws.numel(), st)
 
-    def bwd(self, desc):
+    def bwd(self, desc, poison=False):
         self.workspace(desc)
+        if poison:
+            self.ws.fill_(0xFF)
         st = torch.cuda.current_stream(self.dev).cuda_stream
         self.fb.ss_ffn_bwd(desc, self.X, self.W1, self.b1, self.W2, self.dY, self.dX, self.dW1, self.db1, self.dW2,
                            self.db2, self.ws, self.ws.numel(), st)

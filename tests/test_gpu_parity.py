@@ -119,7 +119,9 @@ def test_rising_scores_raise_the_running_maximum(name):
     n = cfg["H"] if cfg["axis"] == "head" else cfg["B"]
     for k in (1, min(n, 2)):
         print(f"case {name} rising scores k={k}", flush=True)
-        check_against_oracle(cfg, k=k, inputs=inp)
+        # keys that differ by a factor of eight make output rows differ as much in magnitude, and the
+        # element-wise bar is taken from the whole tensor's rms: more near-zero entries of the large rows miss it
+        check_against_oracle(cfg, k=k, inputs=inp, elem_fail_max=1e-3)
 
 
 @pytest.mark.parametrize("name", ["long_seq_few_heads", "long_seq_bias_d64", "gpt_like", "tri_like", "swin_like"])
