@@ -43,7 +43,8 @@ enum {
   SS_ERR_BAD_K = -4,       /* k < 1 or k > hi-lo                                       */
   SS_ERR_UNSUPPORTED = -5, /* no kernel for this dtype / D / S / bias / mask / flags   */
   SS_ERR_WORKSPACE = -6,   /* workspace NULL, too small, or not 256-byte aligned       */
-  SS_ERR_HIP = -7          /* a kernel launch failed (hipGetLastError text on stderr)  */
+  SS_ERR_HIP = -7,         /* a kernel launch failed (hipGetLastError text on stderr)  */
+  SS_ERR_STATIC_SCRATCH = -8 /* ss_attn_bwd_static: the share needs more than its buffer */
 };
 
 /* desc.flags */
@@ -139,6 +140,22 @@ int ss_attn_bwd(const ss_attn_desc* desc, const void* Q, const void* K, const vo
                 const void* dY, const float* lse,
                 void* dQ, void* dK, void* dV, float* dBias, void* dG,
                 void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* The backward for callers that cannot allocate device memory and have no workspace to hand
+ * over: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same arguments, results and kernels as ss_attn_bwd, but the scratch is a buffer built into
+ * the library (SS_ATTN_STATIC_SCRATCH_BYTES of device memory per GPU the library is used on,
+ * held until the process ends) instead of a caller workspace.  The call allocates and frees
+ * nothing.  A share whose ss_attn_workspace_bytes backward figure exceeds the buffer is
+ * rejected with SS_ERR_STATIC_SCRATCH before anything is enqueued (raise k, or use
+ * ss_attn_bwd).  Every call on one GPU shares that GPU's buffer: two calls that may run at
+ * the same time on one GPU (different streams or threads) race; calls on one stream are safe.
+ * The buffer keeps the previous call's contents; no part of it needs to start at zero. */
+#define SS_ATTN_STATIC_SCRATCH_BYTES (32u << 20)
+int ss_attn_bwd_static(const ss_attn_desc* desc, const void* Q, const void* K, const void* V,
+                       const void* bias, const int32_t* region_ids, const void* G,
+                       const void* dY, const float* lse,
+                       void* dQ, void* dK, void* dV, float* dBias, void* dG, void* hip_stream);
 
 /* Static text for an error code (never NULL). */
 const char* ss_strerror(int code);

@@ -19,9 +19,11 @@ SS_BIAS_NONE, SS_BIAS_DENSE, SS_BIAS_RELPOS = 0, 1, 2
 SS_FLAG_GENERIC_KERNELS = 1
 SS_OK = 0
 SS_ERR_NULL, SS_ERR_BAD_SHAPE, SS_ERR_BAD_RANGE, SS_ERR_BAD_K = -1, -2, -3, -4
-SS_ERR_UNSUPPORTED, SS_ERR_WORKSPACE, SS_ERR_HIP = -5, -6, -7
+SS_ERR_UNSUPPORTED, SS_ERR_WORKSPACE, SS_ERR_HIP, SS_ERR_STATIC_SCRATCH = -5, -6, -7, -8
+SS_ATTN_STATIC_SCRATCH_BYTES = 32 << 20
 
-EXPORTS = ("ss_attn_workspace_bytes", "ss_attn_chunk_range", "ss_attn_fwd", "ss_attn_bwd", "ss_strerror",
+EXPORTS = ("ss_attn_workspace_bytes", "ss_attn_chunk_range", "ss_attn_fwd", "ss_attn_bwd", "ss_attn_bwd_static",
+           "ss_strerror",
            "ss_attn_kernel_family", "ss_attn_profile_enable", "ss_attn_profile_read")
 SS_K_FWD, SS_K_RECOMPUTE, SS_K_DQ, SS_K_DKDV, SS_K_DBIAS, SS_K_TABLE_REDUCE, SS_K_DQ_DKDV, SS_K_COUNT = range(8)
 KERNEL_NAMES = ("fwd", "recompute", "dq", "dkdv", "dbias", "table_reduce", "dq_dkdv")
@@ -67,6 +69,8 @@ def lib():
         L.ss_attn_fwd.restype = C.c_int
         L.ss_attn_bwd.argtypes = [P, V, V, V, V, V, V, V, V, V, V, V, V, V, V, C.c_size_t, V]
         L.ss_attn_bwd.restype = C.c_int
+        L.ss_attn_bwd_static.argtypes = [P, V, V, V, V, V, V, V, V, V, V, V, V, V, V]
+        L.ss_attn_bwd_static.restype = C.c_int
         L.ss_attn_kernel_family.argtypes = [P]
         L.ss_attn_kernel_family.restype = C.c_char_p
         L.ss_attn_profile_enable.argtypes = [C.c_int]
@@ -133,6 +137,13 @@ def ss_attn_bwd(desc, Q, K, V, bias, region_ids, G, dY, lse, dQ, dK, dV, dBias, 
                            _ptr(workspace), workspace_bytes, stream)
     if rc != SS_OK:
         raise SSAttnError(rc, "ss_attn_bwd")
+
+
+def ss_attn_bwd_static(desc, Q, K, V, bias, region_ids, G, dY, lse, dQ, dK, dV, dBias, dG, stream):
+    rc = lib().ss_attn_bwd_static(C.byref(desc), _ptr(Q), _ptr(K), _ptr(V), _ptr(bias), _ptr(region_ids), _ptr(G),
+                                  _ptr(dY), _ptr(lse), _ptr(dQ), _ptr(dK), _ptr(dV), _ptr(dBias), _ptr(dG), stream)
+    if rc != SS_OK:
+        raise SSAttnError(rc, "ss_attn_bwd_static")
 
 
 def ss_attn_kernel_family(desc: ss_attn_desc):

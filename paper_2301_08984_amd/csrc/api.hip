@@ -6,7 +6,13 @@
 #include "kparams.h"
 
 #include <cstdio>
+#include <mutex>
 #include <vector>
+
+// Built-in scratch of ss_attn_bwd_static: one copy per GPU the library runs on, held until the
+// process ends.  Host code never uses this name as an address: it asks the runtime for the
+// device address once per device (static_scratch below) and passes that pointer on.
+static __device__ __align__(256) unsigned char scratch[SS_ATTN_STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -123,6 +129,32 @@ inline void set_chunk(KP& p, const ss_attn_desc* d, int c) {
   else { p.b0 = a; p.b1 = b; p.h0 = 0; p.h1 = d->H; }
 }
 
+// Device address of this GPU's copy of `scratch`, looked up on the first call per device.
+constexpr int MAX_DEVICES = 64;
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[MAX_DEVICES] = {nullptr};
+
+int static_scratch(void** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess || dev < 0 || dev >= MAX_DEVICES) {
+    fprintf(stderr, "ss_attn: hipGetDevice: %s (device %d)\n", hipGetErrorString(e), dev);
+    return SS_ERR_HIP;
+  }
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !ptr) {
+      fprintf(stderr, "ss_attn: hipGetSymbolAddress(scratch): %s\n", hipGetErrorString(e));
+      return SS_ERR_HIP;
+    }
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return SS_OK;
+}
+
 int hip_fail(hipError_t e, const char* what) {
   fprintf(stderr, "ss_attn: %s: %s\n", what, hipGetErrorString(e));
   return SS_ERR_HIP;
@@ -171,6 +203,7 @@ const char* ss_strerror(int code) {
     case SS_ERR_UNSUPPORTED: return "unsupported dtype / head size / bias / mask / flags";
     case SS_ERR_WORKSPACE: return "workspace missing, too small or not 256-byte aligned";
     case SS_ERR_HIP: return "HIP kernel launch failed";
+    case SS_ERR_STATIC_SCRATCH: return "the backward needs more scratch than the built-in buffer of ss_attn_bwd_static holds";
     default: return "unknown error code";
   }
 }
@@ -250,6 +283,21 @@ int ss_attn_fwd(const ss_attn_desc* d, const void* Q, const void* K, const void*
     else SS_LAUNCH(SS_K_FWD, ssa::launch_generic_fwd(p, bf16, false, st), "forward (generic)");
   }
   return SS_OK;
+}
+
+int ss_attn_bwd_static(const ss_attn_desc* d, const void* Q, const void* K, const void* V, const void* bias,
+                       const int32_t* region_ids, const void* G, const void* dY, const float* lse, void* dQ,
+                       void* dK, void* dV, float* dBias, void* dG, void* hip_stream) {
+  const int rc = validate(d);
+  if (rc != SS_OK) return rc;
+  if (bwd_layout(d, family_of(d)).total > (size_t)SS_ATTN_STATIC_SCRATCH_BYTES) return SS_ERR_STATIC_SCRATCH;
+  void* ptr = nullptr;
+  const int rs = static_scratch(&ptr);
+  if (rs != SS_OK) return rs;
+  // nothing in the backward relies on scratch that starts at zero: every region is written by
+  // the call before it is read, so the previous call's contents need no clearing
+  return ss_attn_bwd(d, Q, K, V, bias, region_ids, G, dY, lse, dQ, dK, dV, dBias, dG, ptr,
+                     (size_t)SS_ATTN_STATIC_SCRATCH_BYTES, hip_stream);
 }
 
 int ss_attn_bwd(const ss_attn_desc* d, const void* Q, const void* K, const void* V, const void* bias,

@@ -85,8 +85,20 @@ def test_null_and_workspace_errors_enqueue_nothing():
     g = _desc(gated=True)
     assert L.ss_attn_fwd(C.byref(g), one, one, one, None, None, None, one, None, None, 0, None) == ss.SS_ERR_NULL
     assert L.ss_attn_workspace_bytes(None, None, None) == ss.SS_ERR_NULL
-    for code in range(-8, 1):
+    for code in range(-9, 1):
         assert ss.ss_strerror(code)
+
+
+def test_share_beyond_the_built_in_buffer_is_rejected():
+    """Validation only: nothing is enqueued, no pointer is dereferenced."""
+    d = ss.make_desc(1024, 4, 1024, 32, ss.SS_BF16, 0.17, ss.SS_AXIS_ROW, 0, 1024, 4, bias_kind=ss.SS_BIAS_DENSE,
+                     gated=True)
+    _, need = ss.ss_attn_workspace_bytes(d)
+    assert need > ss.SS_ATTN_STATIC_SCRATCH_BYTES
+    one = 256
+    rc = ss.lib().ss_attn_bwd_static(C.byref(d), one, one, one, one, None, one, one, None, one, one, one, None, one, None)
+    assert rc == ss.SS_ERR_STATIC_SCRATCH
+    assert "built-in" in ss.ss_strerror(rc)
 
 
 def test_chunk_ranges_match_the_plan_rule():
