@@ -22,11 +22,30 @@ sys.path.insert(0, ROOT)
 
 PEAK_MFMA_BF16 = 2.5e15  # dense bf16 FLOP/s, MI355X
 PEAK_HBM = 8.0e12        # B/s
-# which published roofline bounds the dominant kernel of each workload
-BOUND = {"gpt3_shard": "mfma", "gpt3_long": "mfma", "swin_window": "hbm", "af2_msa_row": "hbm", "af2_triangle": "hbm",
-         "af2_msa_col": "hbm", "af2_triangle_end": "hbm", "tiny_mha": "hbm"}
-# contractions (each 2*D flop per visible score element) a kernel performs
-CONTRACTIONS = {"fwd": 2, "recompute": 2, "dq": 3, "dkdv": 4, "dbias": 2, "table_reduce": 0, "dq_dkdv": 7}
+# Vector-ALU peak in lane-operations per second: 256 compute units x 4 SIMDs x 16 lanes x 2.4 GHz (one
+# fp32 instruction of a 64-wide wavefront occupies its SIMD for 4 cycles).  This is half of the 78.6
+# TFLOP/s fp32 vector figure (which counts an fma as two flops) and a quarter of 157.3 (packed fp32,
+# which this build does not emit); transcendental instructions (exp2, rcp) run at a quarter of it.
+PEAK_VALU_LANEOPS = 256 * 64 * 2.4e9
+# which roofline bounds the dominant kernel of each workload: the D = 128 shapes are matrix-core
+# work; at D = 32 a score element costs 2-3 matrix steps but the same softmax arithmetic, so the vector
+# ALUs (exp2 above all) bind and the HBM fraction is reported beside it; the window shape moves its
+# activations in 64-byte pieces and is nearest to the HBM roof
+BOUND = {"gpt3_shard": "mfma", "gpt3_long": "mfma", "swin_window": "hbm", "af2_msa_row": "alu", "af2_triangle": "alu",
+         "af2_msa_col": "alu", "af2_triangle_end": "alu", "tiny_mha": "hbm"}
+# Contractions (each 2*D flop per visible score element) of the METHOD that a kernel stands for: the
+# forward has 2 (scores, value product), the backward 5 (scores, dP, dV, dK, dQ); where the backward
+# is two kernels the scores and dP are counted once, half with each; the recompute pass and the score
+# recompute of the bias-gradient kernel are not part of the method's count.
+CONTRACTIONS = {"fwd": 2, "recompute": 0, "dq": 2, "dkdv": 3, "dbias": 0, "table_reduce": 0, "dq_dkdv": 5}
+# contractions a kernel actually executes on the matrix cores (scores and dP are formed again by
+# every kernel that needs them)
+EXECUTED = {"fwd": 2, "recompute": 2, "dq": 3, "dkdv": 4, "dbias": 2, "table_reduce": 0, "dq_dkdv": 7}
+# Vector-ALU lane-operations per visible score element that the method needs at least, quarter-rate
+# instructions counted as 4: forward = scale/bias fma 1 + running max 1 + exp2 4 + row sum 1 + bf16
+# conversion 1 = 8; backward = score fma 1 + exp2 4 + (dP - Delta) 1 + times P 1 + two conversions 2
+# = 9, + 1 for the bias-gradient addition.  Recomputation is not counted.
+VALU_SLOTS = {"fwd": 8, "recompute": 0, "dq": 4.5, "dkdv": 4.5, "dbias": 1, "table_reduce": 0, "dq_dkdv": 9}
 
 
 def visible_fraction(w):
@@ -39,9 +58,14 @@ def job_flops(w):
     return 14.0 * E * w["D"] * visible_fraction(w)
 
 
-def kernel_flops(w, name, units, axis_extent):
+def kernel_flops(w, name, units, axis_extent, table=CONTRACTIONS):
     E = w["B"] * w["H"] * w["S"] ** 2 * (units / axis_extent)
-    return 2.0 * CONTRACTIONS[name] * E * w["D"] * visible_fraction(w)
+    return 2.0 * table[name] * E * w["D"] * visible_fraction(w)
+
+
+def kernel_laneops(w, name, units, axis_extent):
+    E = w["B"] * w["H"] * w["S"] ** 2 * (units / axis_extent) * visible_fraction(w)
+    return VALU_SLOTS[name] * E
 
 
 def kernel_bytes(w, name, units, axis_extent):
@@ -252,8 +276,16 @@ def main():
     ks = list(w["k"])
     k_main = a.k if a.k is not None else (ks[1] if len(ks) > 1 else ks[0])
     ss.lib()  # fail loudly if the HIP library is missing
-    dc = DeviceCase(make_inputs(**w), dtype=w["dtype"], bias=w["bias"], mask=w["mask"], gated=w["gated"],
+    host_inputs = make_inputs(**w)
+    torch.zeros(1, device="cuda:0")   # context and allocator set up before the first memory reading
+    torch.cuda.synchronize()
+    free0 = torch.cuda.mem_get_info()[0]
+    dc = DeviceCase(host_inputs, dtype=w["dtype"], bias=w["bias"], mask=w["mask"], gated=w["gated"],
                     win=w.get("win"), fill=0.0, layout=w.get("layout", "bshd"))
+    del host_inputs
+    torch.cuda.synchronize()
+    torch.cuda.empty_cache()   # staging copies of the upload go back to the driver
+    caller_measured = free0 - torch.cuda.mem_get_info()[0]
     desc = dc.desc(w["axis"], 0, ext, k_main)
     family = ss.ss_attn_kernel_family(desc)
     dc.workspace(desc)
@@ -273,12 +305,17 @@ def main():
     for _ in range(a.warmup):
         step(desc)
     torch.cuda.synchronize()
+    # the library enqueues on torch's current stream, so events recorded there bracket each step
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(a.steps + 1)]
     t0 = time.perf_counter()
-    for _ in range(a.steps):
+    marks[0].record()
+    for i in range(a.steps):
         step(desc)
+        marks[i + 1].record()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     ms = dt / a.steps * 1e3
+    per_step = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(a.steps))
     value = job_flops(w) / (ms * 1e-3) / 1e12
 
     out = {
@@ -291,6 +328,8 @@ def main():
                    "bias": w["bias"], "mask": w["mask"], "gated": w["gated"], "shard_axis": w["axis"],
                    "k": k_main, "kernels": family},
         "pct_mfma_peak": 100.0 * value * 1e12 / PEAK_MFMA_BF16,
+        # per-step durations between events on the launch stream (the value above is wall clock over all K)
+        "ms_per_step_median": per_step[len(per_step) // 2], "ms_per_step_min": per_step[0],
     }
 
     if not a.no_extras:
@@ -309,14 +348,23 @@ def main():
         dom = max(per_kernel, key=lambda n: per_kernel[n]["ms_per_step"])
         units = ext / k_main
         dur = per_kernel[dom]["avg_us"] * 1e-6
+        gbs = kernel_bytes(w, dom, units, ext) / dur / 1e9
+        tfs = kernel_flops(w, dom, units, ext) / dur / 1e12
         if BOUND[a.workload] == "mfma":
-            ach = kernel_flops(w, dom, units, ext) / dur / 1e12
-            roof = {"bound": "mfma", "achieved": ach, "peak": PEAK_MFMA_BF16 / 1e12, "unit": "TFLOP/s",
-                    "frac": ach * 1e12 / PEAK_MFMA_BF16, "traffic": None}
+            roof = {"bound": "mfma", "achieved": tfs, "peak": PEAK_MFMA_BF16 / 1e12, "unit": "TFLOP/s",
+                    "frac": tfs * 1e12 / PEAK_MFMA_BF16, "traffic": None}
+        elif BOUND[a.workload] == "alu":
+            ach = kernel_laneops(w, dom, units, ext) / dur / 1e12
+            roof = {"bound": "alu", "achieved": ach, "peak": PEAK_VALU_LANEOPS / 1e12, "unit": "Tlane-op/s",
+                    "frac": ach * 1e12 / PEAK_VALU_LANEOPS, "traffic": None}
         else:
-            ach = kernel_bytes(w, dom, units, ext) / dur / 1e9
-            roof = {"bound": "hbm", "achieved": ach, "peak": PEAK_HBM / 1e9, "unit": "GB/s",
-                    "frac": ach * 1e9 / PEAK_HBM, "traffic": None}
+            roof = {"bound": "hbm", "achieved": gbs, "peak": PEAK_HBM / 1e9, "unit": "GB/s",
+                    "frac": gbs * 1e9 / PEAK_HBM, "traffic": None}
+        # the other two fractions of the same kernel, for context: algorithmic bytes against HBM, the
+        # method's contractions against the matrix cores, and the contractions the kernel executes
+        roof["hbm_frac"] = gbs * 1e9 / PEAK_HBM
+        roof["mfma_frac"] = tfs * 1e12 / PEAK_MFMA_BF16
+        roof["mfma_issue_frac"] = kernel_flops(w, dom, units, ext, EXECUTED) / dur / PEAK_MFMA_BF16
         # HBM bytes per launch of that kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
         # same command (calibrated by a known-size copy), recorded under profiles/
         try:
@@ -330,15 +378,23 @@ def main():
         out["kernels"] = per_kernel
 
         # throughput, workspace and peak HBM bytes for every co-shard factor of the workload
+        # "measured" = what hipMemGetInfo (through torch) says the device lost: the caller tensors once, the
+        # workspace per k (allocated alone after the allocator's cache was emptied; the allocator
+        # rounds blocks up, 2 MiB granularity for large ones, so the reading sits a little above the exact figure)
         table = []
         caller = dc.caller_bytes()
         for k in ([] if a.no_per_k else sorted(set(ks) | {k_main})):
             d = dc.desc(w["axis"], 0, ext, k)
             _, wsb = ss.ss_attn_workspace_bytes(d)
+            dc.ws = None
+            torch.cuda.synchronize()
+            torch.cuda.empty_cache()
+            f0 = torch.cuda.mem_get_info()[0]
             dc.workspace(d)
             for _ in range(3):
                 step(d)
             torch.cuda.synchronize()
+            ws_measured = f0 - torch.cuda.mem_get_info()[0]
             n = max(5, a.steps // 5)
             t0 = time.perf_counter()
             for _ in range(n):
@@ -349,6 +405,7 @@ def main():
             sxs = chunk_units * (w["B"] * w["H"] / ext) * w["S"] ** 2 * 2
             table.append({"k": k, "ms_per_step": t * 1e3, "tflops": job_flops(w) / t / 1e12,
                           "workspace_bytes": wsb, "peak_hbm_bytes": caller + wsb,
+                          "measured_peak_hbm_bytes": caller_measured + ws_measured,
                           "unfused_scores_bytes_per_chunk": int(sxs)})
         out["per_k"] = table
 
