@@ -188,18 +188,23 @@ def ffn_main(a):
     for _ in range(a.warmup):
         step(desc)
     torch.cuda.synchronize()
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(a.steps + 1)]
     t0 = time.perf_counter()
-    for _ in range(a.steps):
+    marks[0].record()
+    for i in range(a.steps):
         step(desc)
+        marks[i + 1].record()
     torch.cuda.synchronize()
     ms = (time.perf_counter() - t0) / a.steps * 1e3
+    per_step = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(a.steps))
     value = flops / (ms * 1e-3) / 1e12
     out = {"metric": "feed-forward fwd+bwd TFLOP/s (1 GPU) + % MFMA peak; peak HBM bytes vs co-shard k",
            "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": ms,
            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
            "config": {"workload": a.workload, "T": w["T"], "d_model": w["dm"], "hidden_share": nh, "act": w["act"],
                       "k": k_main},
-           "pct_mfma_peak": 100.0 * value * 1e12 / PEAK_MFMA_BF16}
+           "pct_mfma_peak": 100.0 * value * 1e12 / PEAK_MFMA_BF16,
+           "ms_per_step_median": per_step[len(per_step) // 2], "ms_per_step_min": per_step[0]}
     if not a.no_extras:
         fb.ss_ffn_profile_enable(True)
         for _ in range(a.steps):

@@ -11,19 +11,25 @@
  * dimension, Section 3.1; op-assign to one device and op-order, Section 3.2).  The share is the
  * hidden range [lo,hi).  Unlike the head split of attention every sub-operator contributes to the
  * whole output: Y and dX are value-split partial sums (Section 4; Section 5 for the gradient of
- * the shared input) which the library accumulates in fp32 in the workspace, in an order that does
- * not depend on k; dW1, db1 and dW2 are disjoint slices.  Only one chunk's hidden activations
- * [T, (hi-lo)/k] are alive at a time, and the backward recomputes them (Sections 2 and 6.3).
+ * the shared input).  By default the partial sum between chunks lives in the output tensor itself
+ * (bf16: every chunk's product is accumulated in fp32 on top of the widened partial sum and rounded
+ * once per chunk), so the workspace holds one chunk's hidden activations and nothing else, and
+ * shrinks as 1/k: the point of the plan (Sections 2 and 6.3).  Y and dX then carry one bf16
+ * rounding per chunk and differ between k in the last bits.  With SS_FFN_FLAG_EXACT_SUM the partial
+ * sum is kept in fp32 in the workspace instead (4 T dm more bytes for k > 1, more than the hidden
+ * activations the split frees when hi-lo < 2 dm) and Y and dX are the same bits for every k.
+ * dW1, db1, dW2 and db2 are disjoint slices or whole-operator sums and never depend on k.  Only one
+ * chunk's hidden activations [T, (hi-lo)/k] are alive at a time, and the backward recomputes them.
  *
  * All pointers are DEVICE pointers unless said otherwise; the descriptor and size outputs are HOST
  * memory.  The library allocates no device memory and never synchronises the host; the work is
  * enqueued on the caller's stream, except that ss_ffn_bwd forks dW2 and the bias gradients onto a
  * helper stream of the library's own (one per device, default priority, created on first use) and
  * joins it back into the caller's stream with events before the call returns: to the caller the
- * call is ordered on its stream like any other.  SS_FFN_ONE_STREAM=1 in the environment keeps
- * everything on the caller's stream.  The helper stream is shared by all calls on a device: calls
- * from several host threads, or on several streams of one device at once, must be serialised by
- * the caller.  Error codes are those of ss_attn.h.
+ * call is ordered on its stream like any other.  That stream is the only state the library keeps;
+ * the fork / join events are created and released per call, so calls from several host threads or
+ * on several caller streams of one device are independent (their helper work is merely queued on
+ * the same helper stream).  Error codes are those of ss_attn.h.
  */
 #ifndef SS_FFN_H
 #define SS_FFN_H
@@ -54,19 +60,24 @@ typedef struct {
   int64_t ld_x, ld_w1, ld_w2;
   int32_t lo, hi; /* this GPU's hidden range */
   int32_t k;      /* co-shard factor, 1 <= k <= ceil((hi-lo)/16) */
-  int32_t flags;  /* 0 */
+  int32_t flags;  /* 0 or SS_FFN_FLAG_EXACT_SUM */
 } ss_ffn_desc;
 
-/* Workspace bytes ss_ffn_fwd / ss_ffn_bwd need (host outputs).  Forward: one chunk's H plus, for
- * k > 1, the fp32 accumulator of Y.  Backward: one chunk's H and act'(Z) (overwritten by dZ) plus,
- * for k > 1, the fp32 accumulator of dX.  The hidden-activation part shrinks with k. */
+enum {
+  SS_FFN_FLAG_EXACT_SUM = 1 /* fp32 partial sums of Y / dX in the workspace: identical bits for every k */
+};
+
+/* Workspace bytes ss_ffn_fwd / ss_ffn_bwd need (host outputs).  Forward: one chunk's H.  Backward:
+ * one chunk's H and act'(Z) (overwritten by dZ).  Both shrink as 1/k.  With SS_FFN_FLAG_EXACT_SUM
+ * and k > 1 the fp32 accumulator of Y (forward) or dX (backward) is added. */
 int ss_ffn_workspace_bytes(const ss_ffn_desc* desc, size_t* fwd_bytes, size_t* bwd_bytes);
 
 /* Hidden range of chunk c (0 <= c < k): balanced in units of 16 columns counted from lo. */
 int ss_ffn_chunk_range(const ss_ffn_desc* desc, int32_t c, int32_t* lo, int32_t* hi);
 
 /* Y = sum over the share's chunks of act(X W1[:,c] + b1[c]) W2[c,:], plus b2 if b2 != NULL.
- * Y is written once, by the last chunk.  workspace: 256-byte aligned, >= fwd_bytes. */
+ * Y holds the partial sum between chunks (written once, by the last chunk, with
+ * SS_FFN_FLAG_EXACT_SUM).  workspace: 256-byte aligned, >= fwd_bytes. */
 int ss_ffn_fwd(const ss_ffn_desc* desc, const void* X, const void* W1, const void* b1, const void* W2, const void* b2,
                void* Y, void* workspace, size_t workspace_bytes, void* stream);
 

@@ -270,7 +270,7 @@ __global__ __launch_bounds__(64 * NG) __attribute__((amdgpu_waves_per_eu(2, 2)))
 
 template <int D, bool RECOMP>
 hipError_t fwd_wave_r(const KP& p, hipStream_t st) {
-  constexpr int NG = 4;
+  constexpr int NG = 8;
   const dim3 g((p.S + 31) / 32, p.h1 - p.h0, p.b1 - p.b0);
   const bool bias = p.bias_kind == 1, causal = p.mask_kind == 1;
   if (bias && causal) fwd_wave_kernel<D, true, true, RECOMP, NG><<<g, 64 * NG, 0, st>>>(p);

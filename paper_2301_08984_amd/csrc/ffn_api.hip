@@ -3,7 +3,7 @@
 #include "../../include/ss_ffn.h"
 
 #include <cstdio>
-#include <cstdlib>
+#include <mutex>
 
 #include "ffn_kernels.h"
 
@@ -18,7 +18,8 @@ int validate(const ss_ffn_desc* d) {
   if (d->T < 1 || d->dm < 8 || d->dh < 8 || (d->dm & 7) || (d->dh & 7)) return SS_ERR_BAD_SHAPE;
   if (d->ld_x < d->dm || d->ld_w1 < d->dh || d->ld_w2 < d->dm || (d->ld_x & 7) || (d->ld_w1 & 7) || (d->ld_w2 & 7))
     return SS_ERR_BAD_SHAPE;
-  if (d->dtype != SS_BF16 || (d->act != SS_ACT_RELU && d->act != SS_ACT_GELU_TANH) || d->flags != 0)
+  if (d->dtype != SS_BF16 || (d->act != SS_ACT_RELU && d->act != SS_ACT_GELU_TANH) ||
+      (d->flags & ~(int32_t)SS_FFN_FLAG_EXACT_SUM))
     return SS_ERR_UNSUPPORTED;
   if (d->lo < 0 || d->lo >= d->hi || d->hi > d->dh || (d->lo & 7) || (d->hi & 7)) return SS_ERR_BAD_RANGE;
   const int units = (d->hi - d->lo + UNIT - 1) / UNIT;
@@ -56,7 +57,9 @@ Ws layout(const ss_ffn_desc* d, bool backward) {
   size_t off = 0;
   w.H = off; off += hb;
   w.D = off; if (backward) off += hb;
-  w.acc = off; if (d->k > 1) off += align256(ssa::gemm_acc_bytes(d->T, d->dm));
+  // the fp32 partial sum between chunks exists only when the caller asks for sums that do not depend
+  // on k bit for bit; otherwise the partial sum lives in the output tensor itself
+  w.acc = off; if (d->k > 1 && (d->flags & SS_FFN_FLAG_EXACT_SUM)) off += align256(ssa::gemm_acc_bytes(d->T, d->dm));
   w.total = off;
   return w;
 }
@@ -101,36 +104,52 @@ void drain() {
       Prof ps_(stream_, kind);                       \
       e_ = (expr);                                   \
     }                                                \
-    if (e_ != hipSuccess) return hip_fail(e_, what); \
+    if (e_ != hipSuccess) {                          \
+      FF_ON_ERROR;                                   \
+      return hip_fail(e_, what);                     \
+    }                                                \
   } while (0)
+#define FF_ON_ERROR ((void)0)
 #define FF_LAUNCH(kind, expr, what) FF_LAUNCH_ON(st, kind, expr, what)
 
-// A helper stream per device (default priority, created on first use, kept until the process ends):
-// dW2 = H^T dY needs only H, and the bias gradients only dY or dZ, so they are forked onto the helper
-// stream, run beside the products of the caller's stream -- dZ = (dY W2^T) act'(Z) has too few tiles
-// to fill the chip -- and are joined back before the next chunk overwrites H and dZ, and before the
-// call returns.
+// A helper stream per device (default priority, created on first use under a lock, kept until the
+// process ends): dW2 = H^T dY needs only H, and the bias gradients only dY or dZ, so they are forked
+// onto the helper stream, run beside the products of the caller's stream -- dZ = (dY W2^T) act'(Z)
+// has too few tiles to fill the chip -- and are joined back before the next chunk overwrites H and
+// dZ, and before the call returns.  The fork and join events belong to ONE call (created when it
+// starts, released when it returns; the runtime keeps a released event alive until the work that
+// waits on it has passed), so calls from several host threads or on several caller streams share
+// nothing but the helper stream, on which each call's launches are ordered after its own fork.
+std::mutex g_side_mu;
+hipStream_t g_side_stream[64] = {nullptr};
+int g_side_state[64] = {0};  // 0 not tried, 1 ready, -1 unavailable
+hipStream_t side_stream() {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
+  std::lock_guard<std::mutex> lock(g_side_mu);
+  if (g_side_state[dev] == 0) {
+    g_side_state[dev] = hipStreamCreateWithFlags(&g_side_stream[dev], hipStreamNonBlocking) == hipSuccess ? 1 : -1;
+    (void)hipGetLastError();
+  }
+  return g_side_state[dev] == 1 ? g_side_stream[dev] : nullptr;
+}
+// the fork / join events of one ss_ffn_bwd call
 struct Side {
   hipStream_t s = nullptr;
   hipEvent_t fork = nullptr, join = nullptr;
-  int state = 0;  // 0 not tried, 1 ready, -1 unavailable
-};
-Side g_side[64];
-Side* side_stream() {
-  int dev = 0;
-  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
-  Side& sd = g_side[dev];
-  if (sd.state == 0) {
-    const char* off = std::getenv("SS_FFN_ONE_STREAM");
-    sd.state = -1;
-    if (!(off && off[0] == '1') && hipStreamCreateWithFlags(&sd.s, hipStreamNonBlocking) == hipSuccess &&
-        hipEventCreateWithFlags(&sd.fork, hipEventDisableTiming) == hipSuccess &&
-        hipEventCreateWithFlags(&sd.join, hipEventDisableTiming) == hipSuccess)
-      sd.state = 1;
-    (void)hipGetLastError();
+  bool ok = false;
+  explicit Side(bool want) {
+    if (!want) return;
+    s = side_stream();
+    ok = s && hipEventCreateWithFlags(&fork, hipEventDisableTiming) == hipSuccess &&
+         hipEventCreateWithFlags(&join, hipEventDisableTiming) == hipSuccess;
+    if (!ok) (void)hipGetLastError();
   }
-  return sd.state == 1 ? &sd : nullptr;
-}
+  ~Side() {
+    if (fork) (void)hipEventDestroy(fork);
+    if (join) (void)hipEventDestroy(join);
+  }
+};
 
 ssa::GemmArgs gemm(const void* A, int64_t lda, const void* B, int64_t ldb, int M, int N, int K) {
   ssa::GemmArgs g{};
@@ -172,6 +191,7 @@ int ss_ffn_fwd(const ss_ffn_desc* d, const void* X, const void* W1, const void* 
   char* ws = (char*)workspace;
   const uint16_t* W1p = (const uint16_t*)W1;
   const uint16_t* W2p = (const uint16_t*)W2;
+  const bool exact = (d->flags & SS_FFN_FLAG_EXACT_SUM) != 0 || d->k == 1;
   for (int c = 0; c < d->k; ++c) {
     int a, b;
     chunk(d, c, &a, &b);
@@ -184,8 +204,8 @@ int ss_ffn_fwd(const ss_ffn_desc* d, const void* X, const void* W1, const void* 
     // Y += H_c W2[a:b, :]; the last chunk adds b2 and writes Y
     ssa::GemmArgs dn = gemm(ws + w.H, w.ldh, W2p + (int64_t)a * d->ld_w2, d->ld_w2, d->T, d->dm, nc);
     dn.acc32 = (float*)(ws + w.acc); dn.accumulate = c > 0; dn.last = c == d->k - 1;
-    dn.bias = (const uint16_t*)b2; dn.out = (uint16_t*)Y; dn.ldo = d->ld_x;
-    FF_LAUNCH(SS_FK_DOWN, ssa::launch_gemm(dn, false, false, ssa::EPI_ACC, st), "Y += H W2");
+    dn.bias = dn.last ? (const uint16_t*)b2 : nullptr; dn.out = (uint16_t*)Y; dn.ldo = d->ld_x;
+    FF_LAUNCH(SS_FK_DOWN, ssa::launch_gemm(dn, false, false, exact ? ssa::EPI_ACC : ssa::EPI_ACC16, st), "Y += H W2");
   }
   return SS_OK;
 }
@@ -204,7 +224,9 @@ int ss_ffn_bwd(const ss_ffn_desc* d, const void* X, const void* W1, const void* 
   const uint16_t* W2p = (const uint16_t*)W2;
   uint16_t* Hc = (uint16_t*)(ws + w.H);
   uint16_t* Dc = (uint16_t*)(ws + w.D);
-  Side* side = g_on ? nullptr : side_stream();  // per-kernel timing wants the kernels one at a time
+  const bool exact = (d->flags & SS_FFN_FLAG_EXACT_SUM) != 0 || d->k == 1;
+  Side side_obj(!g_on);  // per-kernel timing wants the kernels one at a time
+  Side* side = side_obj.ok ? &side_obj : nullptr;
   bool pending = false;  // work on the helper stream that the caller's stream has not waited for yet
   // run `launch` on the helper stream after everything enqueued on the caller's stream so far
   auto fork = [&]() {
@@ -216,6 +238,9 @@ int ss_ffn_bwd(const ss_ffn_desc* d, const void* X, const void* W1, const void* 
     const hipError_t e = hipEventRecord(side->join, side->s);
     return e != hipSuccess ? e : hipStreamWaitEvent(st, side->join, 0);
   };
+  // a failed launch still leaves the caller's stream ordered after whatever runs on the helper stream
+#undef FF_ON_ERROR
+#define FF_ON_ERROR ((void)join())
   if (db2) {
     if (fork()) {
       pending = true;
@@ -263,10 +288,12 @@ int ss_ffn_bwd(const ss_ffn_desc* d, const void* X, const void* W1, const void* 
     ssa::GemmArgs gx = gemm(Dc, w.ldh, W1p + a, d->ld_w1, d->T, d->dm, nc);
     gx.acc32 = (float*)(ws + w.acc); gx.accumulate = c > 0; gx.last = c == d->k - 1;
     gx.out = (uint16_t*)dX; gx.ldo = d->ld_x;
-    FF_LAUNCH(SS_FK_DX, ssa::launch_gemm(gx, false, true, ssa::EPI_ACC, st), "dX += dZ W1^T");
+    FF_LAUNCH(SS_FK_DX, ssa::launch_gemm(gx, false, true, exact ? ssa::EPI_ACC : ssa::EPI_ACC16, st), "dX += dZ W1^T");
   }
   if (join() != hipSuccess) return hip_fail(hipGetLastError(), "join");
   return SS_OK;
+#undef FF_ON_ERROR
+#define FF_ON_ERROR ((void)0)
 }
 
 int ss_ffn_profile_enable(int on) {

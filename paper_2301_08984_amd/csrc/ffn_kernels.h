@@ -5,7 +5,7 @@
 
 namespace ssa {
 
-enum { EPI_ACT = 0, EPI_MUL = 1, EPI_ACC = 2, EPI_STORE = 3 };
+enum { EPI_ACT = 0, EPI_MUL = 1, EPI_ACC = 2, EPI_STORE = 3, EPI_ACC16 = 4 };
 
 // C[M,N] = A B (see gemm_kernel for the operand layouts); what happens to C:
 //   EPI_ACT   out = act(C + bias[n]) (bf16); out2, if given, = act'(C + bias[n])
@@ -13,6 +13,8 @@ enum { EPI_ACT = 0, EPI_MUL = 1, EPI_ACC = 2, EPI_STORE = 3 };
 //   EPI_ACC   the accumulator starts from acc32 if `accumulate`; then `last` ? out = C + bias[n] (bf16,
 //             bias may be NULL) : acc32 = C (fp32, whole tiles in the kernel's own order; see gemm_acc_bytes)
 //   EPI_STORE out = C (bf16)
+//   EPI_ACC16 the accumulator starts from `out` (bf16, widened) if `accumulate`; out = C + bias[n] (bf16,
+//             bias may be NULL): the partial sum between chunks lives in the output itself
 struct GemmArgs {
   const uint16_t* A;
   const uint16_t* B;
@@ -26,10 +28,6 @@ struct GemmArgs {
   int64_t ldm;
   float* acc32;  // ceil(M/256) * ceil(N/256) tiles of 256 x 256 fp32, in the kernel's own order
   int accumulate, last, act;
-#ifdef SS_TRACE
-  unsigned long long* trace;  // development builds only: time stamps of one work-group
-  int trace_block;
-#endif
 };
 
 // bytes of the fp32 partial-result buffer of an M x N product

@@ -237,15 +237,6 @@ __global__ __launch_bounds__(256, (FI * FJ <= 8 && KS == 2) ? 2 : 1) void gemm_k
   ra.init(lane, wm);
   rb.init(lane, wn);
 
-#ifdef SS_TRACE
-  __shared__ uint64_t tr_buf[16];
-  int tr_n = 0;
-  auto stamp = [&] { if (tr_n < 16) tr_buf[tr_n] = __builtin_amdgcn_s_memtime(); ++tr_n; };
-#define SS_MARK() do { if (w == 0) stamp(); } while (0)
-#else
-#define SS_MARK() do {} while (0)
-#endif
-  SS_MARK();
   // acc[j][i]: row m0 + 32 FI wm + 32 i + r, columns n0 + 32 FJ wn + 32 j + key_of(v, hl).
   // The fp32 partial result between chunks lives in the workspace in the order the registers hold
   // it (tile, wavefront, (j, i, quad), lane): 1 KB per wavefront instruction, fully coalesced.
@@ -330,16 +321,46 @@ __global__ __launch_bounds__(256, (FI * FJ <= 8 && KS == 2) ? 2 : 1) void gemm_k
 #pragma unroll
     for (int t = 0; t < NL - LA; ++t) sb.issue(dst + A_BYTES, w, t);
   };
-  SS_MARK();
   fetch_all(stage0);
   fetch_all(stage1);
   if (NS == 4) fetch_all(stage2);
+  if constexpr (EPI == EPI_ACC16) {
+   if (g.accumulate) {
+    // The partial sum of the earlier chunks is the output itself (bf16): read as whole rows (64 FJ
+    // contiguous bytes per row), widened, and turned into the register layout through a piece of
+    // LDS of the wavefront's own -- the epilogue's path backwards.  The pieces lie in the third stage
+    // buffer, which no load targets before the barrier that ends the prologue.
+    constexpr int TLD = 128 * FJ + 16, LPR = 8 * FJ, RPI = 64 / LPR;
+    static_assert(NS == 3 && 4 * 32 * TLD <= STAGE_BYTES, "accumulator staging does not fit");
+    char* tb = stage2 + w * (32 * TLD);
+    const int c4 = 4 * (lane % LPR), rsub = lane / LPR;
+    const int n = n0 + wn * 32 * FJ + c4;
+#pragma unroll
+    for (int i = 0; i < FI; ++i) {
+#pragma unroll
+      for (int it = 0; it < 32 / RPI; ++it) {
+        const int row = RPI * it + rsub, m = m0 + wm * 32 * FI + 32 * i + row;
+        float x[4] = {0.f, 0.f, 0.f, 0.f};
+        if (m < g.M && n < g.N) unpack4(*(const uint2*)(g.out + (int64_t)m * g.ldo + n), x);
+        *(f32x4*)(tb + row * TLD + c4 * 4) = f32x4{x[0], x[1], x[2], x[3]};
+      }
+#pragma unroll
+      for (int j = 0; j < FJ; ++j)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const f32x4 v = *(const f32x4*)(tb + r * TLD + (32 * j + 8 * q + 4 * hl) * 4);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) acc[j][i][4 * q + e] = v[e];
+        }
+    }
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+   }
+  }
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NS - 2) * NL) : "memory");
   __builtin_amdgcn_s_barrier();
   asm volatile("" ::: "memory");
 #pragma unroll
   for (int item = 0; item < NR; ++item) read_item(stage0, item, 0, 0);
-  SS_MARK();
   for (int kt = 0; kt < nkr; kt += NS) {
     if (NS == 4) {
       stage(stage0, stage1, stage3);
@@ -353,7 +374,6 @@ __global__ __launch_bounds__(256, (FI * FJ <= 8 && KS == 2) ? 2 : 1) void gemm_k
     }
   }
   asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
-  SS_MARK();
 
   if (EPI == EPI_ACC && !g.last) {
 #pragma unroll
@@ -380,7 +400,7 @@ __global__ __launch_bounds__(256, (FI * FJ <= 8 && KS == 2) ? 2 : 1) void gemm_k
     const int c4 = 4 * (lane % LPR), rsub = lane / LPR;
     const int n = n0 + wn * 32 * FJ + c4;
     float bias[4] = {0.f, 0.f, 0.f, 0.f};
-    if ((EPI == EPI_ACT || EPI == EPI_ACC) && g.bias && n < g.N) unpack4(*(const uint2*)(g.bias + n), bias);
+    if ((EPI == EPI_ACT || EPI == EPI_ACC || EPI == EPI_ACC16) && g.bias && n < g.N) unpack4(*(const uint2*)(g.bias + n), bias);
 #pragma unroll
     for (int i = 0; i < FI; ++i) {
 #pragma unroll
@@ -417,13 +437,6 @@ __global__ __launch_bounds__(256, (FI * FJ <= 8 && KS == 2) ? 2 : 1) void gemm_k
       }
     }
   }
-#ifdef SS_TRACE
-  __builtin_amdgcn_s_waitcnt(0);
-  SS_MARK();
-  if (w == 0 && lane == 0 && g.trace && (int)blockIdx.x == g.trace_block) {
-    for (int i = 0; i < 16 && i < tr_n; ++i) g.trace[i] = tr_buf[i];
-  }
-#endif
 }
 
 // out[n] = sum over m of A[m][n], fp32, fixed order: a work-group takes 64 columns; 32 row groups
@@ -463,19 +476,14 @@ __global__ __launch_bounds__(256) void colsum_kernel(const uint16_t* A, int64_t 
 #define SS_GEMM_INST(a, b, e, fi, fj, ks) template __global__ void gemm_kernel<a, b, e, fi, fj, ks>(GemmArgs);
 #define SS_GEMM_INST4(a, b, fi, fj, ks) \
   SS_GEMM_INST(a, b, 0, fi, fj, ks) SS_GEMM_INST(a, b, 1, fi, fj, ks) SS_GEMM_INST(a, b, 2, fi, fj, ks) SS_GEMM_INST(a, b, 3, fi, fj, ks)
-#ifdef SS_FORCE_TILE
-SS_GEMM_INST4(false, false, SS_FORCE_TILE / 100, SS_FORCE_TILE / 10 % 10, SS_FORCE_TILE % 10)
-SS_GEMM_INST4(false, true, SS_FORCE_TILE / 100, SS_FORCE_TILE / 10 % 10, SS_FORCE_TILE % 10)
-SS_GEMM_INST4(true, false, SS_FORCE_TILE / 100, SS_FORCE_TILE / 10 % 10, SS_FORCE_TILE % 10)
-#else
 SS_GEMM_INST4(false, false, 4, 2, 4)
 SS_GEMM_INST4(false, true, 4, 2, 4)
 SS_GEMM_INST4(true, false, 4, 2, 2)
+SS_GEMM_INST(false, false, 4, 4, 2, 4) SS_GEMM_INST(false, true, 4, 4, 2, 4)
 // 128 x 128 tiles for products that are not accumulated over chunks, when the large tiles are few
 SS_GEMM_INST(false, false, 0, 2, 2, 4) SS_GEMM_INST(false, false, 1, 2, 2, 4) SS_GEMM_INST(false, false, 3, 2, 2, 4)
 SS_GEMM_INST(false, true, 0, 2, 2, 4) SS_GEMM_INST(false, true, 1, 2, 2, 4) SS_GEMM_INST(false, true, 3, 2, 2, 4)
 SS_GEMM_INST(true, false, 0, 2, 2, 4) SS_GEMM_INST(true, false, 1, 2, 2, 4) SS_GEMM_INST(true, false, 3, 2, 2, 4)
-#endif
 #undef SS_GEMM_INST4
 #undef SS_GEMM_INST
 
@@ -493,22 +501,21 @@ hipError_t launch_one(const GemmArgs& g, hipStream_t st) {
 // tiles, twice as many work-groups at 4/3 of the operand traffic per flop.
 template <bool AT, bool BT>
 hipError_t launch_epi(const GemmArgs& g, int epi, hipStream_t st) {
-#ifdef SS_FORCE_TILE
-  constexpr int FI = SS_FORCE_TILE / 100, FJ = SS_FORCE_TILE / 10 % 10, KS = SS_FORCE_TILE % 10;
-#else
   constexpr int FI = 4, FJ = 2, KS = AT ? 2 : 4;
-  if (epi != EPI_ACC && (int64_t)((g.M + 255) / 256) * ((g.N + 127) / 128) < 160) {
+  if (epi != EPI_ACC && epi != EPI_ACC16 && (int64_t)((g.M + 255) / 256) * ((g.N + 127) / 128) < 160) {
     switch (epi) {
       case EPI_ACT: return launch_one<AT, BT, EPI_ACT, 2, 2, 4>(g, st);
       case EPI_MUL: return launch_one<AT, BT, EPI_MUL, 2, 2, 4>(g, st);
       default: return launch_one<AT, BT, EPI_STORE, 2, 2, 4>(g, st);
     }
   }
-#endif
   switch (epi) {
     case EPI_ACT: return launch_one<AT, BT, EPI_ACT, FI, FJ, KS>(g, st);
     case EPI_MUL: return launch_one<AT, BT, EPI_MUL, FI, FJ, KS>(g, st);
     case EPI_ACC: return launch_one<AT, BT, EPI_ACC, FI, FJ, KS>(g, st);
+    case EPI_ACC16:
+      if constexpr (AT) return hipErrorInvalidValue;  // the accumulated products read A untransposed
+      else return launch_one<AT, BT, EPI_ACC16, FI, FJ, KS>(g, st);
     default: return launch_one<AT, BT, EPI_STORE, FI, FJ, KS>(g, st);
   }
 }

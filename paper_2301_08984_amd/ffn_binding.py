@@ -7,6 +7,7 @@ import ctypes as C
 from . import binding as _b
 
 SS_ACT_RELU, SS_ACT_GELU_TANH = 0, 1
+SS_FFN_FLAG_EXACT_SUM = 1
 EXPORTS = ("ss_ffn_workspace_bytes", "ss_ffn_chunk_range", "ss_ffn_fwd", "ss_ffn_bwd", "ss_ffn_profile_enable",
            "ss_ffn_profile_read")
 KERNEL_NAMES = ("up", "down", "dh", "dw2", "dw1", "dx", "colsum")

@@ -136,9 +136,9 @@ class FfnCase:
         self.db1, self.db2 = torch.full_like(self.b1, fill), torch.full((self.dm,), fill, dtype=torch.bfloat16, device=self.dev)
         self.ws = None
 
-    def desc(self, lo, hi, k):
+    def desc(self, lo, hi, k, flags=0):
         return self.fb.make_desc(self.T, self.dm, self.dh, lo, hi, k, act=self.act, ld_x=self.dm + self.pad[0],
-                                 ld_w1=self.dh + self.pad[1], ld_w2=self.dm + self.pad[2])
+                                 ld_w1=self.dh + self.pad[1], ld_w2=self.dm + self.pad[2], flags=flags)
 
     def workspace(self, desc):
         f, b = self.fb.ss_ffn_workspace_bytes(desc)
@@ -147,18 +147,18 @@ class FfnCase:
             self.ws = torch.empty(need, dtype=torch.uint8, device=self.dev)
         return f, b
 
-    def fwd(self, desc, poison=False):
+    def fwd(self, desc, poison=False, stream=None):
         self.workspace(desc)
         if poison:
             self.ws.fill_(0xFF)
-        st = torch.cuda.current_stream(self.dev).cuda_stream
+        st = torch.cuda.current_stream(self.dev).cuda_stream if stream is None else stream
         self.fb.ss_ffn_fwd(desc, self.X, self.W1, self.b1, self.W2, self.b2, self.Y, self.ws, self.ws.numel(), st)
 
-    def bwd(self, desc, poison=False):
+    def bwd(self, desc, poison=False, stream=None):
         self.workspace(desc)
         if poison:
             self.ws.fill_(0xFF)
-        st = torch.cuda.current_stream(self.dev).cuda_stream
+        st = torch.cuda.current_stream(self.dev).cuda_stream if stream is None else stream
         self.fb.ss_ffn_bwd(desc, self.X, self.W1, self.b1, self.W2, self.dY, self.dX, self.dW1, self.db1, self.dW2,
                            self.db2, self.ws, self.ws.numel(), st)
 

@@ -59,12 +59,25 @@ def test_validation_and_chunks():
         d = fb.make_desc(10, 64, 256, lo, hi, k)
         # the library promises boundaries at multiples of 16 columns from lo (include/ss_ffn.h)
         assert [fb.ss_ffn_chunk_range(d, c) for c in range(k)] == orc.chunk_ranges(lo, hi, k, unit=16)
-    # the hidden-activation part of the workspace shrinks with k; the fp32 accumulator appears for k > 1
+    # the workspace is one chunk's hidden activations and shrinks as 1/k; the fp32 accumulator appears only
+    # when sums that are bit-identical for every k are asked for
     T, dm, dh = 2048, 512, 4096
     f1, b1 = fb.ss_ffn_workspace_bytes(fb.make_desc(T, dm, dh, 0, dh, 1))
     f4, b4 = fb.ss_ffn_workspace_bytes(fb.make_desc(T, dm, dh, 0, dh, 4))
     assert f1 == T * dh * 2 and b1 == 2 * T * dh * 2
-    assert f4 == T * (dh // 4) * 2 + T * dm * 4 and b4 == 2 * T * (dh // 4) * 2 + T * dm * 4
+    assert f4 == T * (dh // 4) * 2 and b4 == 2 * T * (dh // 4) * 2
+    x = fb.SS_FFN_FLAG_EXACT_SUM
+    assert fb.ss_ffn_workspace_bytes(fb.make_desc(T, dm, dh, 0, dh, 1, flags=x)) == (f1, b1)
+    assert fb.ss_ffn_workspace_bytes(fb.make_desc(T, dm, dh, 0, dh, 4, flags=x)) == (f4 + T * dm * 4, b4 + T * dm * 4)
+    with pytest.raises(ss.SSAttnError) as e:
+        fb.ss_ffn_workspace_bytes(fb.make_desc(T, dm, dh, 0, dh, 4, flags=2))
+    assert e.value.code == ss.SS_ERR_UNSUPPORTED
+    # the GPT-3 share of the benchmark: peak memory must fall with k (Sections 2 and 6.3)
+    from paper_2301_08984_amd.workloads import FFN_WORKLOADS
+    w = FFN_WORKLOADS["gpt3_ffn"]
+    sizes = [fb.ss_ffn_workspace_bytes(fb.make_desc(w["T"], w["dm"], w["dh"], w["lo"], w["hi"], k)) for k in w["k"]]
+    assert all(a[0] > b[0] and a[1] > b[1] for a, b in zip(sizes, sizes[1:])), sizes
+    assert sizes[-1][1] * w["k"][-1] == sizes[0][1] * w["k"][0], sizes
     # null pointers and workspace errors are reported before anything is launched
     d = fb.make_desc(16, 64, 64, 0, 64, 1)
     with pytest.raises(ss.SSAttnError) as e:
