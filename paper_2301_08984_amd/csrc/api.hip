@@ -315,7 +315,6 @@ int ss_attn_bwd(const ss_attn_desc* d, const void* Q, const void* K, const void*
   if (!workspace || workspace_bytes < w.total || ((uintptr_t)workspace % ALIGN)) return SS_ERR_WORKSPACE;
   hipStream_t st = (hipStream_t)hip_stream;
   const bool bf16 = d->dtype == SS_BF16;
-  const size_t es = esize(d->dtype);
   char* ws = (char*)workspace;
   const bool want_dbias = d->bias_kind != SS_BIAS_NONE && dBias != nullptr;
 
@@ -338,22 +337,20 @@ int ss_attn_bwd(const ss_attn_desc* d, const void* Q, const void* K, const void*
     set_chunk(p, d, c);
     const int64_t Bc = p.b1 - p.b0, Hc = p.h1 - p.h0;
     (void)Bc;
-    // chunk-local scratch, addressed with whole-operator (b,h): pre-offset the bases
+    // chunk-sized scratch holds the chunk's (row, head) pairs from its origin (b0, h0) on
     const int64_t st_sb = Hc * d->S, st_sh = d->S;
-    const int64_t st_off = (int64_t)p.b0 * st_sb + (int64_t)p.h0 * st_sh;
-    p.delta = (float*)(ws + w.delta) - st_off; p.dl_sb = st_sb; p.dl_sh = st_sh;
+    p.delta = (float*)(ws + w.delta); p.dl_sb = st_sb; p.dl_sh = st_sh; p.dl_b0 = p.b0; p.dl_h0 = p.h0;
     if (lse) {
-      p.lse = lse; p.lse_out = nullptr; p.lse_sb = (int64_t)d->H * d->S; p.lse_sh = d->S;
+      p.lse = lse; p.lse_out = nullptr; p.lse_sb = (int64_t)d->H * d->S; p.lse_sh = d->S; p.lse_b0 = 0; p.lse_h0 = 0;
     } else {
-      p.lse_out = (float*)(ws + w.lse) - st_off; p.lse = p.lse_out; p.lse_sb = st_sb; p.lse_sh = st_sh;
+      p.lse_out = (float*)(ws + w.lse); p.lse = p.lse_out; p.lse_sb = st_sb; p.lse_sh = st_sh;
+      p.lse_b0 = p.b0; p.lse_h0 = p.h0;
     }
     if (d->gated) {
       p.do_sh = d->D; p.do_ss = Hc * d->D; p.do_sb = (int64_t)d->S * p.do_ss;
-      const int64_t off = (int64_t)p.b0 * p.do_sb + (int64_t)p.h0 * p.do_sh;
-      p.dO_out = (void*)(ws + w.dO - off * (int64_t)es);
-      p.dO = p.dO_out;
+      p.dO_out = (void*)(ws + w.dO); p.dO = p.dO_out; p.do_b0 = p.b0; p.do_h0 = p.h0;
     } else {
-      p.dO = dY; p.dO_out = nullptr; p.do_sb = p.sb; p.do_ss = p.ss; p.do_sh = p.sh;
+      p.dO = dY; p.dO_out = nullptr; p.do_sb = p.sb; p.do_ss = p.ss; p.do_sh = p.sh; p.do_b0 = 0; p.do_h0 = 0;
     }
     // the first chunk that touches a bias-gradient entry starts its sum: for a HEAD split every
     // chunk owns its heads; for a ROW split chunk 0 starts and later chunks continue in row order

@@ -34,9 +34,9 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(D <= 32
   const uint16_t* Qb = (const uint16_t*)p.Q + base;
   const uint16_t* Kb = (const uint16_t*)p.K + base;
   const uint16_t* Vb = (const uint16_t*)p.V + base;
-  const uint16_t* dOb = (const uint16_t*)p.dO + (int64_t)b * p.do_sb + (int64_t)h * p.do_sh;
-  const float* lse_b = p.lse + (int64_t)b * p.lse_sb + (int64_t)h * p.lse_sh;
-  const float* dl_b = p.delta + (int64_t)b * p.dl_sb + (int64_t)h * p.dl_sh;
+  const uint16_t* dOb = (const uint16_t*)p.dO + (int64_t)(b - p.do_b0) * p.do_sb + (int64_t)(h - p.do_h0) * p.do_sh;
+  const float* lse_b = p.lse + (int64_t)(b - p.lse_b0) * p.lse_sb + (int64_t)(h - p.lse_h0) * p.lse_sh;
+  const float* dl_b = p.delta + (int64_t)(b - p.dl_b0) * p.dl_sb + (int64_t)(h - p.dl_h0) * p.dl_sh;
   // bias comes from the transposed copy biasT[h][key][query], so that a lane (= key) finds four
   // consecutive queries in 8 bytes
   BiasTile bt;
@@ -316,14 +316,14 @@ void dbias_tile_kernel(KP p) {
         const int hc = HP == 1 ? h : hA;  // HP = 2: addressed from the first head, hh * D columns on
         const int64_t ba = (int64_t)b * p.sb + (int64_t)hc * p.sh + hh * D + col;
         pre[0][c] = *(const u32x4*)((const uint16_t*)p.Q + ba + (int64_t)rq * p.ss);
-        pre[1][c] = *(const u32x4*)((const uint16_t*)p.dO + (int64_t)b * p.do_sb + (int64_t)hc * p.do_sh + (int64_t)rq * p.do_ss + hh * D + col);
+        pre[1][c] = *(const u32x4*)((const uint16_t*)p.dO + (int64_t)(b - p.do_b0) * p.do_sb + (int64_t)(hc - p.do_h0) * p.do_sh + (int64_t)rq * p.do_ss + hh * D + col);
         pre[2][c] = *(const u32x4*)((const uint16_t*)p.K + ba + (int64_t)rk * p.ss);
         pre[3][c] = *(const u32x4*)((const uint16_t*)p.V + ba + (int64_t)rk * p.ss);
       }
       if (tid < 128 * HP) {
         const int hs = hA + tid / 128, i = min(q0t + (tid & 63), p.S - 1);
-        pstat = (tid & 64) == 0 ? p.lse[(int64_t)b * p.lse_sb + (int64_t)hs * p.lse_sh + i]
-                                : p.delta[(int64_t)b * p.dl_sb + (int64_t)hs * p.dl_sh + i];
+        pstat = (tid & 64) == 0 ? p.lse[(int64_t)(b - p.lse_b0) * p.lse_sb + (int64_t)(hs - p.lse_h0) * p.lse_sh + i]
+                                : p.delta[(int64_t)(b - p.dl_b0) * p.dl_sb + (int64_t)(hs - p.dl_h0) * p.dl_sh + i];
       }
     };
     auto lstore = [&](int buf) {

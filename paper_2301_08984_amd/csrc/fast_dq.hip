@@ -38,7 +38,7 @@ __attribute__((amdgpu_waves_per_eu(D <= 32 ? (BIAS ? 3 : 4) : 2, D <= 32 ? (BIAS
   const uint16_t* Qb = (const uint16_t*)p.Q + base;
   const uint16_t* Kb = (const uint16_t*)p.K + base;
   const uint16_t* Vb = (const uint16_t*)p.V + base;
-  const uint16_t* dOb = (const uint16_t*)p.dO + (int64_t)b * p.do_sb + (int64_t)h * p.do_sh;
+  const uint16_t* dOb = (const uint16_t*)p.dO + (int64_t)(b - p.do_b0) * p.do_sb + (int64_t)(h - p.do_h0) * p.do_sh;
   BiasTile bt;
   if (BIAS)
     bt.init((const uint16_t*)p.bias + (int64_t)h * p.S * p.S, q0, p.S,
@@ -50,8 +50,8 @@ __attribute__((amdgpu_waves_per_eu(D <= 32 ? (BIAS ? 3 : 4) : 2, D <= 32 ? (BIAS
     qf[ks] = *(const bf16x8*)(Qb + (int64_t)qc * p.ss + 16 * ks + 8 * hl);
     gf[ks] = *(const bf16x8*)(dOb + (int64_t)qc * p.do_ss + 16 * ks + 8 * hl);
   }
-  const float lse2 = p.lse[(int64_t)b * p.lse_sb + (int64_t)h * p.lse_sh + qc] * LOG2E;
-  const float delta = p.delta[(int64_t)b * p.dl_sb + (int64_t)h * p.dl_sh + qc];
+  const float lse2 = p.lse[(int64_t)(b - p.lse_b0) * p.lse_sb + (int64_t)(h - p.lse_h0) * p.lse_sh + qc] * LOG2E;
+  const float delta = p.delta[(int64_t)(b - p.dl_b0) * p.dl_sb + (int64_t)(h - p.dl_h0) * p.dl_sh + qc];
   f32x16 acc[DB];
 #pragma unroll
   for (int db = 0; db < DB; ++db)

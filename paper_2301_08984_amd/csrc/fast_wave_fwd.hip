@@ -248,7 +248,7 @@ __global__ __launch_bounds__(64 * NG) __attribute__((amdgpu_waves_per_eu(2, 2)))
     }
     const float lse = (m + log2f(l)) * LN2;
     if (!RECOMP) {
-      if (grp == 0 && hl == 0 && q < p.S && p.lse_out) p.lse_out[(int64_t)b * p.lse_sb + (int64_t)h * p.lse_sh + q] = lse;
+      if (grp == 0 && hl == 0 && q < p.S && p.lse_out) p.lse_out[(int64_t)(b - p.lse_b0) * p.lse_sb + (int64_t)(h - p.lse_h0) * p.lse_sh + q] = lse;
       return;
     }
     // recompute: Delta = sum over the output blocks of the partial row sums, in block order
@@ -259,8 +259,8 @@ __global__ __launch_bounds__(64 * NG) __attribute__((amdgpu_waves_per_eu(2, 2)))
       float dl = 0.f;
 #pragma unroll
       for (int db = 0; db < (DB < NG ? DB : NG); ++db) dl += dpart[db * 32 + r];
-      p.delta[(int64_t)b * p.dl_sb + (int64_t)h * p.dl_sh + q] = dl;
-      if (p.lse_out) p.lse_out[(int64_t)b * p.lse_sb + (int64_t)h * p.lse_sh + q] = lse;
+      p.delta[(int64_t)(b - p.dl_b0) * p.dl_sb + (int64_t)(h - p.dl_h0) * p.dl_sh + q] = dl;
+      if (p.lse_out) p.lse_out[(int64_t)(b - p.lse_b0) * p.lse_sb + (int64_t)(h - p.lse_h0) * p.lse_sh + q] = lse;
     }
     return;
   }
@@ -270,7 +270,7 @@ __global__ __launch_bounds__(64 * NG) __attribute__((amdgpu_waves_per_eu(2, 2)))
 
 template <int D, bool RECOMP>
 hipError_t fwd_wave_r(const KP& p, hipStream_t st) {
-  constexpr int NG = 8;
+  constexpr int NG = 4;
   const dim3 g((p.S + 31) / 32, p.h1 - p.h0, p.b1 - p.b0);
   const bool bias = p.bias_kind == 1, causal = p.mask_kind == 1;
   if (bias && causal) fwd_wave_kernel<D, true, true, RECOMP, NG><<<g, 64 * NG, 0, st>>>(p);

@@ -45,7 +45,7 @@ __device__ inline T* actw(void* base, const KP& p, int b, int s, int h) {
 }
 template <typename T>
 __device__ inline const T* dorow(const KP& p, int b, int s, int h) {
-  return (const T*)p.dO + (int64_t)b * p.do_sb + (int64_t)s * p.do_ss + (int64_t)h * p.do_sh;
+  return (const T*)p.dO + (int64_t)(b - p.do_b0) * p.do_sb + (int64_t)s * p.do_ss + (int64_t)(h - p.do_h0) * p.do_sh;
 }
 
 __device__ inline bool is_masked(const KP& p, int b, int i, int j) {
@@ -143,7 +143,7 @@ __global__ __launch_bounds__(WAVES * 64) void generic_fwd_kernel(KP p) {
           stf(y + d, v);
         }
       }
-      if (p.lse_out && lane == 0) p.lse_out[(int64_t)b * p.lse_sb + (int64_t)h * p.lse_sh + i] = lse;
+      if (p.lse_out && lane == 0) p.lse_out[(int64_t)(b - p.lse_b0) * p.lse_sb + (int64_t)(h - p.lse_h0) * p.lse_sh + i] = lse;
     }
   } else {
     float part = 0.f;
@@ -158,15 +158,15 @@ __global__ __launch_bounds__(WAVES * 64) void generic_fwd_kernel(KP p) {
           if (live) stf(actw<T>(p.dG, p, b, i, h) + d, go * ov * g * (1.f - g));
           go = rnd(go * g, (const T*)nullptr);
           if (live)
-            stf((T*)p.dO_out + (int64_t)b * p.do_sb + (int64_t)i * p.do_ss + (int64_t)h * p.do_sh + d, go);
+            stf((T*)p.dO_out + (int64_t)(b - p.do_b0) * p.do_sb + (int64_t)i * p.do_ss + (int64_t)(h - p.do_h0) * p.do_sh + d, go);
         }
         part = fmaf(go, ov, part);
       }
     }
     part = wave_sum(part);
     if (live && lane == 0) {
-      p.delta[(int64_t)b * p.dl_sb + (int64_t)h * p.dl_sh + i] = part;
-      if (p.lse_out) p.lse_out[(int64_t)b * p.lse_sb + (int64_t)h * p.lse_sh + i] = lse;
+      p.delta[(int64_t)(b - p.dl_b0) * p.dl_sb + (int64_t)(h - p.dl_h0) * p.dl_sh + i] = part;
+      if (p.lse_out) p.lse_out[(int64_t)(b - p.lse_b0) * p.lse_sb + (int64_t)(h - p.lse_h0) * p.lse_sh + i] = lse;
     }
   }
 }
@@ -188,8 +188,8 @@ __global__ __launch_bounds__(WAVES * 64) void generic_dq_kernel(KP p) {
   const T* go = dorow<T>(p, b, i, h);
   for (int d = lane; d < p.D; d += 64) { qrow[w][d] = ldf(q + d); grow[w][d] = ldf(go + d); }
   __syncthreads();
-  const float lse = p.lse[(int64_t)b * p.lse_sb + (int64_t)h * p.lse_sh + i];
-  const float delta = p.delta[(int64_t)b * p.dl_sb + (int64_t)h * p.dl_sh + i];
+  const float lse = p.lse[(int64_t)(b - p.lse_b0) * p.lse_sb + (int64_t)(h - p.lse_h0) * p.lse_sh + i];
+  const float delta = p.delta[(int64_t)(b - p.dl_b0) * p.dl_sb + (int64_t)(h - p.dl_h0) * p.dl_sh + i];
   float acc[4] = {0.f, 0.f, 0.f, 0.f};
   for (int j0 = 0; j0 < p.S; j0 += TILE) {
 #pragma unroll
@@ -254,9 +254,9 @@ __global__ __launch_bounds__(WAVES * 64) void generic_dkdv_kernel(KP p) {
       float pr = 0.f, ds = 0.f;
       if (i < p.S && !is_masked(p, b, i, j)) {
         const float s = p.scale * dot_lds(krow[w], act<T>(p.Q, p, b, i, h), p.D) + bias_at(p, h, i, j);
-        pr = expf(s - p.lse[(int64_t)b * p.lse_sb + (int64_t)h * p.lse_sh + i]);
+        pr = expf(s - p.lse[(int64_t)(b - p.lse_b0) * p.lse_sb + (int64_t)(h - p.lse_h0) * p.lse_sh + i]);
         const float dp = dot_lds(vrow[w], dorow<T>(p, b, i, h), p.D);
-        ds = pr * (dp - p.delta[(int64_t)b * p.dl_sb + (int64_t)h * p.dl_sh + i]);
+        ds = pr * (dp - p.delta[(int64_t)(b - p.dl_b0) * p.dl_sb + (int64_t)(h - p.dl_h0) * p.dl_sh + i]);
       }
       pbuf[w][lane + 64 * t] = pr;
       dsbuf[w][lane + 64 * t] = ds;
@@ -315,9 +315,9 @@ __global__ __launch_bounds__(256) void generic_dbias_kernel(KP p) {
     __syncthreads();
     if (!is_masked(p, b, i, jc)) {
       const float s = p.scale * dot_lds(qrow, act<T>(p.K, p, b, jc, h), p.D) + bias;
-      const float pr = expf(s - p.lse[(int64_t)b * p.lse_sb + (int64_t)h * p.lse_sh + i]);
+      const float pr = expf(s - p.lse[(int64_t)(b - p.lse_b0) * p.lse_sb + (int64_t)(h - p.lse_h0) * p.lse_sh + i]);
       const float dp = dot_lds(grow, act<T>(p.V, p, b, jc, h), p.D);
-      acc += pr * (dp - p.delta[(int64_t)b * p.dl_sb + (int64_t)h * p.dl_sh + i]);
+      acc += pr * (dp - p.delta[(int64_t)(b - p.dl_b0) * p.dl_sb + (int64_t)(h - p.dl_h0) * p.dl_sh + i]);
     }
   }
   if (live) *dst = acc;

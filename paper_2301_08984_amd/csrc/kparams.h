@@ -11,17 +11,22 @@ struct KP {
   const void *Q, *K, *V, *G, *dY;
   void *Y, *dQ, *dK, *dV, *dG;
   int64_t sb, ss, sh;
-  // gradient w.r.t. the un-gated output: dY itself, or the chunk's pre-gated copy in
-  // the workspace (pointer pre-offset so that whole-operator (b,h) indices address it)
+  // gradient w.r.t. the un-gated output: dY itself, or the chunk's pre-gated copy in the
+  // workspace; element (b,s,h,d) at (b - do_b0)*do_sb + s*do_ss + (h - do_h0)*do_sh + d, where
+  // (do_b0, do_h0) is the first (row, head) the buffer holds: (0,0) for a whole-operator tensor,
+  // the chunk's origin for chunk-sized scratch
   const void* dO;
   int64_t do_sb, do_ss, do_sh;
+  int do_b0, do_h0;
   void* dO_out;  // recompute pass writes here when gated (same indexing as dO)
-  // softmax statistics, (b,h,s) at b*st_sb + h*st_sh + s (pointers pre-offset likewise)
+  // softmax statistics, (b,h,s) at (b - lse_b0)*lse_sb + (h - lse_h0)*lse_sh + s, origins as above
   float* lse_out;       // forward: optional caller tensor; recompute: workspace
   const float* lse;     // backward kernels read this
   int64_t lse_sb, lse_sh;
-  float* delta;         // rowsum(dO*O), workspace
+  int lse_b0, lse_h0;
+  float* delta;         // rowsum(dO*O), workspace; (b,h,s) at (b - dl_b0)*dl_sb + (h - dl_h0)*dl_sh + s
   int64_t dl_sb, dl_sh;
+  int dl_b0, dl_h0;
   // bias / mask
   const void* bias;     // dense [H,S,S] or table [H,R]
   const void* biasT;    // workspace copy of a dense bf16 bias with the last two axes swapped (or nullptr)

@@ -242,7 +242,7 @@ __device__ inline float fwd_epilogue_block(const KP& p, const f32x16& o16, int d
         o2[g].x = (uint32_t)dor[0] | ((uint32_t)dor[1] << 16); o2[g].y = (uint32_t)dor[2] | ((uint32_t)dor[3] << 16);
       }
       store_row32((uint16_t*)p.dG + row, o1, hl, true);
-      store_row32((uint16_t*)p.dO_out + (int64_t)b * p.do_sb + (int64_t)q * p.do_ss + (int64_t)h * p.do_sh + 32 * db, o2, hl,
+      store_row32((uint16_t*)p.dO_out + (int64_t)(b - p.do_b0) * p.do_sb + (int64_t)q * p.do_ss + (int64_t)(h - p.do_h0) * p.do_sh + 32 * db, o2, hl,
                   true);
     }
 #pragma unroll
@@ -264,12 +264,12 @@ __device__ inline void fwd_epilogue(const KP& p, f32x16 (&oacc)[DB], float m, fl
 #pragma unroll
   for (int db = 0; db < DB; ++db) part = fwd_epilogue_block<RECOMP>(p, oacc[db], db, inv, b, h, q, hl, base, part);
   if (!RECOMP) {
-    if (p.lse_out && hl == 0) p.lse_out[(int64_t)b * p.lse_sb + (int64_t)h * p.lse_sh + q] = lse;
+    if (p.lse_out && hl == 0) p.lse_out[(int64_t)(b - p.lse_b0) * p.lse_sb + (int64_t)(h - p.lse_h0) * p.lse_sh + q] = lse;
   } else {
     part = half_sum(part);
     if (hl == 0) {
-      p.delta[(int64_t)b * p.dl_sb + (int64_t)h * p.dl_sh + q] = part;
-      if (p.lse_out) p.lse_out[(int64_t)b * p.lse_sb + (int64_t)h * p.lse_sh + q] = lse;
+      p.delta[(int64_t)(b - p.dl_b0) * p.dl_sb + (int64_t)(h - p.dl_h0) * p.dl_sh + q] = part;
+      if (p.lse_out) p.lse_out[(int64_t)(b - p.lse_b0) * p.lse_sb + (int64_t)(h - p.lse_h0) * p.lse_sh + q] = lse;
     }
   }
 }

@@ -296,7 +296,7 @@ __global__ __launch_bounds__(NW * 64) void mfma_dq_kernel(KP p) {
   const uint16_t* Qb = (const uint16_t*)p.Q + base;
   const uint16_t* Kb = (const uint16_t*)p.K + base;
   const uint16_t* Vb = (const uint16_t*)p.V + base;
-  const uint16_t* dOb = (const uint16_t*)p.dO + (int64_t)b * p.do_sb + (int64_t)h * p.do_sh;
+  const uint16_t* dOb = (const uint16_t*)p.dO + (int64_t)(b - p.do_b0) * p.do_sb + (int64_t)(h - p.do_h0) * p.do_sh;
   BiasCtx bc;
   relpos_setup(p, h, s_cidx, s_table, tid, NT, bc);
   const int32_t* rid = p.mask_kind == 2 ? p.region + (int64_t)(b % p.mask_period) * p.S : nullptr;
@@ -308,8 +308,8 @@ __global__ __launch_bounds__(NW * 64) void mfma_dq_kernel(KP p) {
     qf[ks] = q < p.S ? *(const bf16x8*)(Qb + (int64_t)q * p.ss + 16 * ks + 8 * hl) : zero8();
     gf[ks] = q < p.S ? *(const bf16x8*)(dOb + (int64_t)q * p.do_ss + 16 * ks + 8 * hl) : zero8();
   }
-  const float lse2 = p.lse[(int64_t)b * p.lse_sb + (int64_t)h * p.lse_sh + qc] * LOG2E;
-  const float delta = p.delta[(int64_t)b * p.dl_sb + (int64_t)h * p.dl_sh + qc];
+  const float lse2 = p.lse[(int64_t)(b - p.lse_b0) * p.lse_sb + (int64_t)(h - p.lse_h0) * p.lse_sh + qc] * LOG2E;
+  const float delta = p.delta[(int64_t)(b - p.dl_b0) * p.dl_sb + (int64_t)(h - p.dl_h0) * p.dl_sh + qc];
   f32x16 acc[DB];
 #pragma unroll
   for (int db = 0; db < DB; ++db)
@@ -396,9 +396,9 @@ __global__ __launch_bounds__(NW * 64) void mfma_dkdv_kernel(KP p) {
   const uint16_t* Qb = (const uint16_t*)p.Q + base;
   const uint16_t* Kb = (const uint16_t*)p.K + base;
   const uint16_t* Vb = (const uint16_t*)p.V + base;
-  const uint16_t* dOb = (const uint16_t*)p.dO + (int64_t)b * p.do_sb + (int64_t)h * p.do_sh;
-  const float* lse_b = p.lse + (int64_t)b * p.lse_sb + (int64_t)h * p.lse_sh;
-  const float* dl_b = p.delta + (int64_t)b * p.dl_sb + (int64_t)h * p.dl_sh;
+  const uint16_t* dOb = (const uint16_t*)p.dO + (int64_t)(b - p.do_b0) * p.do_sb + (int64_t)(h - p.do_h0) * p.do_sh;
+  const float* lse_b = p.lse + (int64_t)(b - p.lse_b0) * p.lse_sb + (int64_t)(h - p.lse_h0) * p.lse_sh;
+  const float* dl_b = p.delta + (int64_t)(b - p.dl_b0) * p.dl_sb + (int64_t)(h - p.dl_h0) * p.dl_sh;
   BiasCtx bc;
   relpos_setup(p, h, s_cidx, s_table, tid, NT, bc);
   const int32_t* rid = p.mask_kind == 2 ? p.region + (int64_t)(b % p.mask_period) * p.S : nullptr;
@@ -530,9 +530,9 @@ __global__ __launch_bounds__(256) void mfma_dbias_kernel(KP p) {
     const uint16_t* Qr = (const uint16_t*)p.Q + base + (int64_t)qa * p.ss;
     const uint16_t* Kr = (const uint16_t*)p.K + base + (int64_t)kc * p.ss;
     const uint16_t* Vr = (const uint16_t*)p.V + base + (int64_t)kc * p.ss;
-    const uint16_t* Gr = (const uint16_t*)p.dO + (int64_t)b * p.do_sb + (int64_t)h * p.do_sh + (int64_t)qa * p.do_ss;
-    const float* lse_b = p.lse + (int64_t)b * p.lse_sb + (int64_t)h * p.lse_sh;
-    const float* dl_b = p.delta + (int64_t)b * p.dl_sb + (int64_t)h * p.dl_sh;
+    const uint16_t* Gr = (const uint16_t*)p.dO + (int64_t)(b - p.do_b0) * p.do_sb + (int64_t)(h - p.do_h0) * p.do_sh + (int64_t)qa * p.do_ss;
+    const float* lse_b = p.lse + (int64_t)(b - p.lse_b0) * p.lse_sb + (int64_t)(h - p.lse_h0) * p.lse_sh;
+    const float* dl_b = p.delta + (int64_t)(b - p.dl_b0) * p.dl_sb + (int64_t)(h - p.dl_h0) * p.dl_sh;
     const int32_t* rid = p.mask_kind == 2 ? p.region + (int64_t)(b % p.mask_period) * p.S : nullptr;
     const int my_rid = rid ? rid[kc] : 0;
     f32x16 sacc, pacc;

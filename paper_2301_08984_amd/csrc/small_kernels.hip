@@ -216,7 +216,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
         *(uint2*)(L.t2 + q * SLD + 8 * g + 4 * hl) = o;
       }
       if (q < p.S && hl == 0 && p.lse_out)
-        p.lse_out[(int64_t)b * p.lse_sb + (int64_t)h * p.lse_sh + q] = (m + log2f(l)) * LN2;
+        p.lse_out[(int64_t)(b - p.lse_b0) * p.lse_sb + (int64_t)(h - p.lse_h0) * p.lse_sh + q] = (m + log2f(l)) * LN2;
     }
     wave_lds_sync();
     // Y rows leave as whole 64-byte segments
@@ -274,7 +274,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     {
       u32x4 tk[4], tg[4], tq[4];
       load_rows((const uint16_t*)p.K + base, p.ss, p.S, lane, tk);
-      load_rows((const uint16_t*)p.dO + (int64_t)b * p.do_sb + (int64_t)h * p.do_sh, p.do_ss, p.S, lane, tg);
+      load_rows((const uint16_t*)p.dO + (int64_t)(b - p.do_b0) * p.do_sb + (int64_t)(h - p.do_h0) * p.do_sh, p.do_ss, p.S, lane, tg);
       load_rows((const uint16_t*)p.Q + base, p.ss, p.S, lane, tq);
       u32x4 tv[4];
       load_rows((const uint16_t*)p.V + base, p.ss, p.S, lane, tv);
