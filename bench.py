@@ -31,7 +31,7 @@ PEAK_VALU_LANEOPS = 256 * 64 * 2.4e9
 # work; at D = 32 a score element costs 2-3 matrix steps but the same softmax arithmetic, so the vector
 # ALUs (exp2 above all) bind and the HBM fraction is reported beside it; the window shape moves its
 # activations in 64-byte pieces and is nearest to the HBM roof
-BOUND = {"gpt3_shard": "mfma", "gpt3_long": "mfma", "swin_window": "hbm", "af2_msa_row": "alu", "af2_triangle": "alu",
+BOUND = {"gpt3_shard": "mfma", "gpt3_long": "mfma", "gpt3_long_16k": "mfma", "swin_window": "hbm", "af2_msa_row": "alu", "af2_triangle": "alu",
          "af2_msa_col": "alu", "af2_triangle_end": "alu", "tiny_mha": "hbm"}
 # Contractions (each 2*D flop per visible score element) of the METHOD that a kernel stands for: the
 # forward has 2 (scores, value product), the backward 5 (scores, dP, dV, dK, dQ); where the backward

@@ -57,7 +57,9 @@ inline void chunk(const ss_attn_desc* d, int c, int* a, int* b) {
 
 struct WsLayout {
   size_t lse, delta, dO, dense, partial, biasT, total;
-  int gw, g0, ngroups;  // grouped bias-gradient sums: rows per group (0: none), first group, group count
+  // grouped bias-gradient sums: rows per group (0: none), first group and group count of the share,
+  // groups per slice of the two-level sum, ring of group slots kept in the workspace, heads per slot
+  int gw, g0, ngroups, slice, ring, hs;
 };
 
 constexpr int SMALL_GW = 8;  // rows per bias-gradient group of the short-sequence kernels
@@ -91,7 +93,19 @@ WsLayout bwd_layout(const ss_attn_desc* d, Family fam) {
   if (w.gw > 0) {
     w.g0 = row_lo / w.gw;
     w.ngroups = (row_hi - 1) / w.gw - w.g0 + 1;
-    off += align_up((size_t)w.ngroups * d->H * d->S * d->S * 4);
+    // slices depend on the share only, so that the order of additions does not depend on k
+    w.slice = w.ngroups / 16 < 1 ? 1 : (w.ngroups / 16 > 32 ? 32 : w.ngroups / 16);
+    if (d->shard_axis == SS_AXIS_ROW) {
+      // complete slices are folded into the result after every chunk: what stays alive is the slice
+      // under way plus the groups the next chunk touches
+      const int64_t per_chunk = (nmax + w.gw - 1) / w.gw + 1;
+      w.ring = (int)(w.slice + per_chunk < w.ngroups ? w.slice + per_chunk : w.ngroups);
+      w.hs = d->H;
+    } else {
+      w.ring = w.ngroups;   // a chunk of heads walks every row: all groups, but only the chunk's heads
+      w.hs = (int)nmax;
+    }
+    off += align_up((size_t)w.ring * w.hs * d->S * d->S * 4);
   }
   w.biasT = off;
   if (d->bias_kind == SS_BIAS_DENSE && d->bias_dtype == SS_BF16) off += align_up((size_t)d->H * d->S * d->S * 2);
@@ -333,6 +347,31 @@ int ss_attn_bwd(const ss_attn_desc* d, const void* Q, const void* K, const void*
     dense = d->bias_kind == SS_BIAS_DENSE ? dBias : (float*)(ws + w.dense);
     p.dbias_acc = dense;
   }
+  // grouped bias-gradient sums: slot addressing for the chunk, and the fold of the slices that the
+  // chunk just completed (ROW split: groups complete as the rows go by; HEAD split: a chunk walks
+  // every row of its heads, so all of its groups complete at once)
+  int slices_done = 0;
+  auto set_groups = [&](KP& q) {
+    q.sm_g0 = w.g0; q.sm_ring = w.ring; q.sm_hs = w.hs;
+    q.sm_h0 = d->shard_axis == SS_AXIS_HEAD ? q.h0 : 0;
+  };
+  auto fold_groups = [&](const KP& q, int c) -> int {
+    const int nslices = (w.ngroups + w.slice - 1) / w.slice;
+    int s0, s1, hd0, nh;
+    if (d->shard_axis == SS_AXIS_HEAD) {
+      s0 = 0; s1 = nslices; hd0 = q.h0; nh = q.h1 - q.h0;
+    } else {
+      const int done = c == d->k - 1 ? nslices : (q.b1 / w.gw - w.g0) / w.slice;
+      s0 = slices_done; s1 = done > slices_done ? done : slices_done; hd0 = 0; nh = d->H;
+      slices_done = s1;
+    }
+    if (s1 <= s0) return SS_OK;
+    SS_LAUNCH(SS_K_DBIAS,
+              ssa::launch_group_fold(q.sm_partial, dense, w.ring, w.hs, hd0, nh, d->S, w.slice, s0, s1, w.ngroups,
+                                     s0 == 0, st),
+              "bias gradient group fold");
+    return SS_OK;
+  };
   for (int c = 0; c < d->k; ++c) {
     set_chunk(p, d, c);
     const int64_t Bc = p.b1 - p.b0, Hc = p.h1 - p.h0;
@@ -359,18 +398,18 @@ int ss_attn_bwd(const ss_attn_desc* d, const void* Q, const void* K, const void*
       // one fused kernel per chunk; group partial sums of the bias gradient live in the workspace
       // across chunks and are reduced once the last chunk that touches them is enqueued
       p.sm_partial = want_dbias ? (float*)(ws + w.partial) : nullptr;
-      p.sm_g0 = w.g0;
+      set_groups(p);
       SS_LAUNCH(SS_K_DKDV, ssa::launch_small_bwd(p, st), "backward (short)");
-      if (want_dbias && (d->shard_axis == SS_AXIS_HEAD || c == d->k - 1)) {
-        const int h0 = d->shard_axis == SS_AXIS_HEAD ? p.h0 : 0;
-        const int h1 = d->shard_axis == SS_AXIS_HEAD ? p.h1 : d->H;
-        SS_LAUNCH(SS_K_DBIAS,
-                  ssa::launch_small_group_reduce(p.sm_partial, dense, w.ngroups, d->H, h0, h1, d->S, st),
-                  "bias gradient group reduce");
-        if (d->bias_kind == SS_BIAS_RELPOS)
+      if (want_dbias) {
+        const int rf = fold_groups(p, c);
+        if (rf != SS_OK) return rf;
+        if (d->bias_kind == SS_BIAS_RELPOS && (d->shard_axis == SS_AXIS_HEAD || c == d->k - 1)) {
+          const int h0 = d->shard_axis == SS_AXIS_HEAD ? p.h0 : 0;
+          const int h1 = d->shard_axis == SS_AXIS_HEAD ? p.h1 : d->H;
           SS_LAUNCH(SS_K_TABLE_REDUCE,
                     ssa::launch_relpos_reduce(dense, dBias, h0, h1, d->S, d->win_h, d->win_w, st),
                     "relative-position table reduce");
+        }
       }
       continue;
     }
@@ -383,18 +422,15 @@ int ss_attn_bwd(const ss_attn_desc* d, const void* Q, const void* K, const void*
         SS_LAUNCH(SS_K_DKDV, ssa::launch_mfma_dkdv(p, st), "dK/dV");
       }
       if (want_dbias) {
-        if (w.gw > 0) {  // grouped sum: partials in the workspace, reduced after the last chunk that adds to them
+        if (w.gw > 0) {  // grouped sum: partials in the workspace, folded into the result as the groups complete
           p.sm_partial = (float*)(ws + w.partial);
           p.sm_gw = w.gw;
-          p.sm_g0 = w.g0;
+          set_groups(p);
         }
         SS_LAUNCH(SS_K_DBIAS, ssa::launch_mfma_dbias(p, st), "dBias");
-        if (w.gw > 0 && (d->shard_axis == SS_AXIS_HEAD || c == d->k - 1)) {
-          const int h0 = d->shard_axis == SS_AXIS_HEAD ? p.h0 : 0;
-          const int h1 = d->shard_axis == SS_AXIS_HEAD ? p.h1 : d->H;
-          SS_LAUNCH(SS_K_DBIAS,
-                    ssa::launch_small_group_reduce(p.sm_partial, dense, w.ngroups, d->H, h0, h1, d->S, st),
-                    "bias gradient group reduce");
+        if (w.gw > 0) {
+          const int rf = fold_groups(p, c);
+          if (rf != SS_OK) return rf;
         }
       }
     } else {

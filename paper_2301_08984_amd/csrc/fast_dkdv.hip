@@ -279,7 +279,7 @@ void dbias_tile_kernel(KP p) {
     const int g = p.b0 / p.sm_gw + blk.z / Hc;
     bfirst = max(g * p.sm_gw, p.b0);
     blast = min((g + 1) * p.sm_gw, p.b1);
-    dst = p.sm_partial + ((int64_t)(g - p.sm_g0) * p.H + h) * p.S * p.S + (int64_t)qc * p.S;
+    dst = p.sm_partial + ((int64_t)((g - p.sm_g0) % p.sm_ring) * p.sm_hs + (h - p.sm_h0)) * p.S * p.S + (int64_t)qc * p.S;
     resume = max(g * p.sm_gw, p.share_b0) < p.b0;
   } else {
     dst = p.dbias_acc + ((int64_t)h * p.S + qc) * p.S;

@@ -36,10 +36,13 @@ struct KP {
   // shapes and the chunk
   int B, H, S, D;
   int b0, b1, h0, h1;
-  // short-sequence path: bias-gradient partial sums per group of sm_gw consecutive global rows,
-  // [group - sm_g0][H][S*S] fp32 in the workspace (nullptr: bias gradient not wanted)
+  // grouped bias-gradient sums: partial sums per group of sm_gw consecutive global rows, fp32 in the
+  // workspace (nullptr: not grouped / bias gradient not wanted).  Group g, head h sits at
+  // [((g - sm_g0) % sm_ring) * sm_hs + (h - sm_h0)][S*S]: a ring of sm_ring group slots (complete groups
+  // are folded into the result after every chunk and their slots reused), sm_hs heads per slot from
+  // head sm_h0 on
   float* sm_partial;
-  int sm_gw, sm_g0;
+  int sm_gw, sm_g0, sm_ring, sm_hs, sm_h0;
   int share_b0;     // first row of the whole share
   int share_units;  // (row, head) pairs in the whole share [lo,hi): kernel-shape choices use this, never the chunk
   float scale;
@@ -59,9 +62,13 @@ hipError_t launch_fill_zero(float* p, size_t n, hipStream_t st);
 bool small_supported(const KP& p, bool bf16);
 hipError_t launch_small_fwd(const KP& p, hipStream_t st);
 hipError_t launch_small_bwd(const KP& p, hipStream_t st);
-// sums the group partials into dense[h][i][j] for heads [h0,h1); overwrites part of `partial`
-hipError_t launch_small_group_reduce(float* partial, float* dense, int ngroups, int H, int h0, int h1, int S,
-                                     hipStream_t st);
+// Folds the complete slices [s0, s1) of `slice` consecutive groups each (the last may be shorter:
+// `ngroups` groups exist) into dense[h][i][j], heads h = hd0 .. hd0 + nh - 1 (slot heads 0 .. nh-1):
+// every slice is summed in ascending group order into its first group's slot, then the slice sums
+// are added in ascending order to dense (which starts from zero when `first`).  The additions are
+// the same whatever the chunking, so the result does not depend on k.
+hipError_t launch_group_fold(float* partial, float* dense, int ring, int hs, int hd0, int nh, int S, int slice,
+                             int s0, int s1, int ngroups, bool first, hipStream_t st);
 
 bool mfma_supported(const KP& p, bool bf16);
 hipError_t launch_mfma_fwd(const KP& p, bool recompute, hipStream_t st);

@@ -254,7 +254,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   float acc[2][2][16];
   float* part = nullptr;
   if (p.sm_partial) {
-    part = p.sm_partial + ((int64_t)(g - p.sm_g0) * p.H + h) * p.S * p.S;
+    part = p.sm_partial + ((int64_t)((g - p.sm_g0) % p.sm_ring) * p.sm_hs + (h - p.sm_h0)) * p.S * p.S;
     const bool resume = max(g * p.sm_gw, p.share_b0) < p.b0;  // an earlier chunk started this group
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb)
@@ -459,45 +459,47 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   }
 }
 
-// Two-level, fixed-shape sum over groups.  Level 1 folds every slice of SLICE consecutive groups
-// into the slice's first group (in place, ascending order); level 2 adds the slice sums in
-// ascending order into dense[h][i][j].  The tree depends only on the group count.
-constexpr int SLICE = 32;
+// Two-level, fixed-shape sum over groups, done slice by slice as the groups complete.  Level 1 folds
+// a slice of `slice` consecutive groups into the slot of the slice's first group (ascending order,
+// starting from zero); level 2 adds the slice sums in ascending order to dense[h][i][j].  Which
+// groups form a slice depends only on the share, so the additions are the same for every k.
 typedef f32x4 f32x4_u __attribute__((aligned(4)));
-// The heads [h0, h0 + nh) of one group are one contiguous run of nh * SS floats: a thread takes four
-// consecutive ones (16-byte loads need 4-byte alignment only), each summed over the groups in order.
-__global__ __launch_bounds__(256) void small_group_fold_kernel(float* partial, int ngroups, int H, int h0, int nh,
-                                                               int SS) {
+// The nh heads of one slot are one contiguous run of nh * SS floats: a thread takes four consecutive
+// ones (16-byte loads need 4-byte alignment only), each summed over the slice's groups in order.
+__global__ __launch_bounds__(256) void group_fold_kernel(float* partial, int ring, int hs, int nh, int SS, int slice,
+                                                         int s0, int ngroups) {
   const int64_t n = (int64_t)nh * SS, t = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
   if (t >= n) return;
-  const int g0 = blockIdx.y * SLICE, g1 = min(g0 + SLICE, ngroups);
-  const int64_t gs = (int64_t)H * SS;
-  float* p0 = partial + (int64_t)h0 * SS + t;
+  const int g0 = (s0 + blockIdx.y) * slice, g1 = min(g0 + slice, ngroups);
+  const int64_t gs = (int64_t)hs * SS;
+  float* dst = partial + (int64_t)(g0 % ring) * gs + t;
   if (t + 4 <= n) {
     f32x4 a = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll 8
     for (int g = g0; g < g1; ++g) {
-      const f32x4 v = *(const f32x4_u*)(p0 + g * gs);
+      const f32x4 v = *(const f32x4_u*)(partial + (int64_t)(g % ring) * gs + t);
 #pragma unroll
       for (int e = 0; e < 4; ++e) a[e] += v[e];
     }
-    *(f32x4_u*)(p0 + g0 * gs) = a;
+    *(f32x4_u*)dst = a;
   } else {
     for (int e = 0; t + e < n; ++e) {
       float a = 0.f;
-      for (int g = g0; g < g1; ++g) a += p0[g * gs + e];
-      p0[g0 * gs + e] = a;
+      for (int g = g0; g < g1; ++g) a += partial[(int64_t)(g % ring) * gs + t + e];
+      dst[e] = a;
     }
   }
 }
-__global__ __launch_bounds__(256) void small_group_reduce_kernel(const float* partial, float* dense, int ngroups,
-                                                                 int H, int h0, int nh, int SS) {
+__global__ __launch_bounds__(256) void group_reduce_kernel(const float* partial, float* dense, int ring, int hs,
+                                                           int hd0, int nh, int SS, int slice, int s0, int s1,
+                                                           int first) {
   const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (t >= (int64_t)nh * SS) return;
-  const int h = h0 + (int)(t / SS), ij = (int)(t % SS);
-  float a = 0.f;
-  for (int g = 0; g < ngroups; g += SLICE) a += partial[((int64_t)g * H + h) * SS + ij];
-  dense[(int64_t)h * SS + ij] = a;
+  const int hh = (int)(t / SS), ij = (int)(t % SS);
+  float* out = dense + (int64_t)(hd0 + hh) * SS + ij;
+  float a = first ? 0.f : *out;
+  for (int s = s0; s < s1; ++s) a += partial[((int64_t)((s * slice) % ring) * hs + hh) * SS + ij];
+  *out = a;
 }
 
 }  // namespace
@@ -522,15 +524,18 @@ hipError_t launch_small_bwd(const KP& p, hipStream_t st) {
   return hipGetLastError();
 }
 
-hipError_t launch_small_group_reduce(float* partial, float* dense, int ngroups, int H, int h0, int h1, int S,
-                                     hipStream_t st) {
-  const int64_t n = (int64_t)(h1 - h0) * S * S;
-  const unsigned bx = (unsigned)((n + 255) / 256);
-  small_group_fold_kernel<<<dim3((unsigned)((n + 1023) / 1024), (ngroups + SLICE - 1) / SLICE), 256, 0, st>>>(
-      partial, ngroups, H, h0, h1 - h0, S * S);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
-  small_group_reduce_kernel<<<bx, 256, 0, st>>>(partial, dense, ngroups, H, h0, h1 - h0, S * S);
+hipError_t launch_group_fold(float* partial, float* dense, int ring, int hs, int hd0, int nh, int S, int slice,
+                             int s0, int s1, int ngroups, bool first, hipStream_t st) {
+  if (s1 <= s0) return hipSuccess;
+  const int64_t n = (int64_t)nh * S * S;
+  if (slice > 1) {  // a slice of one group is its own sum (0 + x = x exactly)
+    group_fold_kernel<<<dim3((unsigned)((n + 1023) / 1024), s1 - s0), 256, 0, st>>>(partial, ring, hs, nh, S * S,
+                                                                                    slice, s0, ngroups);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  group_reduce_kernel<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(partial, dense, ring, hs, hd0, nh, S * S, slice, s0,
+                                                                   s1, first ? 1 : 0);
   return hipGetLastError();
 }
 

@@ -13,7 +13,19 @@ namespace {
 // units the late, light ones fill in behind the early ones.
 __device__ inline BlockId heavy_first_block_id() {
   const int units = gridDim.y * gridDim.z;
-  const int lin = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);
+  const int n = gridDim.x * units;
+  int lin = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);
+  // Between one and two work-groups per compute unit, two resident at a time: the dispatcher deals
+  // the first NCU out one per compute unit and then starts over, so work-group p + NCU joins
+  // work-group p.  With t counting from the heaviest, the NCU - m heaviest (m = n - NCU) are given
+  // the positions that stay alone, and the others are paired medium with light (t = NCU - m + i with
+  // t = n - 1 - i), so that every compute unit gets about the same number of sub-tiles.  Only the
+  // order of execution depends on this; any order gives the same results.
+  constexpr int NCU = 256;
+  if (n > NCU && n <= 2 * NCU) {
+    const int m = n - NCU;
+    lin = lin < m ? NCU - m + lin : lin < NCU ? lin - m : n - 1 - (lin - NCU);
+  }
   BlockId b;
   b.x = lin / units;
   b.y = (lin % units) % gridDim.y;

@@ -78,6 +78,9 @@ WORKLOADS = {
                              gated=True, axis="row", k=(4, 16, 64), layout="sbhd"),
     "gpt3_long": dict(seed=6006, B=1, H=12, S=12288, D=128, dtype="bf16", bias=None, mask="causal",
                       gated=False, axis="head", k=(1, 2, 4)),
+    # the upper end of that range
+    "gpt3_long_16k": dict(seed=6016, B=1, H=12, S=16384, D=128, dtype="bf16", bias=None, mask="causal",
+                          gated=False, axis="head", k=(1, 2, 4)),
 }
 
 

@@ -26,7 +26,7 @@ SS_STUB_LAUNCH(launch_relpos_reduce, const float*, float*, int, int, int, int, i
 SS_STUB_LAUNCH(launch_fill_zero, float*, size_t, hipStream_t)
 SS_STUB_LAUNCH(launch_small_fwd, const KP&, hipStream_t)
 SS_STUB_LAUNCH(launch_small_bwd, const KP&, hipStream_t)
-SS_STUB_LAUNCH(launch_small_group_reduce, float*, float*, int, int, int, int, int, hipStream_t)
+SS_STUB_LAUNCH(launch_group_fold, float*, float*, int, int, int, int, int, int, int, int, int, bool, hipStream_t)
 SS_STUB_LAUNCH(launch_mfma_fwd, const KP&, bool, hipStream_t)
 SS_STUB_LAUNCH(launch_mfma_dq, const KP&, hipStream_t)
 SS_STUB_LAUNCH(launch_mfma_dkdv, const KP&, hipStream_t)

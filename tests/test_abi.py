@@ -129,6 +129,27 @@ def test_workspace_shrinks_with_k():
         assert sizes[0] - sizes[3] >= 0.8 * per_chunk_k1 * (1 - 1 / 8), sizes
 
 
+def test_workspace_of_the_workloads_scales_down_with_k():
+    """The bias-gradient partial sums are folded into the result as their row groups complete, so they
+    too are chunk-sized: the backward workspace is a constant (a transposed bias copy, one slice of
+    group partials) plus a part proportional to the chunk.  Checked on the workload shapes:
+    workspace(k) <= constant + workspace(1) / k * 1.25."""
+    from paper_2301_08984_amd.workloads import WORKLOADS
+    const = {"af2_msa_row": 16 << 20, "af2_triangle": 12 << 20, "af2_msa_col": 0, "gpt3_shard": 0}
+    for name, c in const.items():
+        w = WORKLOADS[name]
+        ext = w["H"] if w["axis"] == "head" else w["B"]
+        sizes = {}
+        for k in (1,) + tuple(w["k"]):
+            d = ss.make_desc(w["B"], w["H"], w["S"], w["D"], ss.SS_BF16, 0.1,
+                             ss.SS_AXIS_HEAD if w["axis"] == "head" else ss.SS_AXIS_ROW, 0, ext, k,
+                             bias_kind={None: 0, "dense": 1, "relpos": 2}[w["bias"]], gated=w["gated"],
+                             mask_kind={None: 0, "causal": 1, "region": 2}[w["mask"]])
+            sizes[k] = ss.ss_attn_workspace_bytes(d)[1]
+        for k, b in sizes.items():
+            assert b <= c + 1.25 * sizes[1] / k + 4096, (name, k, sizes)
+
+
 def test_kernel_family_selection():
     assert ss.ss_attn_kernel_family(_desc(S=128)) == "mfma_bf16"
     assert ss.ss_attn_kernel_family(_desc(S=64)) == "mfma_bf16_short"

@@ -107,6 +107,28 @@ def test_long_sequence_one_head_against_oracle(k):
     _bitwise_vs_first(name, k, dc)
 
 
+def test_longest_sequence_one_head_against_oracle():
+    """S = 16384, the upper end of the long-document range, at k = 2: head 6 (the first of the second
+    chunk) against the oracle, every output finite."""
+    name, k, h = "gpt3_long_16k", 2, 6
+    print(f"full-size {name} k={k}, head {h} against the oracle", flush=True)
+    w, inp, dc = _run(name, k)
+    _ORACLE.clear()
+    one = {n: np.ascontiguousarray(inp[n][:, :, h:h + 1]) for n in ("Q", "K", "V", "dY")}
+    p = oracle_problem(one, w)
+    Y, LSE = orc.attn_forward(p, orc.AXIS_HEAD)
+    g = orc.attn_backward(p, one["dY"].astype(np.float64), orc.AXIS_HEAD)
+    tol = TOL["bf16"]
+    errs = {"Y": assert_close("Y", dc.host("Y")[:, :, h:h + 1], Y, tol),
+            "lse": float(np.max(np.abs(dc.host("lse")[:, h:h + 1] - LSE)))}
+    for n in ("dQ", "dK", "dV"):
+        errs[n] = assert_close(n, dc.host(n)[:, :, h:h + 1], g[n], tol)
+    print(name, k, {n: f"{e:.2e}" for n, e in errs.items()}, flush=True)
+    assert errs["lse"] <= 1e-3
+    for n in ("Y", "dQ", "dK", "dV"):
+        assert bool(getattr(dc, n).isfinite().all()), n
+
+
 TRI_LINES = ((0, [0, 517]), (3, [1023, 64]))
 
 
