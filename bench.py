@@ -40,7 +40,8 @@ BOUND = {"gpt3_shard": "mfma", "gpt3_long": "mfma", "gpt3_long_16k": "mfma", "sw
 CONTRACTIONS = {"fwd": 2, "recompute": 0, "dq": 2, "dkdv": 3, "dbias": 0, "table_reduce": 0, "dq_dkdv": 5}
 # contractions a kernel actually executes on the matrix cores (scores and dP are formed again by
 # every kernel that needs them)
-EXECUTED = {"fwd": 2, "recompute": 2, "dq": 3, "dkdv": 4, "dbias": 2, "table_reduce": 0, "dq_dkdv": 7}
+EXECUTED = {"fwd": 2, "recompute": 2, "dq": 3, "dkdv": 4, "dbias": 2, "table_reduce": 0, "dq_dkdv": 8}
+# ("dq_dkdv": the one-gradient-per-work-group launch forms the scores three times and dP twice: 3 + 2 + 3)
 # Vector-ALU lane-operations per visible score element that the method needs at least, quarter-rate
 # instructions counted as 4: forward = scale/bias fma 1 + running max 1 + exp2 4 + row sum 1 + bf16
 # conversion 1 = 8; backward = score fma 1 + exp2 4 + (dP - Delta) 1 + times P 1 + two conversions 2

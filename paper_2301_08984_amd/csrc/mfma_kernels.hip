@@ -636,7 +636,11 @@ hipError_t launch_mfma_dbias(const KP& p, hipStream_t st) {
 bool mfma_wants_bias_transpose(const KP& p) { return fast_ok(p) && p.bias_kind == 1; }
 // small shares with long rows: dQ and dK/dV share one launch
 bool mfma_fuses_dq_dkdv(const KP& p) { return fast_ok(p) && wg_shape(p) == WG_2x4; }
-hipError_t launch_mfma_dq_dkdv(const KP& p, hipStream_t st) { return launch_fast_bwd_wave(p, st); }
+hipError_t launch_mfma_dq_dkdv(const KP& p, hipStream_t st) {
+  // head size 128 without a bias: one gradient per work-group, two work-groups per compute unit
+  if (p.D == 128 && p.bias_kind == 0) return launch_fast_bwd_wave3(p, st);
+  return launch_fast_bwd_wave(p, st);
+}
 int mfma_dbias_group_rows(const KP& p) { return dbias_group_rows(p); }
 
 }  // namespace ssa
