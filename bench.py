@@ -37,16 +37,19 @@ BOUND = {"gpt3_shard": "mfma", "gpt3_long": "mfma", "gpt3_long_16k": "mfma", "sw
 # forward has 2 (scores, value product), the backward 5 (scores, dP, dV, dK, dQ); where the backward
 # is two kernels the scores and dP are counted once, half with each; the recompute pass and the score
 # recompute of the bias-gradient kernel are not part of the method's count.
-CONTRACTIONS = {"fwd": 2, "recompute": 0, "dq": 2, "dkdv": 3, "dbias": 0, "table_reduce": 0, "dq_dkdv": 5}
+CONTRACTIONS = {"fwd": 2, "recompute": 0, "dq": 2, "dkdv": 3, "dbias": 0, "table_reduce": 0, "dq_dkdv": 5,
+                "dbias_fold": 0}
 # contractions a kernel actually executes on the matrix cores (scores and dP are formed again by
 # every kernel that needs them)
-EXECUTED = {"fwd": 2, "recompute": 2, "dq": 3, "dkdv": 4, "dbias": 2, "table_reduce": 0, "dq_dkdv": 8}
+EXECUTED = {"fwd": 2, "recompute": 2, "dq": 3, "dkdv": 4, "dbias": 2, "table_reduce": 0, "dq_dkdv": 8,
+            "dbias_fold": 0}
 # ("dq_dkdv": the one-gradient-per-work-group launch forms the scores three times and dP twice: 3 + 2 + 3)
 # Vector-ALU lane-operations per visible score element that the method needs at least, quarter-rate
 # instructions counted as 4: forward = scale/bias fma 1 + running max 1 + exp2 4 + row sum 1 + bf16
 # conversion 1 = 8; backward = score fma 1 + exp2 4 + (dP - Delta) 1 + times P 1 + two conversions 2
 # = 9, + 1 for the bias-gradient addition.  Recomputation is not counted.
-VALU_SLOTS = {"fwd": 8, "recompute": 0, "dq": 4.5, "dkdv": 4.5, "dbias": 1, "table_reduce": 0, "dq_dkdv": 9}
+VALU_SLOTS = {"fwd": 8, "recompute": 0, "dq": 4.5, "dkdv": 4.5, "dbias": 1, "table_reduce": 0, "dq_dkdv": 9,
+              "dbias_fold": 0}
 
 
 def visible_fraction(w):
@@ -88,6 +91,7 @@ def kernel_bytes(w, name, units, axis_extent):
         "dq_dkdv": 7 * T + nb + 2 * stat,
         "dbias": 4 * T + nb + 2 * stat + (w["H"] * w["S"] ** 2 * 4 if w["bias"] else 0),
         "table_reduce": w["H"] * w["S"] ** 2 * 4,
+        "dbias_fold": 3 * w["H"] * w["S"] ** 2 * 4,
     }
     return table[name]
 

@@ -366,7 +366,7 @@ int ss_attn_bwd(const ss_attn_desc* d, const void* Q, const void* K, const void*
       slices_done = s1;
     }
     if (s1 <= s0) return SS_OK;
-    SS_LAUNCH(SS_K_DBIAS,
+    SS_LAUNCH(SS_K_DBIAS_FOLD,
               ssa::launch_group_fold(q.sm_partial, dense, w.ring, w.hs, hd0, nh, d->S, w.slice, s0, s1, w.ngroups,
                                      s0 == 0, st),
               "bias gradient group fold");
