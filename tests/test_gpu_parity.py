@@ -44,6 +44,7 @@ SMALL = {
     "dbias_two_heads": dict(seed=58, B=3, H=16, S=512, D=32, dtype="bf16", bias="dense", axis="row"),
     # long rows in a small share: work-groups split the keys (forward, dQ) / the queries (dK, dV)
     "long_seq_few_heads": dict(seed=48, B=1, H=2, S=600, D=128, dtype="bf16", mask="causal", axis="head"),
+    "long_seq_no_mask_d128": dict(seed=59, B=1, H=2, S=530, D=128, dtype="bf16", axis="head"),
     "long_seq_bias_d64": dict(seed=49, B=2, H=1, S=516, D=64, dtype="bf16", bias="dense", gated=True, axis="row"),
     "long_seq_bias_causal_d32": dict(seed=50, B=1, H=3, S=520, D=32, dtype="bf16", bias="dense", mask="causal",
                                      axis="head"),
@@ -88,7 +89,7 @@ def test_sub_range_and_saved_lse(name):
 
 @pytest.mark.parametrize("name", ["gpt_like", "swin_like", "msa_like", "tiny_mha", "bias_causal_d64",
                                   "short_dense_causal", "long_rows_many_groups", "long_seq_few_heads",
-                                  "long_seq_bias_d64", "swin_head_axis", "tri_end_like", "dbias_two_heads"])
+                                  "long_seq_no_mask_d128", "long_seq_bias_d64", "swin_head_axis", "tri_end_like", "dbias_two_heads"])
 def test_results_identical_across_k(name):
     cfg = SMALL[name]
     ref = None
@@ -124,7 +125,8 @@ def test_rising_scores_raise_the_running_maximum(name):
         check_against_oracle(cfg, k=k, inputs=inp, elem_fail_max=1e-3)
 
 
-@pytest.mark.parametrize("name", ["long_seq_few_heads", "long_seq_bias_d64", "gpt_like", "tri_like", "swin_like"])
+@pytest.mark.parametrize("name", ["long_seq_few_heads", "long_seq_no_mask_d128", "long_seq_bias_d64", "gpt_like",
+                                  "tri_like", "swin_like"])
 def test_rows_past_the_sequence_end_are_never_used(name):
     """Ragged S: the staged tiles extend past row S-1.  Every activation is followed in memory by a
     NaN-filled batch, so anything read past the end of the last batch and used would poison the result."""
