@@ -45,6 +45,9 @@ SMALL = {
     # long rows in a small share: work-groups split the keys (forward, dQ) / the queries (dK, dV)
     "long_seq_few_heads": dict(seed=48, B=1, H=2, S=600, D=128, dtype="bf16", mask="causal", axis="head"),
     "long_seq_no_mask_d128": dict(seed=59, B=1, H=2, S=530, D=128, dtype="bf16", axis="head"),
+    # more than 32 key sub-tiles per query block: every wavefront of a block walks many sub-tiles
+    "longer_seq_causal_d128": dict(seed=60, B=1, H=3, S=1200, D=128, dtype="bf16", mask="causal", axis="head"),
+    "longer_seq_no_mask_d128": dict(seed=61, B=1, H=2, S=1100, D=128, dtype="bf16", axis="head"),
     "long_seq_bias_d64": dict(seed=49, B=2, H=1, S=516, D=64, dtype="bf16", bias="dense", gated=True, axis="row"),
     "long_seq_bias_causal_d32": dict(seed=50, B=1, H=3, S=520, D=32, dtype="bf16", bias="dense", mask="causal",
                                      axis="head"),
@@ -79,7 +82,7 @@ def test_matches_oracle_for_every_k(name, flags):
         check_against_oracle(cfg, k=k, flags=flags)
 
 
-@pytest.mark.parametrize("name", ["gpt_like", "swin_like", "msa_like", "f32_all"])
+@pytest.mark.parametrize("name", ["gpt_like", "swin_like", "msa_like", "f32_all", "longer_seq_causal_d128"])
 def test_sub_range_and_saved_lse(name):
     cfg = SMALL[name]
     n = cfg["H"] if cfg["axis"] == "head" else cfg["B"]
@@ -89,7 +92,8 @@ def test_sub_range_and_saved_lse(name):
 
 @pytest.mark.parametrize("name", ["gpt_like", "swin_like", "msa_like", "tiny_mha", "bias_causal_d64",
                                   "short_dense_causal", "long_rows_many_groups", "long_seq_few_heads",
-                                  "long_seq_no_mask_d128", "long_seq_bias_d64", "swin_head_axis", "tri_end_like", "dbias_two_heads"])
+                                  "long_seq_no_mask_d128", "long_seq_bias_d64", "swin_head_axis", "tri_end_like", "dbias_two_heads",
+                                  "longer_seq_causal_d128", "longer_seq_no_mask_d128"])
 def test_results_identical_across_k(name):
     cfg = SMALL[name]
     ref = None
@@ -106,7 +110,8 @@ def test_results_identical_across_k(name):
 
 
 @pytest.mark.parametrize("name", ["gpt_like", "long_seq_few_heads", "bias_causal_d64", "long_seq_bias_d64",
-                                  "long_seq_bias_causal_d32", "long_seq_mid_share", "tri_like"])
+                                  "long_seq_bias_causal_d32", "long_seq_mid_share", "tri_like", "longer_seq_causal_d128",
+                                  "longer_seq_no_mask_d128"])
 def test_rising_scores_raise_the_running_maximum(name):
     """Keys grow by powers of two along the sequence, so the row maximum jumps by far more than the
     lazy-rescale threshold several times per row: the accumulated output has to be rescaled while
@@ -126,7 +131,7 @@ def test_rising_scores_raise_the_running_maximum(name):
 
 
 @pytest.mark.parametrize("name", ["long_seq_few_heads", "long_seq_no_mask_d128", "long_seq_bias_d64", "gpt_like",
-                                  "tri_like", "swin_like"])
+                                  "tri_like", "swin_like", "longer_seq_causal_d128", "longer_seq_no_mask_d128"])
 def test_rows_past_the_sequence_end_are_never_used(name):
     """Ragged S: the staged tiles extend past row S-1.  Every activation is followed in memory by a
     NaN-filled batch, so anything read past the end of the last batch and used would poison the result."""
