@@ -12,16 +12,22 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libss_attn.so")
-SOURCES = ["api.hip", "generic_kernels.hip", "mfma_kernels.hip", "small_kernels.hip", "fast_fwd.hip", "fast_dq.hip", "fast_wave_fwd.hip", "fast_wave_bwd.hip", "fast_wave_bwd2.hip", "ffn_kernels.hip", "ffn_api.hip", "planner.hip",
+SOURCES = ["api.hip", "generic_kernels.hip", "mfma_kernels.hip", "small_kernels.hip", "fast_fwd.hip", "fast_dq.hip", "fast_wave_fwd.hip", "fast_wave_fwd128.hip", "fast_wave_bwd.hip", "fast_wave_bwd2.hip", "ffn_kernels.hip", "ffn_api.hip", "planner.hip",
            "fast_dkdv.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-command-line-argument"]
 
 
+# Sources that use no accumulation registers: matrix instructions in their vector-register form, so
+# that all of a wavefront's registers are vector registers (see the header of fast_wave_fwd128.hip).
+VGPR_FORM = ["-mllvm", "-amdgpu-mfma-vgpr-form=1"]
+EXTRA_FLAGS = {"fast_wave_fwd128.hip": VGPR_FORM}
+
+
 def _compile(src: str, objdir: str) -> str:
     obj = os.path.join(objdir, src.replace(".hip", ".o"))
-    cmd = ["hipcc", *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+    cmd = ["hipcc", *FLAGS, *EXTRA_FLAGS.get(src, []), "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     err = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l)
     if r.returncode != 0:

@@ -289,7 +289,7 @@ hipError_t launch_fast_fwd_wave(const KP& p, bool recompute, hipStream_t st) {
   switch (p.D) {
     case 32: return fwd_wave_d<32>(p, recompute, st);
     case 64: return fwd_wave_d<64>(p, recompute, st);
-    case 128: return fwd_wave_d<128>(p, recompute, st);
+    case 128: return launch_fast_fwd_wave128(p, recompute, st);
     default: return hipErrorInvalidValue;
   }
 }
