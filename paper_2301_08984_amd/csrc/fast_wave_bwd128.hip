@@ -143,6 +143,9 @@ __device__ __forceinline__ void dq2_block(const KP& p, char* smem, int rank, int
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) sa = mfma(w_frag(fk[ks]), w_frag(qf[ks]), sa);
     }
+    // the transposed fragments of K arrive under the arithmetic on the scores
+    u32x2 kt[2][2 * DB];
+    w_tr_issue<0>(kt, va);
     if ((j * SUB + SUB > p.S) || (CAUSAL && j * SUB + SUB - 1 > q0)) {
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
@@ -159,8 +162,6 @@ __device__ __forceinline__ void dq2_block(const KP& p, char* smem, int rank, int
       df[0] = pack8(&ds[0]);
       df[1] = pack8(&ds[8]);
     }
-    u32x2 kt[2][2 * DB];
-    w_tr_issue<0>(kt, va);
     w_tr_wait(kt);
     w_fetch(t0, Kb, next, slice, goff);
 #pragma unroll
@@ -281,6 +282,14 @@ __device__ __forceinline__ void kv2_block(const KP& p, char* smem, int rank, int
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) sa = mfma(w_frag(fq[ks]), w_frag(kf[ks]), sa);
     }
+    // the transposed fragments of the late tile arrive under the arithmetic on the scores
+    u32x2 tf[2][2 * DB];
+    if (DK) {
+      w_tr_issue<0>(tf, va);
+    } else {
+      W_VMCNT(9);  // the late tile (dO) has landed
+      w_tr_issue<W_TILE_B>(tf, va);
+    }
     if ((j * SUB + SUB > p.S) || (k0 + 32 > p.S) || (CAUSAL && j * SUB < k0 + 31)) {
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
@@ -317,18 +326,10 @@ __device__ __forceinline__ void kv2_block(const KP& p, char* smem, int rank, int
       of[0] = pack8(&x[0]);
       of[1] = pack8(&x[8]);
     }
-    // dK += Q^T dS, dV += dO^T P: transposed reads of the late tile, which is then refilled
-    u32x2 tf[2][2 * DB];
-    if (DK) {
-      w_tr_issue<0>(tf, va);
-      w_tr_wait(tf);
-      w_fetch(t0, Qb, (uint32_t)(jn * SUB) * ss2, slice, goff);
-    } else {
-      W_VMCNT(9);  // the late tile (dO) has landed
-      w_tr_issue<W_TILE_B>(tf, va);
-      w_tr_wait(tf);
-      fetch_do(t1, (uint32_t)(jn * SUB) * dss2);
-    }
+    // dK += Q^T dS, dV += dO^T P; the late tile is refilled
+    w_tr_wait(tf);
+    if (DK) w_fetch(t0, Qb, (uint32_t)(jn * SUB) * ss2, slice, goff);
+    else fetch_do(t1, (uint32_t)(jn * SUB) * dss2);
 #pragma unroll
     for (int hb = 0; hb < 2; ++hb)
 #pragma unroll
