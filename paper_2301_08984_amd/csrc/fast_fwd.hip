@@ -327,6 +327,8 @@ hipError_t fwd_d(const KP& p, bool recompute, hipStream_t st) {
 hipError_t launch_fast_fwd(const KP& p, bool recompute, hipStream_t st) {
   // small shares: 32-query work-groups whose wavefronts split the keys
   if (wg_shape(p) == WG_2x4) return launch_fast_fwd_wave(p, recompute, st);
+  // large shares at head size 128 without a bias: tiles straight into LDS
+  if (p.D == 128 && p.bias_kind == 0 && wg_shape(p) == WG_4x1) return launch_fast_fwd128(p, recompute, st);
   SS_FAST_DISPATCH_D(fwd_d, p, recompute, st)
 }
 
