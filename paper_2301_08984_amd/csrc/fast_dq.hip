@@ -215,6 +215,10 @@ hipError_t dq_d(const KP& p, hipStream_t st) {
     case 128: return fn<128>(__VA_ARGS__);        \
     default: return hipErrorInvalidValue;         \
   }
-hipError_t launch_fast_dq(const KP& p, hipStream_t st) { SS_FAST_DISPATCH_D(dq_d, p, st) }
+hipError_t launch_fast_dq(const KP& p, hipStream_t st) {
+  // large shares at head size 128 without a bias: tiles straight into LDS
+  if (p.D == 128 && p.bias_kind == 0 && wg_shape(p) == WG_4x1) return launch_fast_dq128(p, st);
+  SS_FAST_DISPATCH_D(dq_d, p, st)
+}
 
 }  // namespace ssa
