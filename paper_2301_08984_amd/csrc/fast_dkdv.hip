@@ -436,7 +436,11 @@ hipError_t dbias_d(const KP& p, hipStream_t st) {
     case 128: return fn<128>(__VA_ARGS__);        \
     default: return hipErrorInvalidValue;         \
   }
-hipError_t launch_fast_dkdv(const KP& p, hipStream_t st) { SS_FAST_DISPATCH_D(dkdv_d, p, st) }
+hipError_t launch_fast_dkdv(const KP& p, hipStream_t st) {
+  // large shares at head size 128 without a bias: one gradient per work-group, tiles straight into LDS
+  if (p.D == 128 && p.bias_kind == 0 && wg_shape(p) == WG_4x1) return launch_fast_kv128(p, st);
+  SS_FAST_DISPATCH_D(dkdv_d, p, st)
+}
 hipError_t launch_fast_dbias(const KP& p, hipStream_t st) { SS_FAST_DISPATCH_D(dbias_d, p, st) }
 
 hipError_t launch_bias_transpose(const void* bias, void* biasT, int S, int h0, int h1, hipStream_t st) {

@@ -315,6 +315,7 @@ hipError_t launch_fast_fwd128(const KP& p, bool recompute, hipStream_t st);
 hipError_t launch_fast_dq(const KP& p, hipStream_t st);
 hipError_t launch_fast_dq128(const KP& p, hipStream_t st);
 hipError_t launch_fast_dkdv(const KP& p, hipStream_t st);
+hipError_t launch_fast_kv128(const KP& p, hipStream_t st);
 hipError_t launch_fast_fwd_wave(const KP& p, bool recompute, hipStream_t st);
 hipError_t launch_fast_fwd_wave128(const KP& p, bool recompute, hipStream_t st);
 hipError_t launch_fast_bwd_wave(const KP& p, hipStream_t st);

@@ -16,7 +16,7 @@ import pytest
 
 from paper_2301_08984_amd import build as B
 
-FILES = ["fast_wave_fwd128.hip", "fast_wave_bwd128.hip", "fast_fwd128.hip", "fast_dq128.hip"]
+FILES = ["fast_wave_fwd128.hip", "fast_wave_bwd128.hip", "fast_fwd128.hip", "fast_dq128.hip", "fast_kv128.hip"]
 
 
 def _regs(tok):
