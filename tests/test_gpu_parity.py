@@ -58,6 +58,10 @@ SMALL = {
                          layout="sbhd"),
     "gpt_like_transposed": dict(seed=55, B=2, H=2, S=600, D=128, dtype="bf16", mask="causal", axis="head",
                                 layout="sbhd"),
+    # head size 128 at a short ragged length with the two leading axes swapped: the tiles-straight-into-LDS
+    # kernels of the large shares with another row stride
+    "d128_transposed_short": dict(seed=62, B=3, H=2, S=300, D=128, dtype="bf16", mask="causal", axis="row",
+                                  layout="sbhd"),
     "swin_like_transposed": dict(seed=56, B=20, H=4, S=49, D=32, dtype="bf16", bias="relpos", win=(7, 7),
                                  mask="region", axis="row", layout="sbhd"),
     # the paper's own split axis for window attention: heads (Section 2)
@@ -93,7 +97,7 @@ def test_sub_range_and_saved_lse(name):
 @pytest.mark.parametrize("name", ["gpt_like", "swin_like", "msa_like", "tiny_mha", "bias_causal_d64",
                                   "short_dense_causal", "long_rows_many_groups", "long_seq_few_heads",
                                   "long_seq_no_mask_d128", "long_seq_bias_d64", "swin_head_axis", "tri_end_like", "dbias_two_heads",
-                                  "longer_seq_causal_d128", "longer_seq_no_mask_d128"])
+                                  "longer_seq_causal_d128", "longer_seq_no_mask_d128", "d128_transposed_short"])
 def test_results_identical_across_k(name):
     cfg = SMALL[name]
     ref = None
@@ -131,7 +135,8 @@ def test_rising_scores_raise_the_running_maximum(name):
 
 
 @pytest.mark.parametrize("name", ["long_seq_few_heads", "long_seq_no_mask_d128", "long_seq_bias_d64", "gpt_like",
-                                  "tri_like", "swin_like", "longer_seq_causal_d128", "longer_seq_no_mask_d128"])
+                                  "tri_like", "swin_like", "longer_seq_causal_d128", "longer_seq_no_mask_d128",
+                                  "d128_gated", "d128_transposed_short"])
 def test_rows_past_the_sequence_end_are_never_used(name):
     """Ragged S: the staged tiles extend past row S-1.  Every activation is followed in memory by a
     NaN-filled batch, so anything read past the end of the last batch and used would poison the result."""
