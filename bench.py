@@ -38,12 +38,13 @@ BOUND = {"gpt3_shard": "mfma", "gpt3_long": "mfma", "gpt3_long_16k": "mfma", "sw
 # is two kernels the scores and dP are counted once, half with each; the recompute pass and the score
 # recompute of the bias-gradient kernel are not part of the method's count.
 CONTRACTIONS = {"fwd": 2, "recompute": 0, "dq": 2, "dkdv": 3, "dbias": 0, "table_reduce": 0, "dq_dkdv": 5,
-                "dbias_fold": 0}
+                "dbias_fold": 0, "recompute_dq": 2}
 # contractions a kernel actually executes on the matrix cores (scores and dP are formed again by
 # every kernel that needs them)
 EXECUTED = {"fwd": 2, "recompute": 2, "dq": 3, "dkdv": 4, "dbias": 2, "table_reduce": 0, "dq_dkdv": 8,
-            "dbias_fold": 0}
-# ("dq_dkdv": the one-gradient-per-work-group launch forms the scores three times and dP twice: 3 + 2 + 3)
+            "dbias_fold": 0, "recompute_dq": 5}
+# ("dq_dkdv": the one-gradient-per-work-group launch forms the scores three times and dP twice: 3 + 2 + 3;
+# "recompute_dq": scores, dP, the value product and the two products that combine into dQ)
 
 
 def executed_table(w):
@@ -59,7 +60,7 @@ def executed_table(w):
 # conversion 1 = 8; backward = score fma 1 + exp2 4 + (dP - Delta) 1 + times P 1 + two conversions 2
 # = 9, + 1 for the bias-gradient addition.  Recomputation is not counted.
 VALU_SLOTS = {"fwd": 8, "recompute": 0, "dq": 4.5, "dkdv": 4.5, "dbias": 1, "table_reduce": 0, "dq_dkdv": 9,
-              "dbias_fold": 0}
+              "dbias_fold": 0, "recompute_dq": 4.5}
 
 
 def visible_fraction(w):
@@ -99,6 +100,7 @@ def kernel_bytes(w, name, units, axis_extent):
         "dq": 5 * T + nb + 2 * stat,
         "dkdv": 6 * T + nb + 2 * stat,
         "dq_dkdv": 7 * T + nb + 2 * stat,
+        "recompute_dq": (5 + g) * T + 2 * g * T + nb + 2 * stat,
         "dbias": 4 * T + nb + 2 * stat + (w["H"] * w["S"] ** 2 * 4 if w["bias"] else 0),
         "table_reduce": w["H"] * w["S"] ** 2 * 4,
         "dbias_fold": 3 * w["H"] * w["S"] ** 2 * 4,

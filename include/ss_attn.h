@@ -177,7 +177,8 @@ typedef enum {
   SS_K_FWD = 0, SS_K_RECOMPUTE = 1, SS_K_DQ = 2, SS_K_DKDV = 3, SS_K_DBIAS = 4, SS_K_TABLE_REDUCE = 5,
   SS_K_DQ_DKDV = 6,   /* dQ and dK/dV in one launch (small shares with long rows) */
   SS_K_DBIAS_FOLD = 7, /* fold of completed bias-gradient group partials into the result */
-  SS_K_COUNT = 8
+  SS_K_RECOMPUTE_DQ = 8, /* recompute pass and dQ in one launch (head size 32, large shares) */
+  SS_K_COUNT = 9
 } ss_kernel_id;
 int ss_attn_profile_enable(int on);
 int ss_attn_profile_read(int kernel, double* total_ms, int64_t* launches);

@@ -26,8 +26,8 @@ EXPORTS = ("ss_attn_workspace_bytes", "ss_attn_chunk_range", "ss_attn_fwd", "ss_
            "ss_strerror",
            "ss_attn_kernel_family", "ss_attn_profile_enable", "ss_attn_profile_read")
 (SS_K_FWD, SS_K_RECOMPUTE, SS_K_DQ, SS_K_DKDV, SS_K_DBIAS, SS_K_TABLE_REDUCE, SS_K_DQ_DKDV, SS_K_DBIAS_FOLD,
- SS_K_COUNT) = range(9)
-KERNEL_NAMES = ("fwd", "recompute", "dq", "dkdv", "dbias", "table_reduce", "dq_dkdv", "dbias_fold")
+ SS_K_RECOMPUTE_DQ, SS_K_COUNT) = range(10)
+KERNEL_NAMES = ("fwd", "recompute", "dq", "dkdv", "dbias", "table_reduce", "dq_dkdv", "dbias_fold", "recompute_dq")
 
 
 class ss_attn_desc(C.Structure):

@@ -12,7 +12,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libss_attn.so")
-SOURCES = ["api.hip", "generic_kernels.hip", "mfma_kernels.hip", "small_kernels.hip", "fast_fwd.hip", "fast_fwd128.hip", "fast_dq.hip", "fast_dq128.hip", "fast_kv128.hip", "fast_wave_fwd.hip", "fast_wave_fwd128.hip", "fast_wave_bwd.hip", "fast_wave_bwd128.hip", "ffn_kernels.hip", "ffn_api.hip", "planner.hip",
+SOURCES = ["api.hip", "generic_kernels.hip", "mfma_kernels.hip", "small_kernels.hip", "fast_fwd.hip", "fast_fwd128.hip", "fast_dq.hip", "fast_rdq.hip", "fast_dq128.hip", "fast_kv128.hip", "fast_wave_fwd.hip", "fast_wave_fwd128.hip", "fast_wave_bwd.hip", "fast_wave_bwd128.hip", "ffn_kernels.hip", "ffn_api.hip", "planner.hip",
            "fast_dkdv.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -414,12 +414,17 @@ int ss_attn_bwd(const ss_attn_desc* d, const void* Q, const void* K, const void*
       continue;
     }
     if (mfma) {
-      SS_LAUNCH(SS_K_RECOMPUTE, ssa::launch_mfma_fwd(p, true, st), "recompute");
-      if (ssa::mfma_fuses_dq_dkdv(p)) {
-        SS_LAUNCH(SS_K_DQ_DKDV, ssa::launch_mfma_dq_dkdv(p, st), "dQ + dK/dV");
-      } else {
-        SS_LAUNCH(SS_K_DQ, ssa::launch_mfma_dq(p, st), "dQ");
+      if (ssa::mfma_fuses_recompute_dq(p)) {
+        SS_LAUNCH(SS_K_RECOMPUTE_DQ, ssa::launch_mfma_recompute_dq(p, st), "recompute + dQ");
         SS_LAUNCH(SS_K_DKDV, ssa::launch_mfma_dkdv(p, st), "dK/dV");
+      } else {
+        SS_LAUNCH(SS_K_RECOMPUTE, ssa::launch_mfma_fwd(p, true, st), "recompute");
+        if (ssa::mfma_fuses_dq_dkdv(p)) {
+          SS_LAUNCH(SS_K_DQ_DKDV, ssa::launch_mfma_dq_dkdv(p, st), "dQ + dK/dV");
+        } else {
+          SS_LAUNCH(SS_K_DQ, ssa::launch_mfma_dq(p, st), "dQ");
+          SS_LAUNCH(SS_K_DKDV, ssa::launch_mfma_dkdv(p, st), "dK/dV");
+        }
       }
       if (want_dbias) {
         if (w.gw > 0) {  // grouped sum: partials in the workspace, folded into the result as the groups complete

@@ -77,6 +77,8 @@ hipError_t launch_mfma_dkdv(const KP& p, hipStream_t st);
 hipError_t launch_mfma_dbias(const KP& p, hipStream_t st);
 bool mfma_fuses_dq_dkdv(const KP& p);
 hipError_t launch_mfma_dq_dkdv(const KP& p, hipStream_t st);
+bool mfma_fuses_recompute_dq(const KP& p);
+hipError_t launch_mfma_recompute_dq(const KP& p, hipStream_t st);
 bool mfma_wants_bias_transpose(const KP& p);
 int mfma_dbias_group_rows(const KP& p);        // 0, or rows per group of the grouped bias-gradient sum  // the backward kernels read a transposed bias copy
 hipError_t launch_bias_transpose(const void* bias, void* biasT, int S, int h0, int h1, hipStream_t st);

@@ -252,12 +252,11 @@ __device__ inline float fwd_epilogue_block(const KP& p, const f32x16& o16, int d
 }
 
 // forward epilogue: normalise, gate, store Y (and LSE); recompute mode: gate gradient,
-// pre-gated dO copy, Delta = rowsum(dO*O) and LSE into the workspace
+// pre-gated dO copy, Delta = rowsum(dO*O) and LSE into the workspace.  `l` is the complete row sum.
 template <int DB, bool RECOMP>
-__device__ inline void fwd_epilogue(const KP& p, f32x16 (&oacc)[DB], float m, float l, int b, int h, int q,
-                                    int hl, int64_t base) {
+__device__ inline void fwd_epilogue_rowsum(const KP& p, f32x16 (&oacc)[DB], float m, float l, int b, int h, int q,
+                                           int hl, int64_t base) {
   if (q >= p.S) return;
-  l = half_sum(l);
   const float inv = 1.f / l;
   const float lse = (m + log2f(l)) * LN2;
   float part = 0.f;
@@ -272,6 +271,13 @@ __device__ inline void fwd_epilogue(const KP& p, f32x16 (&oacc)[DB], float m, fl
       if (p.lse_out) p.lse_out[(int64_t)(b - p.lse_b0) * p.lse_sb + (int64_t)(h - p.lse_h0) * p.lse_sh + q] = lse;
     }
   }
+}
+// the same with `l` = each half-wave's part of the row sum
+template <int DB, bool RECOMP>
+__device__ inline void fwd_epilogue(const KP& p, f32x16 (&oacc)[DB], float m, float l, int b, int h, int q,
+                                    int hl, int64_t base) {
+  if (q >= p.S) return;
+  fwd_epilogue_rowsum<DB, RECOMP>(p, oacc, m, half_sum(l), b, h, q, hl, base);
 }
 
 // the specialised kernels serve: no bias or a dense bf16 bias with S % 4 == 0; no mask or the
@@ -314,6 +320,7 @@ hipError_t launch_fast_fwd(const KP& p, bool recompute, hipStream_t st);
 hipError_t launch_fast_fwd128(const KP& p, bool recompute, hipStream_t st);
 hipError_t launch_fast_dq(const KP& p, hipStream_t st);
 hipError_t launch_fast_dq128(const KP& p, hipStream_t st);
+hipError_t launch_fast_recompute_dq(const KP& p, hipStream_t st);
 hipError_t launch_fast_dkdv(const KP& p, hipStream_t st);
 hipError_t launch_fast_kv128(const KP& p, hipStream_t st);
 hipError_t launch_fast_fwd_wave(const KP& p, bool recompute, hipStream_t st);

@@ -641,6 +641,10 @@ hipError_t launch_mfma_dq_dkdv(const KP& p, hipStream_t st) {
   if (p.D == 128 && p.bias_kind == 0) return launch_fast_bwd_wave3(p, st);
   return launch_fast_bwd_wave(p, st);
 }
+// head size 32 on the large-share work-group shape: the vector arithmetic per score element binds, and
+// the recompute pass and dQ share all of it
+bool mfma_fuses_recompute_dq(const KP& p) { return fast_ok(p) && p.D == 32 && wg_shape(p) == WG_4x1; }
+hipError_t launch_mfma_recompute_dq(const KP& p, hipStream_t st) { return launch_fast_recompute_dq(p, st); }
 int mfma_dbias_group_rows(const KP& p) { return dbias_group_rows(p); }
 
 }  // namespace ssa

@@ -32,12 +32,14 @@ SS_STUB_LAUNCH(launch_mfma_dq, const KP&, hipStream_t)
 SS_STUB_LAUNCH(launch_mfma_dkdv, const KP&, hipStream_t)
 SS_STUB_LAUNCH(launch_mfma_dbias, const KP&, hipStream_t)
 SS_STUB_LAUNCH(launch_mfma_dq_dkdv, const KP&, hipStream_t)
+SS_STUB_LAUNCH(launch_mfma_recompute_dq, const KP&, hipStream_t)
 SS_STUB_LAUNCH(launch_bias_transpose, const void*, void*, int, int, int, hipStream_t)
 SS_STUB_LAUNCH(launch_gemm, const GemmArgs&, bool, bool, int, hipStream_t)
 SS_STUB_LAUNCH(launch_colsum, const void*, int64_t, int, int, void*, hipStream_t)
 bool small_supported(const KP& p, bool bf16) { return bf16 && p.D == 32 && p.S <= 64 && !p.gated; }
 bool mfma_supported(const KP& p, bool bf16) { return bf16 && (p.D == 32 || p.D == 64 || p.D == 128); }
 bool mfma_fuses_dq_dkdv(const KP&) { return false; }
+bool mfma_fuses_recompute_dq(const KP&) { return false; }
 bool mfma_wants_bias_transpose(const KP& p) { return p.bias_kind == 1 && p.bias_bf16; }
 int mfma_dbias_group_rows(const KP& p) { return p.bias_kind == 1 ? 64 : 0; }
 size_t gemm_acc_bytes(int M, int N) { return (size_t)((M + 255) / 256) * ((N + 255) / 256) * 256 * 256 * sizeof(float); }
