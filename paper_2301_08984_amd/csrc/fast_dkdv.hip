@@ -15,8 +15,8 @@ namespace {
 // Q / dO tiles (64 rows) are double-buffered in LDS, one barrier per tile; the next
 // tile travels global -> registers meanwhile.
 // ---------------------------------------------------------------------------
-template <int D, bool BIAS, bool CAUSAL, int NW>
-__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(D <= 32 ? 2 : 1, D <= 32 ? 2 : 1))) void dkdv_fast_kernel(KP p) {
+template <int D, bool BIAS, bool CAUSAL, int NW, bool SLICE32>
+__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(D <= 32 ? (BIAS && CAUSAL ? 2 : 3) : 1, D <= 32 ? (BIAS && CAUSAL ? 2 : 3) : 1))) void dkdv_fast_kernel(KP p) {
   constexpr int KS = D / 16, DB = D / 32, LD = D + 24, NT = 64 * NW, BK = 32 * NW;  // tiles read both ways
   constexpr int CPR = D / 8, CPT = BN * CPR / NT;
   __shared__ __attribute__((aligned(16))) uint16_t sQ[2][BN * LD];
@@ -60,12 +60,37 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(D <= 32
 
   u32x4 pq[CPT], pg[CPT];
   float pstat = 0.f;
-  auto gload = [&](int qt) {
+  // SLICE32: the (row, head) slices of Q and dO are shorter than 2 GiB (decided on the host).  The
+  // tiles are then fetched with buffer loads whose descriptor starts at the tile and ends with the
+  // slice: lane offsets that never change (no 64-bit address per load), and rows past S - 1 arrive as
+  // zeros: their scores are masked, and their dS is P * (0 - Delta) with P = 0.
+  uint32_t goq[SLICE32 ? CPT : 1], gog[SLICE32 ? CPT : 1];
+  if (SLICE32) {
 #pragma unroll
     for (int c = 0; c < CPT; ++c) {
-      const int idx = tid + c * NT, row = min(qt * BN + idx / CPR, p.S - 1), col = (idx % CPR) * 8;
-      pq[c] = *(const u32x4*)(Qb + (int64_t)row * p.ss + col);
-      pg[c] = *(const u32x4*)(dOb + (int64_t)row * p.do_ss + col);
+      const int idx = tid + c * NT;
+      goq[c] = (uint32_t)(idx / CPR) * ((uint32_t)p.ss * 2u) + (uint32_t)(idx % CPR) * 16u;
+      gog[c] = (uint32_t)(idx / CPR) * ((uint32_t)p.do_ss * 2u) + (uint32_t)(idx % CPR) * 16u;
+    }
+  }
+  auto gload = [&](int qt) {
+    if (SLICE32) {
+      const uint32_t bq = (uint32_t)(qt * BN) * ((uint32_t)p.ss * 2u), bg = (uint32_t)(qt * BN) * ((uint32_t)p.do_ss * 2u);
+      const uint32_t nq = (uint32_t)(((int64_t)(p.S - 1) * p.ss + D) * 2), ng = (uint32_t)(((int64_t)(p.S - 1) * p.do_ss + D) * 2);
+      const __amdgpu_buffer_rsrc_t rq = __builtin_amdgcn_make_buffer_rsrc((void*)((const char*)Qb + bq), 0, (int)(nq - bq), 0x00020000);
+      const __amdgpu_buffer_rsrc_t rg = __builtin_amdgcn_make_buffer_rsrc((void*)((const char*)dOb + bg), 0, (int)(ng - bg), 0x00020000);
+#pragma unroll
+      for (int c = 0; c < CPT; ++c) {
+        pq[c] = __builtin_amdgcn_raw_buffer_load_b128(rq, goq[c], 0, 0);
+        pg[c] = __builtin_amdgcn_raw_buffer_load_b128(rg, gog[c], 0, 0);
+      }
+    } else {
+#pragma unroll
+      for (int c = 0; c < CPT; ++c) {
+        const int idx = tid + c * NT, row = min(qt * BN + idx / CPR, p.S - 1), col = (idx % CPR) * 8;
+        pq[c] = *(const u32x4*)(Qb + (int64_t)row * p.ss + col);
+        pg[c] = *(const u32x4*)(dOb + (int64_t)row * p.do_ss + col);
+      }
     }
     if (tid < 2 * BN) {
       const int i = min(qt * BN + (tid & (BN - 1)), p.S - 1);
@@ -110,12 +135,14 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(D <= 32
       float bl[4] = {0.f, 0.f, 0.f, 0.f};
       if (BIAS) {
         const uint2 u = bz[4 * sub + g];
-        bl[0] = __uint_as_float(u.x << 16) * LOG2E; bl[1] = __uint_as_float(u.x & 0xffff0000u) * LOG2E;
-        bl[2] = __uint_as_float(u.y << 16) * LOG2E; bl[3] = __uint_as_float(u.y & 0xffff0000u) * LOG2E;
+        bl[0] = __uint_as_float(u.x << 16); bl[1] = __uint_as_float(u.x & 0xffff0000u);
+        bl[2] = __uint_as_float(u.y << 16); bl[3] = __uint_as_float(u.y & 0xffff0000u);
       }
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
-        float pe = fast_exp2(fmaf(sa[4 * g + e], c1, BIAS ? bl[e] + l4[e] : l4[e]));
+        // with a bias: natural units first, the change to base 2 rides on the subtraction of the LSE
+        float pe = BIAS ? fast_exp2(fmaf(fmaf(sa[4 * g + e], p.scale, bl[e]), LOG2E, l4[e]))
+                        : fast_exp2(fmaf(sa[4 * g + e], c1, l4[e]));
         if (edge) {
           const int i = i0 + 32 * sub + 8 * g + 4 * hl + e;
           const bool dead = i >= p.S || key >= p.S || (CAUSAL && key > i);
@@ -170,7 +197,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(D <= 32
     // one straight-line block per tile: A0 | A1 with V0 | B0 with V1 | B1, where A = scores and dP
     // on the matrix cores, V = P and dS on the vector ALUs, B = gradient products
     uint2 bz[8];
-    if (BIAS) {
+    if (BIAS && D > 32) {
 #pragma unroll
       for (int j = 0; j < 8; ++j) bz[j] = bt.read(r, 8 * j + 4 * hl);
     }
@@ -180,6 +207,24 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(D <= 32
       // below, where their 128 registers push the transposed operands into the accumulation file
       // (measured: 929 -> 785 us on the long-sequence GPT share; smaller D is faster without)
       if (D >= 128) asm volatile("" ::: "memory");
+      if constexpr (D <= 32) {
+        // Head size 32: the vector arithmetic binds, not the matrix cores.  One sub-block at a time
+        // keeps the wavefront within 168 registers, and the third wavefront per SIMD overlaps more
+        // than the pipeline below does with two
+#pragma unroll
+        for (int sub = 0; sub < 2; ++sub) {
+          f32x16 sa, pa;
+          bf16x8 pf[2], df[2];
+          if (BIAS) {
+#pragma unroll
+            for (int g = 0; g < 4; ++g) bz[4 * sub + g] = bt.read(r, 32 * sub + 8 * g + 4 * hl);
+          }
+          stage_a(tq, tg, sub, sa, pa);
+          stage_v(tl, td, i0, sub, sa, pa, bz, pf, df, edge_tag);
+          stage_b(tq, tg, sub, pf, df);
+        }
+        return;
+      }
       f32x16 sa0, pa0, sa1, pa1;
       bf16x8 pf0[2], df0[2], pf1[2], df1[2];
       stage_a(tq, tg, 0, sa0, pa0);
@@ -391,18 +436,22 @@ __global__ __launch_bounds__(256) void bias_transpose_kernel(const uint16_t* src
 }
 
 
-template <int D, int NW>
+template <int D, int NW, bool SLICE32>
 void dkdv_fast_launch(const KP& p, hipStream_t st) {
   const dim3 g((p.S + 32 * NW - 1) / (32 * NW), p.h1 - p.h0, p.b1 - p.b0);
   const bool bias = p.bias_kind == 1, causal = p.mask_kind == 1;
-  if (bias && causal) dkdv_fast_kernel<D, true, true, NW><<<g, 64 * NW, 0, st>>>(p);
-  else if (bias) dkdv_fast_kernel<D, true, false, NW><<<g, 64 * NW, 0, st>>>(p);
-  else if (causal) dkdv_fast_kernel<D, false, true, NW><<<g, 64 * NW, 0, st>>>(p);
-  else dkdv_fast_kernel<D, false, false, NW><<<g, 64 * NW, 0, st>>>(p);
+  if (bias && causal) dkdv_fast_kernel<D, true, true, NW, SLICE32><<<g, 64 * NW, 0, st>>>(p);
+  else if (bias) dkdv_fast_kernel<D, true, false, NW, SLICE32><<<g, 64 * NW, 0, st>>>(p);
+  else if (causal) dkdv_fast_kernel<D, false, true, NW, SLICE32><<<g, 64 * NW, 0, st>>>(p);
+  else dkdv_fast_kernel<D, false, false, NW, SLICE32><<<g, 64 * NW, 0, st>>>(p);
 }
 template <int D>
 hipError_t dkdv_d(const KP& p, hipStream_t st) {
-  dkdv_fast_launch<D, 4>(p, st);
+  // head size 32 runs three wavefronts per SIMD and has no registers to spare for 64-bit addresses
+  const int64_t lim = 1ll << 31;
+  const bool slice32 = D <= 32 && ((int64_t)(p.S - 1) * p.ss + D) * 2 < lim && ((int64_t)(p.S - 1) * p.do_ss + D) * 2 < lim;
+  if (slice32) dkdv_fast_launch<D, 4, D <= 32>(p, st);
+  else dkdv_fast_launch<D, 4, false>(p, st);
   return hipGetLastError();
 }
 template <int D>

@@ -129,12 +129,14 @@ __attribute__((amdgpu_waves_per_eu(D <= 32 ? (BIAS ? 3 : 4) : 2, D <= 32 ? (BIAS
       for (int g = 0; g < 4; ++g) {
         float bl[4] = {0.f, 0.f, 0.f, 0.f};
         if (BIAS) {
-          bl[0] = __uint_as_float(bz[g].x << 16) * LOG2E; bl[1] = __uint_as_float(bz[g].x & 0xffff0000u) * LOG2E;
-          bl[2] = __uint_as_float(bz[g].y << 16) * LOG2E; bl[3] = __uint_as_float(bz[g].y & 0xffff0000u) * LOG2E;
+          bl[0] = __uint_as_float(bz[g].x << 16); bl[1] = __uint_as_float(bz[g].x & 0xffff0000u);
+          bl[2] = __uint_as_float(bz[g].y << 16); bl[3] = __uint_as_float(bz[g].y & 0xffff0000u);
         }
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          float pe = fast_exp2(fmaf(sa[4 * g + e], c1, bl[e] - lse2));
+          // with a bias: natural units first, the change to base 2 rides on the subtraction of the LSE
+          float pe = BIAS ? fast_exp2(fmaf(fmaf(sa[4 * g + e], p.scale, bl[e]), LOG2E, -lse2))
+                          : fast_exp2(fmaf(sa[4 * g + e], c1, -lse2));
           if (edge) {
             const int key = k0 + 32 * kb + 8 * g + 4 * hl + e;
             const bool dead = key >= p.S || (CAUSAL && key > q);

@@ -7,6 +7,8 @@
 namespace ssa {
 namespace {
 
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+
 // ---------------------------------------------------------------------------
 // A query block walks its keys once and leaves O (for Delta, the gate gradient and the pre-gated
 // dO copy), the softmax statistics AND dQ, instead of once for the statistics and once more for dQ
@@ -16,19 +18,22 @@ namespace {
 // so two products are accumulated (A1 with p~ dP, A2 with p~) and combined at the end.  The
 // two terms cancel where a row is peaked (dS -> 0), so Delta' must be the mean the matrix cores
 // actually formed: Delta' = sum_j bf16(p~ dP) / sum_j bf16(p~), both sums over the SAME rounded
-// operands that went into A1 and A2.  They come from the matrix cores as well: one more accumulator
-// whose row operand is all ones in rows 0..15 (times bf16(p~): every such row is l') or in rows
-// 16..31 (times bf16(p~ dP): delta'), so a one-hot row gives A1 - Delta' A2 = 0 up to the rounding
-// of one division, and nothing is paid in vector instructions.  l' also normalises O and gives the
-// LSE, so the row sum costs no vector addition either.  The other backward kernels use Delta =
-// rowsum(dO * O) from the epilogue as before.
+// operands that went into A1 and A2 (a one-hot row then gives A1 - Delta' A2 = 0 up to the rounding
+// of one division; with the mean of the unrounded values the error of such rows is 2^-9 |dP| |K|).
+// The packed operands are summed pairwise by v_dot2c_f32_bf16 against (1, 1): half an instruction
+// per element and sum.  l' = sum_j bf16(p~) also normalises O and gives the LSE, so the row sum
+// costs no separate addition.  The other backward kernels use Delta = rowsum(dO * O) from the
+// epilogue as before.
 //
 // Work-group: four wavefronts of 32 queries sharing 64-key K / V tiles (two buffers, one barrier per
 // tile), as the forward kernel for large shares; K and V are both read as stored (scores, dP) and
-// transposed (A1 / A2, O).
+// transposed (A1 / A2, O).  A tile is taken as two 32-key blocks, each a complete online-softmax
+// step: that and 32-bit buffer offsets keep a wavefront within 168 registers, and three wavefronts
+// per SIMD overlap the vector and matrix work better than a longer software pipeline does with two
+// (measured on the triangle shape: 141 against 158 us per launch).
 // ---------------------------------------------------------------------------
 template <int D, bool BIAS, bool CAUSAL>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void rdq_fast_kernel(KP p) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(BIAS && CAUSAL ? 2 : 3, BIAS && CAUSAL ? 2 : 3))) void rdq_fast_kernel(KP p) {
   constexpr int KS = D / 16, DB = D / 32, NT = 256, BM = 128;
   constexpr int LDT = D + 24;  // conflict-free for b128 and transposed reads
   constexpr int CPR = D / 8, CPT = BN * CPR / NT;
@@ -44,7 +49,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   const int q0 = qblk + 32 * w, q = q0 + r;
   const int qc = min(q, p.S - 1);
   const int64_t base = (int64_t)b * p.sb + (int64_t)h * p.sh;
-  const uint16_t* Qb = (const uint16_t*)p.Q + base;
   const uint16_t* Kb = (const uint16_t*)p.K + base;
   const uint16_t* Vb = (const uint16_t*)p.V + base;
   BiasTile bt;
@@ -76,19 +80,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
       gf[ks] = o.v;
     }
   }
-  // row operands of the sums: ones in rows 0..15 (-> l') and in rows 16..31 (-> delta')
-  bf16x8 ones_lo, ones_hi;
-  {
-    union { u32x4 u; bf16x8 v; } a, c;
-    const uint32_t lo = r < 16 ? 0x3f803f80u : 0u, hi = r < 16 ? 0u : 0x3f803f80u;
-    a.u = u32x4{lo, lo, lo, lo};
-    c.u = u32x4{hi, hi, hi, hi};
-    ones_lo = a.v;
-    ones_hi = c.v;
-  }
-  f32x16 oacc[DB], a1[DB], a2[DB], sums;
-#pragma unroll
-  for (int v = 0; v < 16; ++v) sums[v] = 0.f;
+  union { uint32_t u; bf16x2 v; } one_pair;
+  one_pair.u = 0x3f803f80u;
+  const bf16x2 ones2 = one_pair.v;
+  f32x16 oacc[DB], a1[DB], a2[DB];
+  float lsum = 0.f, dsum = 0.f;  // this half-wave's part of l' and delta'
 #pragma unroll
   for (int db = 0; db < DB; ++db)
 #pragma unroll
@@ -102,13 +98,26 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   if (CAUSAL) wtiles = min(ntiles, (min(q0 + 32, p.S) + BN - 1) / BN);
   if (q0 >= p.S) wtiles = 0;
 
+  // K / V tiles are fetched with buffer loads whose descriptor starts at the tile and ends with the
+  // (row, head) slice: the lane offsets never change, and rows past S - 1 arrive as zeros (their
+  // scores are masked, their dP is 0 * 0).  The slice is shorter than 2 GiB (checked on the host).
+  const uint32_t ss2 = (uint32_t)p.ss * 2u;
+  const uint32_t slice = (uint32_t)(((int64_t)(p.S - 1) * p.ss + D) * 2);
+  uint32_t goff[CPT];
+#pragma unroll
+  for (int c = 0; c < CPT; ++c) {
+    const int idx = tid + c * NT;
+    goff[c] = (uint32_t)(idx / CPR) * ss2 + (uint32_t)(idx % CPR) * 16u;
+  }
   u32x4 pk[CPT], pv[CPT];
   auto gload = [&](int kt) {
+    const uint32_t boff = (uint32_t)(kt * BN) * ss2;  // kt * BN < S
+    const __amdgpu_buffer_rsrc_t rk = __builtin_amdgcn_make_buffer_rsrc((void*)((const char*)Kb + boff), 0, (int)(slice - boff), 0x00020000);
+    const __amdgpu_buffer_rsrc_t rv = __builtin_amdgcn_make_buffer_rsrc((void*)((const char*)Vb + boff), 0, (int)(slice - boff), 0x00020000);
 #pragma unroll
     for (int c = 0; c < CPT; ++c) {
-      const int idx = tid + c * NT, row = min(kt * BN + idx / CPR, p.S - 1), col = (idx % CPR) * 8;
-      pk[c] = *(const u32x4*)(Kb + (int64_t)row * p.ss + col);
-      pv[c] = *(const u32x4*)(Vb + (int64_t)row * p.ss + col);
+      pk[c] = __builtin_amdgcn_raw_buffer_load_b128(rk, goff[c], 0, 0);
+      pv[c] = __builtin_amdgcn_raw_buffer_load_b128(rv, goff[c], 0, 0);
     }
   };
   auto stage = [&](uint16_t* dK) {
@@ -120,103 +129,106 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
       *(u32x4*)(dV + row * LDT + col) = pv[c];
     }
   };
-  // one key tile (K at sK, V behind it): scores and dP, online softmax, the four products and the sums
-  auto tile = [&](const uint16_t* sK, int k0) {
+  // one 32-key block of a tile (K at sK, V behind it): scores and dP, online softmax, the three products and the sums
+  auto block = [&](const uint16_t* sK, int kb, int k0) {
     const uint16_t* sV = sK + BN * LDT;
-    f32x16 sa[2], pa[2];
+    f32x16 sa, pa;
     {
-      bf16x8 fk[2][KS], fv[2][KS];
+      bf16x8 fk[KS], fv[KS];
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
-        fk[0][ks] = lds_nat<LDT>(sK, r, ks, hl);
-        fk[1][ks] = lds_nat<LDT>(sK, 32 + r, ks, hl);
-        fv[0][ks] = lds_nat<LDT>(sV, r, ks, hl);
-        fv[1][ks] = lds_nat<LDT>(sV, 32 + r, ks, hl);
+        fk[ks] = lds_nat<LDT>(sK, 32 * kb + r, ks, hl);
+        fv[ks] = lds_nat<LDT>(sV, 32 * kb + r, ks, hl);
       }
 #pragma unroll
-      for (int v = 0; v < 16; ++v) { sa[0][v] = 0.f; sa[1][v] = 0.f; pa[0][v] = 0.f; pa[1][v] = 0.f; }
+      for (int v = 0; v < 16; ++v) { sa[v] = 0.f; pa[v] = 0.f; }
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
-        sa[0] = mfma(fk[0][ks], qf[ks], sa[0]);
-        sa[1] = mfma(fk[1][ks], qf[ks], sa[1]);
-        pa[0] = mfma(fv[0][ks], gf[ks], pa[0]);
-        pa[1] = mfma(fv[1][ks], gf[ks], pa[1]);
+        sa = mfma(fk[ks], qf[ks], sa);
+        pa = mfma(fv[ks], gf[ks], pa);
       }
     }
     if (BIAS) {
 #pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          const uint2 u = bt.read(r, 32 * kb + 8 * g + 4 * hl);
-          // natural units here; the change to base 2 rides on the subtraction of the maximum below
-          sa[kb][4 * g + 0] = fmaf(sa[kb][4 * g + 0], p.scale, __uint_as_float(u.x << 16));
-          sa[kb][4 * g + 1] = fmaf(sa[kb][4 * g + 1], p.scale, __uint_as_float(u.x & 0xffff0000u));
-          sa[kb][4 * g + 2] = fmaf(sa[kb][4 * g + 2], p.scale, __uint_as_float(u.y << 16));
-          sa[kb][4 * g + 3] = fmaf(sa[kb][4 * g + 3], p.scale, __uint_as_float(u.y & 0xffff0000u));
-        }
+      for (int g = 0; g < 4; ++g) {
+        const uint2 u = bt.read(r, 32 * kb + 8 * g + 4 * hl);
+        // natural units here; the change to base 2 rides on the subtraction of the maximum below
+        sa[4 * g + 0] = fmaf(sa[4 * g + 0], p.scale, __uint_as_float(u.x << 16));
+        sa[4 * g + 1] = fmaf(sa[4 * g + 1], p.scale, __uint_as_float(u.x & 0xffff0000u));
+        sa[4 * g + 2] = fmaf(sa[4 * g + 2], p.scale, __uint_as_float(u.y << 16));
+        sa[4 * g + 3] = fmaf(sa[4 * g + 3], p.scale, __uint_as_float(u.y & 0xffff0000u));
+      }
     }
-    if ((k0 + BN > p.S) || (CAUSAL && k0 + BN - 1 > q0)) {
+    if ((k0 + 32 > p.S) || (CAUSAL && k0 + 31 > q0)) {
 #pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int key = k0 + 32 * kb + key_of(v, hl);
-          const bool dead = key >= p.S || (CAUSAL && key > q);
-          sa[kb][v] = dead ? -INFINITY : sa[kb][v];
-        }
+      for (int v = 0; v < 16; ++v) {
+        const int key = k0 + key_of(v, hl);
+        const bool dead = key >= p.S || (CAUSAL && key > q);
+        sa[v] = dead ? -INFINITY : sa[v];
+      }
     }
     float rmax = -INFINITY;
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) rmax = fmaxf(rmax, sa[kb][v]);
+    for (int v = 0; v < 16; ++v) rmax = fmaxf(rmax, sa[v]);
     rmax *= BIAS ? LOG2E : c1;  // the running maximum is kept in base-2 units; scale > 0 on this path
     rmax = half_max(rmax);
     // the running maximum is raised only when exceeded by more than 2^8, so the rescale is skipped
-    // on most tiles; probabilities stay below 2^8, harmless in fp32/bf16 range
+    // on most blocks; probabilities stay below 2^8, harmless in fp32/bf16 range
     if (__builtin_amdgcn_ballot_w64(rmax > m + 8.f) != 0) {
       const float mn = fmaxf(m, rmax);
       const float alpha = fast_exp2(m - mn);
       m = mn;
-#pragma unroll
-      for (int v = 0; v < 16; ++v) sums[v] *= alpha;
+      lsum *= alpha;
+      dsum *= alpha;
 #pragma unroll
       for (int db = 0; db < DB; ++db)
 #pragma unroll
         for (int v = 0; v < 16; ++v) { oacc[db][v] *= alpha; a1[db][v] *= alpha; a2[db][v] *= alpha; }
     }
-    bf16x8 pf[4], df[4];
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb) {
+    bf16x8 pf[2], df[2];
+    {
       float pr[16], dp[16];
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
-        pr[v] = fast_exp2(fmaf(sa[kb][v], BIAS ? LOG2E : c1, -m));
-        dp[v] = pr[v] * pa[kb][v];
+        pr[v] = fast_exp2(fmaf(sa[v], BIAS ? LOG2E : c1, -m));
+        dp[v] = pr[v] * pa[v];
       }
-      pf[2 * kb] = pack8(&pr[0]);
-      pf[2 * kb + 1] = pack8(&pr[8]);
-      df[2 * kb] = pack8(&dp[0]);
-      df[2 * kb + 1] = pack8(&dp[8]);
+      pf[0] = pack8(&pr[0]);
+      pf[1] = pack8(&pr[8]);
+      df[0] = pack8(&dp[0]);
+      df[1] = pack8(&dp[8]);
+    }
+    // the sums run over the rounded operands
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      union { bf16x8 v; bf16x2 h[4]; } a, c;
+      a.v = pf[j];
+      c.v = df[j];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        lsum = __builtin_amdgcn_fdot2_f32_bf16(a.h[e], ones2, lsum, false);
+        dsum = __builtin_amdgcn_fdot2_f32_bf16(c.h[e], ones2, dsum, false);
+      }
     }
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
+    for (int j = 0; j < 2; ++j) {
       bf16x8 vt[DB], kt[DB];
 #pragma unroll
       for (int db = 0; db < DB; ++db) {
-        vt[db] = lds_tr<LDT>(sV, 16 * j, 32 * db, lane);
-        kt[db] = lds_tr<LDT>(sK, 16 * j, 32 * db, lane);
+        vt[db] = lds_tr<LDT>(sV, 32 * kb + 16 * j, 32 * db, lane);
+        kt[db] = lds_tr<LDT>(sK, 32 * kb + 16 * j, 32 * db, lane);
       }
-      sums = mfma(ones_lo, pf[j], sums);
 #pragma unroll
       for (int db = 0; db < DB; ++db) {
         oacc[db] = mfma(vt[db], pf[j], oacc[db]);
         a2[db] = mfma(kt[db], pf[j], a2[db]);
         a1[db] = mfma(kt[db], df[j], a1[db]);
       }
-      sums = mfma(ones_hi, df[j], sums);
     }
+  };
+  auto tile = [&](const uint16_t* sK, int k0) {
+    block(sK, 0, k0);
+    block(sK, 1, k0 + 32);
   };
 
   // two tile buffers and one barrier per tile: while a tile is multiplied the next one is already in
@@ -248,10 +260,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     __syncthreads();
   }
   if (q >= p.S) return;
-  // rows 0..15 of the sums hold l', rows 16..31 delta' (every register of a lane: its query's column)
-  const float l = sums[0];
+  const float l = half_sum(lsum);
   const float inv = 1.f / l;
-  const float dmean = sums[8] * inv;
+  const float dmean = half_sum(dsum) * inv;
   const float f = p.scale * inv;
   uint16_t* out = (uint16_t*)p.dQ + base + (int64_t)q * p.ss;
 #pragma unroll

@@ -643,7 +643,10 @@ hipError_t launch_mfma_dq_dkdv(const KP& p, hipStream_t st) {
 }
 // head size 32 on the large-share work-group shape: the vector arithmetic per score element binds, and
 // the recompute pass and dQ share all of it
-bool mfma_fuses_recompute_dq(const KP& p) { return fast_ok(p) && p.D == 32 && wg_shape(p) == WG_4x1; }
+bool mfma_fuses_recompute_dq(const KP& p) {
+  if (!fast_ok(p) || p.D != 32 || wg_shape(p) != WG_4x1) return false;
+  return ((int64_t)(p.S - 1) * p.ss + p.D) * 2 < (1ll << 31);  // the kernel addresses a (row, head) slice with 32-bit offsets
+}
 hipError_t launch_mfma_recompute_dq(const KP& p, hipStream_t st) { return launch_fast_recompute_dq(p, st); }
 int mfma_dbias_group_rows(const KP& p) { return dbias_group_rows(p); }
 
