@@ -23,7 +23,7 @@ namespace {
 // not depend on k.
 // ---------------------------------------------------------------------------
 template <int D, bool BIAS, bool CAUSAL, bool RECOMP, int QW, int NG>
-__global__ __launch_bounds__(64 * QW * NG) __attribute__((amdgpu_waves_per_eu(D <= 32 ? (BIAS ? 3 : 4) : 2, D <= 32 ? (BIAS ? 3 : 4) : 2))) void fwd_fast_kernel(KP p) {
+__global__ __launch_bounds__(64 * QW * NG) __attribute__((amdgpu_waves_per_eu(D <= 32 ? (BIAS && (CAUSAL || NG > 1) ? 3 : 4) : 2, D <= 32 ? (BIAS && (CAUSAL || NG > 1) ? 3 : 4) : 2))) void fwd_fast_kernel(KP p) {
   constexpr int KS = D / 16, DB = D / 32, NT = 64 * QW, BM = 32 * QW;
   constexpr int LDK = D + 8, LDV = D + 16;  // row pads chosen for conflict-free b128 / transpose reads
   constexpr int CPR = D / 8, CPT = BN * CPR / NT;
