@@ -52,6 +52,10 @@ SMALL = {
     "long_seq_bias_causal_d32": dict(seed=50, B=1, H=3, S=520, D=32, dtype="bf16", bias="dense", mask="causal",
                                      axis="head"),
     "long_seq_mid_share": dict(seed=51, B=16, H=4, S=512, D=32, dtype="bf16", mask="causal", axis="row"),
+    # head size 32 with a dense bias AND the causal mask on the large-share work-group shape (S < 512):
+    # the one-walk recompute + dQ kernel and dK/dV in their bias + causal variants
+    "bias_causal_d32": dict(seed=63, B=4, H=2, S=236, D=32, dtype="bf16", bias="dense", mask="causal", gated=True,
+                            axis="row"),
     # transposed storage (attention along the first storage axis): strides alone select the variant
     "msa_col_like": dict(seed=53, B=7, H=2, S=150, D=32, dtype="bf16", gated=True, axis="row", layout="sbhd"),
     "tri_end_like": dict(seed=54, B=5, H=2, S=200, D=32, dtype="bf16", bias="dense", gated=True, axis="row",
@@ -86,7 +90,8 @@ def test_matches_oracle_for_every_k(name, flags):
         check_against_oracle(cfg, k=k, flags=flags)
 
 
-@pytest.mark.parametrize("name", ["gpt_like", "swin_like", "msa_like", "f32_all", "longer_seq_causal_d128"])
+@pytest.mark.parametrize("name", ["gpt_like", "swin_like", "msa_like", "f32_all", "longer_seq_causal_d128",
+                                  "tri_like", "bias_causal_d32"])
 def test_sub_range_and_saved_lse(name):
     cfg = SMALL[name]
     n = cfg["H"] if cfg["axis"] == "head" else cfg["B"]
@@ -97,7 +102,8 @@ def test_sub_range_and_saved_lse(name):
 @pytest.mark.parametrize("name", ["gpt_like", "swin_like", "msa_like", "tiny_mha", "bias_causal_d64",
                                   "short_dense_causal", "long_rows_many_groups", "long_seq_few_heads",
                                   "long_seq_no_mask_d128", "long_seq_bias_d64", "swin_head_axis", "tri_end_like", "dbias_two_heads",
-                                  "longer_seq_causal_d128", "longer_seq_no_mask_d128", "d128_transposed_short"])
+                                  "longer_seq_causal_d128", "longer_seq_no_mask_d128", "d128_transposed_short",
+                                  "bias_causal_d32", "msa_col_like"])
 def test_results_identical_across_k(name):
     cfg = SMALL[name]
     ref = None
@@ -115,7 +121,7 @@ def test_results_identical_across_k(name):
 
 @pytest.mark.parametrize("name", ["gpt_like", "long_seq_few_heads", "bias_causal_d64", "long_seq_bias_d64",
                                   "long_seq_bias_causal_d32", "long_seq_mid_share", "tri_like", "longer_seq_causal_d128",
-                                  "longer_seq_no_mask_d128"])
+                                  "longer_seq_no_mask_d128", "bias_causal_d32", "plain_bf16"])
 def test_rising_scores_raise_the_running_maximum(name):
     """Keys grow by powers of two along the sequence, so the row maximum jumps by far more than the
     lazy-rescale threshold several times per row: the accumulated output has to be rescaled while
@@ -136,7 +142,7 @@ def test_rising_scores_raise_the_running_maximum(name):
 
 @pytest.mark.parametrize("name", ["long_seq_few_heads", "long_seq_no_mask_d128", "long_seq_bias_d64", "gpt_like",
                                   "tri_like", "swin_like", "longer_seq_causal_d128", "longer_seq_no_mask_d128",
-                                  "d128_gated", "d128_transposed_short"])
+                                  "d128_gated", "d128_transposed_short", "bias_causal_d32", "msa_col_like"])
 def test_rows_past_the_sequence_end_are_never_used(name):
     """Ragged S: the staged tiles extend past row S-1.  Every activation is followed in memory by a
     NaN-filled batch, so anything read past the end of the last batch and used would poison the result."""
