@@ -2,8 +2,6 @@
 // per score element (head size 32: two matrix steps against ten vector instructions per element).
 #include "mfma_common.h"
 
-#include <type_traits>
-
 namespace ssa {
 namespace {
 
