@@ -56,6 +56,9 @@ SMALL = {
     # the one-walk recompute + dQ kernel and dK/dV in their bias + causal variants
     "bias_causal_d32": dict(seed=63, B=4, H=2, S=236, D=32, dtype="bf16", bias="dense", mask="causal", gated=True,
                             axis="row"),
+    # head size 32 right above one key tile (the second tile holds four keys) and exactly two tiles
+    "d32_just_over_a_tile": dict(seed=64, B=3, H=2, S=68, D=32, dtype="bf16", bias="dense", gated=True, axis="row"),
+    "d32_two_whole_tiles": dict(seed=65, B=2, H=3, S=128, D=32, dtype="bf16", mask="causal", axis="head"),
     # transposed storage (attention along the first storage axis): strides alone select the variant
     "msa_col_like": dict(seed=53, B=7, H=2, S=150, D=32, dtype="bf16", gated=True, axis="row", layout="sbhd"),
     "tri_end_like": dict(seed=54, B=5, H=2, S=200, D=32, dtype="bf16", bias="dense", gated=True, axis="row",
